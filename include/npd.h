@@ -1,0 +1,196 @@
+/*
+ * npd.h -- C ABI of libnpd, the packed knowledge-distillation loss of Near-Policy
+ * Distillation (NPD) for AMD MI355X (gfx950).
+ *
+ * NPD precomputes student-generated responses and teacher logits so that
+ * distillation runs as packed-sequence SFT (Alg. 1).  This library is the loss of
+ * Alg. 1's "Student Optimization" phase and the arithmetic of its "Delta-IFD
+ * Filtering" step, given logits that are already in device memory.
+ *
+ * Conventions for every entry point
+ *   - All array pointers are DEVICE pointers unless marked "host".  The caller owns
+ *     every buffer; the library allocates nothing, frees nothing, never synchronises
+ *     and never copies to the host.  Work is enqueued on `stream` (a hipStream_t
+ *     passed as void*; NULL is the default stream) and the call returns at once.
+ *   - An output the caller does not want is passed as NULL where the comment allows.
+ *   - The return value is an npd_status.  On any status other than NPD_OK nothing has
+ *     been enqueued and no output was touched.  Argument checks run before any HIP
+ *     call, so they work on a machine without a GPU.
+ *   - bf16 = upper 16 bits of an IEEE binary32.  Logits must be finite.
+ *   - Packed layout: the batch is flattened to T positions.  Position p is scored iff
+ *     loss_mask[p] != 0.  labels[p] is the token position p predicts (already
+ *     shifted).  Sample i owns positions [cu_seqlens[i], cu_seqlens[i+1]).
+ *   - Kernels report data errors they meet (a label or top-k index outside [0, V), a
+ *     decreasing cu_seqlens) by OR-ing NPD_DEV_* bits into *dev_status (one int32 the
+ *     caller zeroes; may be NULL) and writing NaN for the position concerned.
+ */
+#ifndef NPD_H
+#define NPD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  NPD_OK = 0,
+  NPD_ERR_NULL = 1,        /* a required pointer is NULL                                  */
+  NPD_ERR_SHAPE = 2,       /* a size, stride or count is out of range                     */
+  NPD_ERR_VALUE = 3,       /* tau <= 0 or not finite, grad_scale not finite, lo > hi ...  */
+  NPD_ERR_ALIAS = 4,       /* grad_out overlaps an input in a way the flags do not allow  */
+  NPD_ERR_UNSUPPORTED = 5, /* a combination this build does not implement                 */
+  NPD_ERR_WORKSPACE = 6,   /* workspace smaller than npd_workspace_bytes() says           */
+  NPD_ERR_HIP = 7          /* the HIP runtime refused the launch (hipGetLastError kept)   */
+} npd_status;
+
+/* what the teacher arguments hold */
+enum {
+  NPD_TEACHER_DENSE_BF16 = 0, /* full-vocabulary bf16 logits [T, teacher_stride]                  */
+  NPD_TEACHER_TOPK = 1,       /* per position k vocabulary ids + k fp32 values (logits or log p)  */
+  NPD_TEACHER_NONE = 2        /* no teacher: only nll_tok / lse_tok are produced (scoring pass)   */
+};
+
+/* npd_kd_desc.flags */
+enum {
+  NPD_FLAG_FWD_ONLY = 1u,      /* no gradient: grad_out must be NULL                               */
+  NPD_FLAG_INPLACE_GRAD = 2u   /* grad_out == student_logits: each row is overwritten by its gradient */
+};
+
+/* bits OR-ed into *dev_status by kernels */
+enum {
+  NPD_DEV_BAD_LABEL = 1,      /* labels[p] outside [0, V) at a scored position        */
+  NPD_DEV_BAD_TOPK_INDEX = 2, /* teacher_idx outside [0, V) at a scored position      */
+  NPD_DEV_BAD_CU_SEQLENS = 4  /* cu_seqlens decreasing or outside [0, T]              */
+};
+
+/* zone codes written by npd_delta_ifd_score (Sec. 3.2, "Differential Difficulty") */
+enum {
+  NPD_ZONE_DEGENERATE = 0, /* Delta < lo                                     */
+  NPD_ZONE_PROXIMAL = 1,   /* lo <= Delta <= hi : the samples that are kept  */
+  NPD_ZONE_DISCONNECT = 2, /* Delta > hi                                     */
+  NPD_ZONE_INVALID = 3     /* empty sample, zero denominator or non-finite   */
+};
+
+/* npd_delta_ifd_score flags */
+enum { NPD_IFD_REQUIRE_TEACHER_LE_1 = 1u };
+
+typedef struct {
+  int64_t n_tokens;       /* T > 0: flattened positions of the packed batch                        */
+  int32_t vocab;          /* V > 0                                                                 */
+  int32_t teacher_kind;   /* NPD_TEACHER_*                                                         */
+  int64_t student_stride; /* elements between consecutive rows of student_logits (>= V); grad_out
+                             uses the same stride                                                  */
+  int64_t teacher_stride; /* dense: elements between rows (>= V); top-k / none: ignored            */
+  int32_t topk;           /* k in [1, V] for NPD_TEACHER_TOPK, else ignored                        */
+  uint32_t flags;         /* NPD_FLAG_*                                                            */
+  float tau;              /* KD temperature, finite, > 0; divides student and teacher logits alike */
+  float grad_scale;       /* finite; multiplies every gradient element (the caller folds the loss
+                             weight lambda of Eq. 1, a tau^2 factor or 1/N_tokens in here)         */
+} npd_kd_desc;
+
+/* Library version (major * 100 + minor). */
+int npd_version(void);
+
+/* Static, never NULL. */
+const char* npd_status_string(npd_status st);
+
+/*
+ * Bytes of device workspace npd_kd_loss_fwd_bwd needs for `desc` (host call; 0 is a
+ * legal answer and then `workspace` may be NULL).  Returns 0 for an invalid desc.
+ */
+size_t npd_workspace_bytes(const npd_kd_desc* desc);
+
+/*
+ * The fused KD loss of one packed batch: for every scored position p (Alg. 1,
+ * "Compute Probs" / "Compute KD Loss"; Eq. 2; L_CE of Eq. 1):
+ *
+ *   p_S = Softmax(student[p, :] / tau)                 over the full vocabulary
+ *   p_T = Softmax(teacher[p, :] / tau)                 dense: over the full vocabulary
+ *                                                      top-k: over the k stored entries only
+ *   kd_tok[p]  = sum_{c in support} p_T(c) * log(p_T(c) / p_S(c))        (Eq. 2; support = V or top-k)
+ *   grad[p, c] = grad_scale / tau * (p_S(c) - p_T(c) * [c in support])   (d kd_tok / d student logit)
+ *   nll_tok[p]         = logsumexp(student[p, :]) - student[p, labels[p]]   (tau = 1 always)
+ *   teacher_nll_tok[p] = logsumexp(teacher[p, :]) - teacher[p, labels[p]]   (dense teacher only)
+ *   lse_tok[p]         = logsumexp(student[p, :])                           (tau = 1)
+ *
+ * At positions with loss_mask[p] == 0 the scalar outputs are 0 and the gradient row is
+ * zero-filled (its logits are not read).  No tau^2 factor is applied.
+ *
+ *   student_logits   bf16 [T, student_stride], required
+ *   teacher_dense    bf16 [T, teacher_stride]; required iff teacher_kind == DENSE, else NULL
+ *   teacher_idx      int32 [T, k], unique per row, in [0, V); required iff TOPK, else NULL
+ *   teacher_val      fp32 [T, k] logits or log-probabilities at tau = 1 (a per-row additive
+ *                    constant changes nothing); required iff TOPK, else NULL
+ *   labels           int32 [T]; required iff nll_tok or teacher_nll_tok is given
+ *   loss_mask        uint8 [T], required
+ *   grad_out         bf16 [T, student_stride]; NULL iff NPD_FLAG_FWD_ONLY or teacher NONE; may equal
+ *                    student_logits iff NPD_FLAG_INPLACE_GRAD (then the student logits are
+ *                    destroyed); any other overlap with an input is NPD_ERR_ALIAS
+ *   kd_tok           fp32 [T] or NULL (must be NULL for teacher NONE)
+ *   nll_tok          fp32 [T] or NULL
+ *   teacher_nll_tok  fp32 [T] or NULL (dense teacher only)
+ *   lse_tok          fp32 [T] or NULL
+ *   dev_status       int32 [1] or NULL
+ *   workspace        device, >= npd_workspace_bytes(desc) bytes, 256-byte aligned (NULL if 0)
+ *
+ * Each gradient element is rounded to bf16 once (round to nearest even) from an fp32
+ * value; all sums are accumulated in fp32.  Results are bitwise reproducible from run
+ * to run (no floating-point atomics).
+ */
+npd_status npd_kd_loss_fwd_bwd(const npd_kd_desc* desc, const void* student_logits, const void* teacher_dense,
+                               const int32_t* teacher_idx, const float* teacher_val, const int32_t* labels,
+                               const uint8_t* loss_mask, void* grad_out, float* kd_tok, float* nll_tok,
+                               float* teacher_nll_tok, float* lse_tok, int32_t* dev_status, void* workspace,
+                               size_t workspace_bytes, void* stream);
+
+/*
+ * Per-sample reduction of a per-position quantity over the packed layout (the
+ * per-sample losses behind Eq. 1-3): for sample i in [0, S)
+ *
+ *   seg_count[i] = #{p in [cu[i], cu[i+1]) : loss_mask[p] != 0}
+ *   seg_sum[i]   = sum of values[p] over those p     (fixed summation order: reproducible)
+ *   seg_mean[i]  = seg_sum[i] / seg_count[i], or 0 when seg_count[i] == 0
+ *   token_to_sample[p] = i for p in [cu[i], cu[i+1]), -1 for positions no sample owns
+ *
+ *   values fp32 [T], loss_mask uint8 [T], cu_seqlens int32 [S+1] (non-decreasing, inside [0, T]);
+ *   seg_sum fp32 [S] / seg_count int32 [S] / seg_mean fp32 [S] / token_to_sample int32 [T]: each may
+ *   be NULL.  n_tokens >= 0, n_segments >= 0 (0 is a no-op apart from token_to_sample = -1).
+ *   A segment whose bounds are decreasing or outside [0, T] sets NPD_DEV_BAD_CU_SEQLENS, gets
+ *   count 0 / sum NaN / mean NaN and owns no position.
+ */
+npd_status npd_segment_reduce(int64_t n_tokens, int32_t n_segments, const float* values, const uint8_t* loss_mask,
+                              const int32_t* cu_seqlens, float* seg_sum, int32_t* seg_count, float* seg_mean,
+                              int32_t* token_to_sample, int32_t* dev_status, void* stream);
+
+/*
+ * Delta-IFD selection score (Sec. 3.2): pair j names two packed samples, pair_cond[j]
+ * = instruction + response (its mean response loss is L(A|Q)) and pair_uncond[j] = the
+ * response alone (L(A)).  With the per-sample mean CE losses of student and teacher:
+ *
+ *   IFD_M   = mean_nll_M[pair_cond] / mean_nll_M[pair_uncond],  M in {student, teacher}   (Eq. 3)
+ *   delta   = IFD_teacher - IFD_student                                                    (Eq. 4)
+ *   zone    = DEGENERATE (delta < lo) | PROXIMAL (lo <= delta <= hi) | DISCONNECT (delta > hi)
+ *             (the paper's lo is 0, hi its threshold tau, e.g. 0.8 or 1.0) | INVALID
+ *   keep    = zone == PROXIMAL  [and IFD_teacher <= 1 if NPD_IFD_REQUIRE_TEACHER_LE_1]
+ *   keep_count[0] = number of kept pairs (written, not accumulated)
+ *
+ * INVALID: a sample of the pair has seg_count == 0, a denominator is 0, or a value is
+ * not finite; ifd_* and delta are then NaN and keep = 0.  All arithmetic in fp32.
+ *
+ *   mean_nll_student, mean_nll_teacher fp32 [S]; seg_count int32 [S]; pair_cond, pair_uncond
+ *   int32 [P], entries in [0, S) (an entry outside marks the pair INVALID);
+ *   ifd_student, ifd_teacher, delta fp32 [P], zone, keep uint8 [P], keep_count int32 [1]:
+ *   each output may be NULL.  n_pairs >= 0; lo <= hi, both finite.
+ */
+npd_status npd_delta_ifd_score(int32_t n_pairs, int32_t n_segments, const float* mean_nll_student,
+                               const float* mean_nll_teacher, const int32_t* seg_count, const int32_t* pair_cond,
+                               const int32_t* pair_uncond, float lo, float hi, uint32_t flags, float* ifd_student,
+                               float* ifd_teacher, float* delta, uint8_t* zone, uint8_t* keep, int32_t* keep_count,
+                               void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NPD_H */

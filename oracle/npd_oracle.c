@@ -1,0 +1,426 @@
+/*
+ * npd_oracle.c -- float64 CPU oracle for the packed knowledge-distillation loss of
+ * Near-Policy Distillation (NPD).
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is a slow, plain statement of what the GPU
+ * library must compute and shares no code with it.  Only the tests, the smoke
+ * check and the benchmark's CPU-baseline leg may call it; the product path never
+ * does.
+ *
+ * Everything here is the textbook definition written out in double precision:
+ *   - student distribution   p_S = Softmax(O_S / tau)           (Alg. 1, "Compute Probs")
+ *   - teacher distribution   p_T = Softmax(O_T / tau)           (Alg. 1, "Compute Probs";
+ *                            with a top-k record the softmax runs over the k stored
+ *                            entries only, Sec. 3.1 "Teacher Logits via Packed
+ *                            Parallel Prefill")
+ *   - KD loss per position   sum_{c in support} p_T(c) log(p_T(c)/p_S(c))   (Eq. 2)
+ *   - CE loss per position   -log Softmax(O)[label]             (L_CE of Eq. 1; the
+ *                            sequence loss L_theta of Eq. 3)
+ *   - gradient of Eq. 2 with respect to the student logits (implied by the
+ *     parameter update of Alg. 1): (1/tau) * (p_S(c) - p_T(c) [c in support])
+ *     (p_T sums to 1 over its support, by construction of the softmax)
+ *   - per-sample reduction over cu_seqlens under the response mask
+ *   - IFD (Eq. 3), Delta-IFD (Eq. 4) and the three curation zones of Sec. 3.2
+ *
+ * The temperature tau divides student and teacher logits alike; tau = 1 is Eq. 2
+ * exactly.  No tau^2 factor is applied (a caller folds it into grad_scale).
+ *
+ * No blocking, no fusion, no online tricks: two-pass log-sum-exp (maximum first,
+ * then the sum), sums in index order.
+ *
+ * Parity pins: every function below is pinned by tests/test_oracle_pins.py against
+ * closed forms, library routines in float64, finite differences and brute force.
+ * What no pin can reach is convention rather than arithmetic (no tau^2, top-k
+ * renormalisation, mean rather than sum in Eq. 3): the paper prints no worked
+ * example, so those readings are "parity unpinned" beyond self-consistency.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* zone codes of Sec. 3.2 */
+enum { ZONE_DEGENERATE = 0, ZONE_PROXIMAL = 1, ZONE_DISCONNECT = 2, ZONE_INVALID = 3 };
+
+int npd_oracle_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+/* bf16 is the upper half of an IEEE binary32: the conversion to double is exact. */
+static double bf16_to_double(uint16_t h) {
+  uint32_t u = ((uint32_t)h) << 16;
+  float f;
+  memcpy(&f, &u, sizeof f);
+  return (double)f;
+}
+
+/* log sum_i exp(a_i), two passes. */
+static double logsumexp(const double *a, int64_t n) {
+  double mx = -INFINITY;
+  for (int64_t i = 0; i < n; ++i)
+    if (a[i] > mx) mx = a[i];
+  if (isinf(mx) && mx < 0) return -INFINITY; /* all -inf: empty distribution */
+  double z = 0.0;
+  for (int64_t i = 0; i < n; ++i) z += exp(a[i] - mx);
+  return mx + log(z);
+}
+
+/* CE loss of one position: logsumexp(o) - o[label]  (natural log, no temperature). */
+static double row_nll(const double *o, int64_t V, int32_t label) {
+  if (label < 0 || label >= V) return NAN;
+  return logsumexp(o, V) - o[label];
+}
+
+/*
+ * One position, dense teacher.  s, t: V logits each.  Outputs (any may be NULL):
+ * kd = Eq. 2 over the full vocabulary, grad[V] = grad_scale * d kd / d s.
+ * a, b are caller-provided work rows of V doubles.
+ */
+static void row_kd_dense(const double *s, const double *t, int64_t V, double tau, double grad_scale,
+                         double *a, double *b, double *kd, double *grad) {
+  for (int64_t c = 0; c < V; ++c) a[c] = s[c] / tau;
+  for (int64_t c = 0; c < V; ++c) b[c] = t[c] / tau;
+  const double lse_a = logsumexp(a, V);
+  const double lse_b = logsumexp(b, V);
+  double acc = 0.0;
+  for (int64_t c = 0; c < V; ++c) {
+    const double logp_t = b[c] - lse_b;
+    const double logp_s = a[c] - lse_a;
+    const double p_t = exp(logp_t);
+    if (p_t > 0.0) acc += p_t * (logp_t - logp_s);
+  }
+  if (kd) *kd = acc;
+  if (grad) {
+    for (int64_t c = 0; c < V; ++c) {
+      const double p_s = exp(a[c] - lse_a);
+      const double p_t = exp(b[c] - lse_b);
+      grad[c] = grad_scale * (1.0 / tau) * (p_s - p_t);
+    }
+  }
+}
+
+/*
+ * One position, top-k teacher record: idx[k] vocabulary ids (unique), val[k] the
+ * stored teacher values (logits or log-probabilities: the softmax below is shift
+ * invariant).  p_T is the softmax of val/tau over the k entries; p_S is the
+ * full-vocabulary softmax of s/tau.  Returns 0, or 1 if an index is out of range
+ * (outputs are then NaN).
+ */
+static int row_kd_topk(const double *s, int64_t V, const int32_t *idx, const double *val, int32_t k,
+                       double tau, double grad_scale, double *a, double *b, double *kd, double *grad) {
+  for (int32_t j = 0; j < k; ++j) {
+    if (idx[j] < 0 || idx[j] >= V) {
+      if (kd) *kd = NAN;
+      if (grad)
+        for (int64_t c = 0; c < V; ++c) grad[c] = NAN;
+      return 1;
+    }
+  }
+  for (int64_t c = 0; c < V; ++c) a[c] = s[c] / tau;
+  for (int32_t j = 0; j < k; ++j) b[j] = val[j] / tau;
+  const double lse_a = logsumexp(a, V);
+  const double lse_b = logsumexp(b, k);
+  double acc = 0.0;
+  for (int32_t j = 0; j < k; ++j) {
+    const double logp_t = b[j] - lse_b;
+    const double logp_s = a[idx[j]] - lse_a;
+    const double p_t = exp(logp_t);
+    if (p_t > 0.0) acc += p_t * (logp_t - logp_s);
+  }
+  if (kd) *kd = acc;
+  if (grad) {
+    for (int64_t c = 0; c < V; ++c) grad[c] = grad_scale * (1.0 / tau) * exp(a[c] - lse_a);
+    for (int32_t j = 0; j < k; ++j)
+      grad[idx[j]] -= grad_scale * (1.0 / tau) * exp(b[j] - lse_b);
+  }
+  return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Entry points on double logits (used by the pin tests).                     */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * Dense-teacher KD over T positions.  s, t: [T, V] doubles, row-major, contiguous.
+ * labels may be NULL (then nll_s / nll_t must be NULL); mask is required.
+ * Masked positions give kd = nll = 0 and a zero gradient row.
+ * Outputs (each may be NULL): kd[T], nll_s[T], nll_t[T], lse_s[T] (log-sum-exp of the
+ * raw student logits, tau = 1), grad[T, V].
+ */
+void npd_oracle_kd_dense_f64(int64_t T, int64_t V, const double *s, const double *t, const int32_t *labels,
+                             const uint8_t *mask, double tau, double grad_scale, double *kd, double *nll_s,
+                             double *nll_t, double *lse_s, double *grad) {
+#pragma omp parallel
+  {
+    double *a = (double *)malloc(sizeof(double) * (size_t)V);
+    double *b = (double *)malloc(sizeof(double) * (size_t)V);
+#pragma omp for schedule(dynamic, 1)
+    for (int64_t r = 0; r < T; ++r) {
+      double *g = grad ? grad + r * V : NULL;
+      if (!mask[r]) {
+        if (kd) kd[r] = 0.0;
+        if (nll_s) nll_s[r] = 0.0;
+        if (nll_t) nll_t[r] = 0.0;
+        if (lse_s) lse_s[r] = 0.0;
+        if (g)
+          for (int64_t c = 0; c < V; ++c) g[c] = 0.0;
+        continue;
+      }
+      const double *sr = s + r * V, *tr = t + r * V;
+      row_kd_dense(sr, tr, V, tau, grad_scale, a, b, kd ? kd + r : NULL, g);
+      if (nll_s) nll_s[r] = row_nll(sr, V, labels[r]);
+      if (nll_t) nll_t[r] = row_nll(tr, V, labels[r]);
+      if (lse_s) lse_s[r] = logsumexp(sr, V);
+    }
+    free(a);
+    free(b);
+  }
+}
+
+/*
+ * Top-k-teacher KD over T positions.  s: [T, V]; idx: [T, k]; val: [T, k].
+ * Returns the number of unmasked positions that held an out-of-range index.
+ */
+int64_t npd_oracle_kd_topk_f64(int64_t T, int64_t V, int32_t k, const double *s, const int32_t *idx,
+                               const double *val, const int32_t *labels, const uint8_t *mask, double tau,
+                               double grad_scale, double *kd, double *nll_s, double *lse_s, double *grad) {
+  int64_t bad = 0;
+#pragma omp parallel reduction(+ : bad)
+  {
+    double *a = (double *)malloc(sizeof(double) * (size_t)V);
+    double *b = (double *)malloc(sizeof(double) * (size_t)(k > 0 ? k : 1));
+#pragma omp for schedule(dynamic, 1)
+    for (int64_t r = 0; r < T; ++r) {
+      double *g = grad ? grad + r * V : NULL;
+      if (!mask[r]) {
+        if (kd) kd[r] = 0.0;
+        if (nll_s) nll_s[r] = 0.0;
+        if (lse_s) lse_s[r] = 0.0;
+        if (g)
+          for (int64_t c = 0; c < V; ++c) g[c] = 0.0;
+        continue;
+      }
+      const double *sr = s + r * V;
+      bad += row_kd_topk(sr, V, idx + r * (int64_t)k, val + r * (int64_t)k, k, tau, grad_scale, a, b,
+                         kd ? kd + r : NULL, g);
+      if (nll_s) nll_s[r] = row_nll(sr, V, labels[r]);
+      if (lse_s) lse_s[r] = logsumexp(sr, V);
+    }
+    free(a);
+    free(b);
+  }
+  return bad;
+}
+
+/* Forward-only CE loss per position of any logits o[T, V] (tau = 1). */
+void npd_oracle_nll_f64(int64_t T, int64_t V, const double *o, const int32_t *labels, const uint8_t *mask,
+                        double *nll, double *lse) {
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t r = 0; r < T; ++r) {
+    if (!mask[r]) {
+      if (nll) nll[r] = 0.0;
+      if (lse) lse[r] = 0.0;
+      continue;
+    }
+    if (nll) nll[r] = row_nll(o + r * V, V, labels[r]);
+    if (lse) lse[r] = logsumexp(o + r * V, V);
+  }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Entry points on bf16 logits (what the GPU library is compared against).   */
+/* Each row is converted exactly to double and handed to the same row code.  */
+/* Strides are in elements.  grad is [T, V] doubles, contiguous.             */
+/* ------------------------------------------------------------------------- */
+
+void npd_oracle_kd_dense_bf16(int64_t T, int64_t V, const uint16_t *s, int64_t s_stride, const uint16_t *t,
+                              int64_t t_stride, const int32_t *labels, const uint8_t *mask, double tau,
+                              double grad_scale, double *kd, double *nll_s, double *nll_t, double *lse_s,
+                              double *grad) {
+#pragma omp parallel
+  {
+    double *sr = (double *)malloc(sizeof(double) * (size_t)V);
+    double *tr = (double *)malloc(sizeof(double) * (size_t)V);
+    double *a = (double *)malloc(sizeof(double) * (size_t)V);
+    double *b = (double *)malloc(sizeof(double) * (size_t)V);
+#pragma omp for schedule(dynamic, 1)
+    for (int64_t r = 0; r < T; ++r) {
+      double *g = grad ? grad + r * V : NULL;
+      if (!mask[r]) {
+        if (kd) kd[r] = 0.0;
+        if (nll_s) nll_s[r] = 0.0;
+        if (nll_t) nll_t[r] = 0.0;
+        if (lse_s) lse_s[r] = 0.0;
+        if (g)
+          for (int64_t c = 0; c < V; ++c) g[c] = 0.0;
+        continue;
+      }
+      for (int64_t c = 0; c < V; ++c) sr[c] = bf16_to_double(s[r * s_stride + c]);
+      for (int64_t c = 0; c < V; ++c) tr[c] = bf16_to_double(t[r * t_stride + c]);
+      row_kd_dense(sr, tr, V, tau, grad_scale, a, b, kd ? kd + r : NULL, g);
+      if (nll_s) nll_s[r] = row_nll(sr, V, labels[r]);
+      if (nll_t) nll_t[r] = row_nll(tr, V, labels[r]);
+      if (lse_s) lse_s[r] = logsumexp(sr, V);
+    }
+    free(sr);
+    free(tr);
+    free(a);
+    free(b);
+  }
+}
+
+int64_t npd_oracle_kd_topk_bf16(int64_t T, int64_t V, int32_t k, const uint16_t *s, int64_t s_stride,
+                                const int32_t *idx, const float *val, const int32_t *labels,
+                                const uint8_t *mask, double tau, double grad_scale, double *kd, double *nll_s,
+                                double *lse_s, double *grad) {
+  int64_t bad = 0;
+#pragma omp parallel reduction(+ : bad)
+  {
+    double *sr = (double *)malloc(sizeof(double) * (size_t)V);
+    double *a = (double *)malloc(sizeof(double) * (size_t)V);
+    double *b = (double *)malloc(sizeof(double) * (size_t)(k > 0 ? k : 1));
+    double *vr = (double *)malloc(sizeof(double) * (size_t)(k > 0 ? k : 1));
+#pragma omp for schedule(dynamic, 1)
+    for (int64_t r = 0; r < T; ++r) {
+      double *g = grad ? grad + r * V : NULL;
+      if (!mask[r]) {
+        if (kd) kd[r] = 0.0;
+        if (nll_s) nll_s[r] = 0.0;
+        if (lse_s) lse_s[r] = 0.0;
+        if (g)
+          for (int64_t c = 0; c < V; ++c) g[c] = 0.0;
+        continue;
+      }
+      for (int64_t c = 0; c < V; ++c) sr[c] = bf16_to_double(s[r * s_stride + c]);
+      for (int32_t j = 0; j < k; ++j) vr[j] = (double)val[r * (int64_t)k + j];
+      bad += row_kd_topk(sr, V, idx + r * (int64_t)k, vr, k, tau, grad_scale, a, b, kd ? kd + r : NULL, g);
+      if (nll_s) nll_s[r] = row_nll(sr, V, labels[r]);
+      if (lse_s) lse_s[r] = logsumexp(sr, V);
+    }
+    free(sr);
+    free(a);
+    free(b);
+    free(vr);
+  }
+  return bad;
+}
+
+void npd_oracle_nll_bf16(int64_t T, int64_t V, const uint16_t *o, int64_t o_stride, const int32_t *labels,
+                         const uint8_t *mask, double *nll, double *lse) {
+#pragma omp parallel
+  {
+    double *row = (double *)malloc(sizeof(double) * (size_t)V);
+#pragma omp for schedule(dynamic, 1)
+    for (int64_t r = 0; r < T; ++r) {
+      if (!mask[r]) {
+        if (nll) nll[r] = 0.0;
+        if (lse) lse[r] = 0.0;
+        continue;
+      }
+      for (int64_t c = 0; c < V; ++c) row[c] = bf16_to_double(o[r * o_stride + c]);
+      if (nll) nll[r] = row_nll(row, V, labels[r]);
+      if (lse) lse[r] = logsumexp(row, V);
+    }
+    free(row);
+  }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Per-sample reduction over the packed layout.                               */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * Sample i owns the flattened positions [cu[i], cu[i+1]).  For each sample:
+ * sum of x over its unmasked positions (index order), their count, and the mean
+ * (0 when the count is 0).  token_to_sample (may be NULL) receives the owning
+ * sample of every position, -1 for positions outside [cu[0], cu[S]).
+ * Returns 0, or 1 if cu is decreasing somewhere or leaves [0, T].
+ */
+int npd_oracle_segment_reduce(int64_t T, int32_t S, const double *x, const uint8_t *mask, const int32_t *cu,
+                              double *seg_sum, int32_t *seg_count, double *seg_mean,
+                              int32_t *token_to_sample) {
+  for (int32_t i = 0; i < S; ++i)
+    if (cu[i] > cu[i + 1]) return 1;
+  if (S > 0 && (cu[0] < 0 || cu[S] > T)) return 1;
+  if (token_to_sample)
+    for (int64_t p = 0; p < T; ++p) token_to_sample[p] = -1;
+  for (int32_t i = 0; i < S; ++i) {
+    double acc = 0.0;
+    int32_t n = 0;
+    for (int64_t p = cu[i]; p < cu[i + 1]; ++p) {
+      if (token_to_sample) token_to_sample[p] = i;
+      if (mask[p]) {
+        acc += x[p];
+        n += 1;
+      }
+    }
+    if (seg_sum) seg_sum[i] = acc;
+    if (seg_count) seg_count[i] = n;
+    if (seg_mean) seg_mean[i] = n > 0 ? acc / (double)n : 0.0;
+  }
+  return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* IFD, Delta-IFD and zones.                                                  */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * Pair p names two packed samples: pair_cond[p] holds instruction + response (its
+ * mean response loss is L(A|Q)), pair_uncond[p] holds the response alone (L(A)).
+ *   IFD_M   = L_M(A|Q) / L_M(A)                  for M in {student, teacher}   (Eq. 3)
+ *   Delta   = IFD_teacher - IFD_student                                         (Eq. 4)
+ *   zone    = DEGENERATE if Delta < lo, DISCONNECT if Delta > hi, else PROXIMAL (Sec. 3.2;
+ *             the paper's lo is 0 and hi its threshold tau); the comparison is made on
+ *             Delta rounded to binary32, the precision the zone decision is specified in.
+ *   INVALID when either sample has no scored position, a denominator is 0, or
+ *             anything is non-finite; IFD and Delta are then NaN.
+ *   keep    = zone is PROXIMAL (and, if flag bit 0 is set, IFD_teacher <= 1, the extra
+ *             condition named in the description of the proximal zone).
+ * Returns the number of kept pairs.
+ */
+int32_t npd_oracle_delta_ifd(int32_t P, const double *mean_nll_student, const double *mean_nll_teacher,
+                             const int32_t *seg_count, const int32_t *pair_cond, const int32_t *pair_uncond,
+                             double lo, double hi, uint32_t flags, double *ifd_student, double *ifd_teacher,
+                             double *delta, uint8_t *zone, uint8_t *keep) {
+  int32_t kept = 0;
+  for (int32_t p = 0; p < P; ++p) {
+    const int32_t ic = pair_cond[p], iu = pair_uncond[p];
+    double is = NAN, it = NAN, d = NAN;
+    uint8_t z = ZONE_INVALID, kp = 0;
+    const int ok_counts = seg_count[ic] > 0 && seg_count[iu] > 0;
+    if (ok_counts && mean_nll_student[iu] != 0.0 && mean_nll_teacher[iu] != 0.0) {
+      is = mean_nll_student[ic] / mean_nll_student[iu];
+      it = mean_nll_teacher[ic] / mean_nll_teacher[iu];
+      d = it - is;
+    }
+    if (isfinite(is) && isfinite(it) && isfinite(d)) {
+      const float d32 = (float)d;
+      if (d32 < (float)lo)
+        z = ZONE_DEGENERATE;
+      else if (d32 > (float)hi)
+        z = ZONE_DISCONNECT;
+      else
+        z = ZONE_PROXIMAL;
+      kp = (z == ZONE_PROXIMAL);
+      if ((flags & 1u) && !((float)it <= 1.0f)) kp = 0;
+    } else {
+      is = it = d = NAN;
+    }
+    if (ifd_student) ifd_student[p] = is;
+    if (ifd_teacher) ifd_teacher[p] = it;
+    if (delta) delta[p] = d;
+    if (zone) zone[p] = z;
+    if (keep) keep[p] = kp;
+    kept += kp;
+  }
+  return kept;
+}

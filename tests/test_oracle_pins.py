@@ -1,0 +1,404 @@
+"""Pins for the float64 oracle: each check ties it to something other than itself --
+closed forms, float64 library routines, finite differences, brute force, hand-worked cases.
+No GPU is needed (run with -m "not gpu")."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+RNG = np.random.default_rng(1234)
+
+
+def _rand(T, V, scale=2.0, rng=RNG):
+    return rng.normal(0.0, scale, size=(T, V))
+
+
+# --------------------------------------------------------------------------- log-sum-exp / NLL
+
+def test_lse_uniform_row_is_logit_plus_ln_V(oracle):
+    for V in (1024, 151936, 262144):
+        s = np.full((1, V), 0.75)
+        out = oracle.nll(s, labels=np.array([V - 1]))
+        assert out["lse"][0] == pytest.approx(0.75 + math.log(V), rel=0, abs=1e-12)
+        assert out["nll"][0] == pytest.approx(math.log(V), rel=0, abs=1e-12)
+    # the three printed constants
+    assert math.log(151936) == pytest.approx(11.931214658, abs=1e-8)
+
+
+def test_lse_shift_invariance_and_library(oracle):
+    s = _rand(7, 333, 5.0)
+    lab = RNG.integers(0, 333, 7)
+    a = oracle.nll(s, lab)
+    b = oracle.nll(s + 123.5, lab)
+    np.testing.assert_allclose(a["nll"], b["nll"], atol=1e-11)
+    np.testing.assert_allclose(a["lse"] + 123.5, b["lse"], atol=1e-11)
+    ts = torch.from_numpy(s)
+    np.testing.assert_allclose(a["lse"], torch.logsumexp(ts, 1).numpy(), atol=1e-12)
+    np.testing.assert_allclose(a["nll"], F.cross_entropy(ts, torch.from_numpy(lab), reduction="none").numpy(),
+                               atol=1e-12)
+
+
+def test_lse_survives_huge_logits(oracle):
+    s = np.array([[5000.0, 4999.0, -5000.0]])
+    out = oracle.nll(s, np.array([1]))
+    assert out["lse"][0] == pytest.approx(5000.0 + math.log1p(math.exp(-1.0)), abs=1e-9)
+    assert out["nll"][0] == pytest.approx(1.0 + math.log1p(math.exp(-1.0)), abs=1e-9)
+
+
+def test_nll_uses_label_and_tau_free(oracle):
+    # NLL is the tau = 1 cross-entropy whatever the KD temperature
+    s, t = _rand(5, 50), _rand(5, 50)
+    lab = RNG.integers(0, 50, 5)
+    o1 = oracle.kd_dense(s, t, lab, tau=1.0)
+    o2 = oracle.kd_dense(s, t, lab, tau=3.0)
+    np.testing.assert_array_equal(o1["nll_s"], o2["nll_s"])
+    np.testing.assert_array_equal(o1["nll_t"], o2["nll_t"])
+    ref_s = -torch.log_softmax(torch.from_numpy(s), 1)[torch.arange(5), torch.from_numpy(lab)]
+    ref_t = -torch.log_softmax(torch.from_numpy(t), 1)[torch.arange(5), torch.from_numpy(lab)]
+    np.testing.assert_allclose(o1["nll_s"], ref_s.numpy(), atol=1e-12)
+    np.testing.assert_allclose(o1["nll_t"], ref_t.numpy(), atol=1e-12)
+    np.testing.assert_allclose(o1["lse_s"], torch.logsumexp(torch.from_numpy(s), 1).numpy(), atol=1e-12)
+
+
+def test_nll_bad_label_is_nan(oracle):
+    s = _rand(2, 10)
+    out = oracle.nll(s, np.array([10, -1]))
+    assert np.isnan(out["nll"]).all()
+
+
+# --------------------------------------------------------------------------- dense KL (Eq. 2 with support = V)
+
+def test_kl_nonnegative_and_zero_iff_equal(oracle):
+    s, t = _rand(64, 257, 3.0), _rand(64, 257, 3.0)
+    for tau in (1.0, 2.0, 0.5):
+        out = oracle.kd_dense(s, t, tau=tau)
+        assert (out["kd"] > 0).all()
+        same = oracle.kd_dense(s, s.copy(), tau=tau)
+        assert (same["kd"] == 0.0).all()          # exactly zero
+        assert (same["grad"] == 0.0).all()
+
+
+def test_kl_two_level_closed_form(oracle):
+    # student logits (beta, 0, ..., 0), teacher (alpha, 0, ..., 0): KL collapses to a binary KL
+    V, alpha, beta = 1000, 3.0, 1.0
+    s = np.zeros((1, V)); s[0, 0] = beta
+    t = np.zeros((1, V)); t[0, 0] = alpha
+    pt = math.exp(alpha) / (math.exp(alpha) + V - 1)
+    ps = math.exp(beta) / (math.exp(beta) + V - 1)
+    want = pt * math.log(pt / ps) + (1 - pt) * math.log((1 - pt) / (1 - ps))
+    got = oracle.kd_dense(s, t)["kd"][0]
+    assert got == pytest.approx(want, rel=1e-12)
+    # the direction is KL(teacher || student): swapping the roles gives the other binary KL
+    want_rev = ps * math.log(ps / pt) + (1 - ps) * math.log((1 - ps) / (1 - pt))
+    assert oracle.kd_dense(t, s)["kd"][0] == pytest.approx(want_rev, rel=1e-12)
+    assert abs(want - want_rev) > 1e-3
+
+
+def test_kl_temperature_identity_and_no_tau_squared(oracle):
+    s, t = _rand(9, 120, 4.0), _rand(9, 120, 4.0)
+    tau = 2.5
+    a = oracle.kd_dense(s, t, tau=tau)
+    b = oracle.kd_dense(s / tau, t / tau, tau=1.0)
+    np.testing.assert_allclose(a["kd"], b["kd"], rtol=1e-12)
+    # d/ds at temperature tau = (1/tau) * d/d(s/tau) at temperature 1
+    np.testing.assert_allclose(a["grad"], b["grad"] / tau, rtol=1e-10, atol=1e-15)
+
+
+def test_kl_matches_library_kl_div(oracle):
+    s, t = _rand(11, 77, 3.0), _rand(11, 77, 3.0)
+    for tau in (1.0, 2.0):
+        ls = torch.log_softmax(torch.from_numpy(s) / tau, 1)
+        lt = torch.log_softmax(torch.from_numpy(t) / tau, 1)
+        ref = F.kl_div(ls, lt, reduction="none", log_target=True).sum(1)
+        np.testing.assert_allclose(oracle.kd_dense(s, t, tau=tau)["kd"], ref.numpy(), rtol=1e-11)
+
+
+# --------------------------------------------------------------------------- top-k KL (Eq. 2)
+
+def test_topk_uniform_closed_form(oracle):
+    # uniform student, k equal teacher entries: KL = ln(V / k)
+    for V, k in ((151936, 64), (1024, 10)):
+        s = np.zeros((1, V))
+        idx = (np.arange(k, dtype=np.int32) * 7 + 3).reshape(1, k)
+        val = np.full((1, k), -2.0)
+        out = oracle.kd_topk(s, idx, val, want_grad=False)
+        assert out["kd"][0] == pytest.approx(math.log(V / k), rel=1e-12)
+    assert math.log(151936 / 64) == pytest.approx(7.772331575, abs=1e-8)
+
+
+def test_topk_with_k_equal_V_is_dense(oracle):
+    V = 40
+    s, t = _rand(6, V), _rand(6, V)
+    idx = np.tile(np.arange(V, dtype=np.int32), (6, 1))
+    for tau in (1.0, 2.0):
+        d = oracle.kd_dense(s, t, tau=tau, grad_scale=0.7)
+        k = oracle.kd_topk(s, idx, t, tau=tau, grad_scale=0.7)
+        np.testing.assert_allclose(k["kd"], d["kd"], rtol=1e-12)
+        np.testing.assert_allclose(k["grad"], d["grad"], rtol=1e-10, atol=1e-15)
+
+
+def test_topk_permutation_and_shift_invariance(oracle):
+    T, V, k = 5, 300, 16
+    s = _rand(T, V, 3.0)
+    idx = np.stack([RNG.choice(V, k, replace=False) for _ in range(T)]).astype(np.int32)
+    val = _rand(T, k, 2.0)
+    base = oracle.kd_topk(s, idx, val, tau=2.0)
+    perm = RNG.permutation(k)
+    p = oracle.kd_topk(s, idx[:, perm], val[:, perm], tau=2.0)
+    np.testing.assert_allclose(p["kd"], base["kd"], rtol=1e-12)
+    np.testing.assert_allclose(p["grad"], base["grad"], rtol=1e-10, atol=1e-15)
+    sh = oracle.kd_topk(s, idx, val + 11.0, tau=2.0)      # stored logits vs stored log-probabilities
+    np.testing.assert_allclose(sh["kd"], base["kd"], rtol=1e-11)
+
+
+def test_topk_brute_force_tiny(oracle):
+    # Eq. 2 written out with python floats: p_T renormalised over the k entries, p_S over the full vocabulary
+    V, k, tau = 12, 3, 2.0
+    s = _rand(1, V, 2.0)
+    idx = np.array([[7, 2, 9]], np.int32)
+    val = np.array([[0.3, -1.2, 0.9]])
+    zs = sum(math.exp(x / tau) for x in s[0])
+    zt = sum(math.exp(v / tau) for v in val[0])
+    kl = 0.0
+    for j in range(k):
+        pt = math.exp(val[0, j] / tau) / zt
+        ps = math.exp(s[0, idx[0, j]] / tau) / zs
+        kl += pt * math.log(pt / ps)
+    out = oracle.kd_topk(s, idx, val, tau=tau, grad_scale=1.0)
+    assert out["kd"][0] == pytest.approx(kl, rel=1e-12)
+    g = np.array([math.exp(x / tau) / zs for x in s[0]]) / tau
+    for j in range(k):
+        g[idx[0, j]] -= math.exp(val[0, j] / tau) / zt / tau
+    np.testing.assert_allclose(out["grad"][0], g, rtol=1e-11, atol=1e-15)
+    # support smaller than V: KL stays >= 0 and is > KL of the renormalised student on the support
+    assert out["kd"][0] > 0
+
+
+def test_topk_bad_index_flagged(oracle):
+    s = _rand(2, 10)
+    idx = np.array([[1, 2], [3, 10]], np.int32)
+    out = oracle.kd_topk(s, idx, np.zeros((2, 2)))
+    assert out["bad_index_rows"] == 1 and np.isnan(out["kd"][1]) and np.isfinite(out["kd"][0])
+
+
+# --------------------------------------------------------------------------- gradient
+
+@pytest.mark.parametrize("tau", [1.0, 2.0])
+def test_grad_dense_finite_differences(oracle, tau):
+    T, V, h = 3, 48, 1e-6
+    s, t = _rand(T, V), _rand(T, V)
+    g = oracle.kd_dense(s, t, tau=tau, grad_scale=1.0)["grad"]
+    for r in range(T):
+        for c in range(V):
+            sp, sm = s.copy(), s.copy()
+            sp[r, c] += h
+            sm[r, c] -= h
+            fd = (oracle.kd_dense(sp, t, tau=tau, want_grad=False)["kd"][r]
+                  - oracle.kd_dense(sm, t, tau=tau, want_grad=False)["kd"][r]) / (2 * h)
+            assert g[r, c] == pytest.approx(fd, rel=2e-6, abs=1e-9)
+
+
+@pytest.mark.parametrize("tau", [1.0, 2.0])
+def test_grad_topk_finite_differences(oracle, tau):
+    T, V, k, h = 2, 40, 5, 1e-6
+    s = _rand(T, V)
+    idx = np.stack([RNG.choice(V, k, replace=False) for _ in range(T)]).astype(np.int32)
+    val = _rand(T, k)
+    g = oracle.kd_topk(s, idx, val, tau=tau)["grad"]
+    for r in range(T):
+        for c in range(V):
+            sp, sm = s.copy(), s.copy()
+            sp[r, c] += h
+            sm[r, c] -= h
+            fd = (oracle.kd_topk(sp, idx, val, tau=tau, want_grad=False)["kd"][r]
+                  - oracle.kd_topk(sm, idx, val, tau=tau, want_grad=False)["kd"][r]) / (2 * h)
+            assert g[r, c] == pytest.approx(fd, rel=2e-6, abs=1e-9)
+
+
+def test_grad_rows_sum_to_zero_and_match_softmax_difference(oracle):
+    T, V = 8, 2000
+    s, t = _rand(T, V, 3.0), _rand(T, V, 3.0)
+    for tau, scale in ((1.0, 1.0), (2.0, -0.3)):
+        g = oracle.kd_dense(s, t, tau=tau, grad_scale=scale)["grad"]
+        assert np.abs(g.sum(1)).max() < 1e-12 * V
+        ref = scale / tau * (torch.softmax(torch.from_numpy(s) / tau, 1) - torch.softmax(torch.from_numpy(t) / tau, 1))
+        np.testing.assert_allclose(g, ref.numpy(), rtol=1e-10, atol=1e-16)
+    idx = np.stack([RNG.choice(V, 64, replace=False) for _ in range(T)]).astype(np.int32)
+    g = oracle.kd_topk(s, idx, _rand(T, 64), tau=2.0)["grad"]
+    assert np.abs(g.sum(1)).max() < 1e-12 * V
+
+
+def test_masked_rows_are_zero(oracle):
+    T, V = 6, 30
+    s, t = _rand(T, V), _rand(T, V)
+    mask = np.array([1, 0, 1, 0, 0, 1], np.uint8)
+    lab = RNG.integers(0, V, T)
+    out = oracle.kd_dense(s, t, lab, mask)
+    for key in ("kd", "nll_s", "nll_t", "lse_s"):
+        assert (out[key][mask == 0] == 0).all() and (out[key][mask == 1] != 0).all()
+    assert (out["grad"][mask == 0] == 0).all()
+    full = oracle.kd_dense(s, t, lab)
+    np.testing.assert_array_equal(out["kd"][mask == 1], full["kd"][mask == 1])
+
+
+# --------------------------------------------------------------------------- bf16 front-ends
+
+def test_bf16_entry_points_equal_f64_entry_points_on_converted_values(oracle):
+    T, V, k = 5, 130, 8
+    sb = torch.from_numpy(_rand(T, V + 6, 3.0)).to(torch.bfloat16)     # row stride V + 6
+    tb = torch.from_numpy(_rand(T, V, 3.0)).to(torch.bfloat16)
+    s_bits = sb.view(torch.int16).numpy().view(np.uint16)[:, :V]
+    t_bits = tb.view(torch.int16).numpy().view(np.uint16)
+    s64, t64 = sb[:, :V].double().numpy(), tb.double().numpy()         # library conversion bf16 -> f64
+    lab = RNG.integers(0, V, T)
+    mask = np.array([1, 1, 0, 1, 1], np.uint8)
+    a = oracle.kd_dense(s_bits, t_bits, lab, mask, tau=2.0, grad_scale=0.5)
+    b = oracle.kd_dense(s64, t64, lab, mask, tau=2.0, grad_scale=0.5)
+    for key in a:
+        np.testing.assert_array_equal(a[key], b[key])
+    idx = np.stack([RNG.choice(V, k, replace=False) for _ in range(T)]).astype(np.int32)
+    val = _rand(T, k).astype(np.float32)
+    a = oracle.kd_topk(s_bits, idx, val, lab, mask, tau=2.0)
+    b = oracle.kd_topk(s64, idx, val.astype(np.float64), lab, mask, tau=2.0)
+    for key in ("kd", "nll_s", "lse_s", "grad"):
+        np.testing.assert_array_equal(a[key], b[key])
+    a = oracle.nll(t_bits, lab, mask)
+    b = oracle.nll(t64, lab, mask)
+    np.testing.assert_array_equal(a["nll"], b["nll"])
+
+
+# --------------------------------------------------------------------------- segment reduce / packing invariance
+
+def _brute_segments(x, mask, cu):
+    S = len(cu) - 1
+    sums, counts, t2s = [0.0] * S, [0] * S, [-1] * len(x)
+    for i in range(S):
+        for p in range(cu[i], cu[i + 1]):
+            t2s[p] = i
+            if mask[p]:
+                sums[i] += float(x[p])
+                counts[i] += 1
+    return sums, counts, t2s
+
+
+def test_segment_reduce_brute_force_and_edge_cases(oracle):
+    T = 100
+    x = RNG.normal(size=T)
+    mask = (RNG.random(T) < 0.6).astype(np.uint8)
+    cu = np.array([0, 0, 1, 1, 8, 9, 40, 40, 77, 93], np.int32)   # empty, length-1, tokens 93.. unowned
+    mask[9:40] = 0                                                # an all-masked sample
+    out = oracle.segment_reduce(x, mask, cu)
+    sums, counts, t2s = _brute_segments(x, mask, cu)
+    np.testing.assert_array_equal(out["count"], counts)
+    np.testing.assert_array_equal(out["token_to_sample"], t2s)
+    np.testing.assert_allclose(out["sum"], sums, rtol=0, atol=1e-13)
+    for i in range(len(cu) - 1):
+        want = sums[i] / counts[i] if counts[i] else 0.0
+        assert out["mean"][i] == pytest.approx(want, abs=1e-13)
+    assert out["count"][5] == 0 and out["mean"][5] == 0.0 and out["sum"][5] == 0.0
+    assert (out["token_to_sample"][93:] == -1).all()
+    with pytest.raises(ValueError):
+        oracle.segment_reduce(x, mask, np.array([0, 5, 3], np.int32))
+    with pytest.raises(ValueError):
+        oracle.segment_reduce(x, mask, np.array([0, 5, 101], np.int32))
+    # every start alignment 0..7, S = 1
+    for a in range(8):
+        o = oracle.segment_reduce(x, np.ones(T, np.uint8), np.array([a, a + 13], np.int32))
+        assert o["sum"][0] == pytest.approx(float(np.sum(x[a:a + 13])), abs=1e-13) and o["count"][0] == 13
+
+
+def test_packing_invariance(oracle):
+    # a packed batch gives, position by position, what each sample gives on its own
+    from paper_2605_05940_amd import synth
+    w = synth.config(0)
+    lay = synth.make_layout(w)
+    assert lay.cu_seqlens.tolist() == [0, 37, 101, 191, 312, 512]
+    assert int(lay.loss_mask.sum()) == 28 + 48 + 68 + 91
+    V = 96
+    s, t = _rand(512, V), _rand(512, V)
+    lab = lay.labels % V
+    packed = oracle.kd_dense(s, t, lab, lay.loss_mask, tau=2.0)
+    seg = oracle.segment_reduce(packed["kd"], lay.loss_mask, lay.cu_seqlens)
+    for i in range(lay.n_segments):
+        a, b = lay.cu_seqlens[i], lay.cu_seqlens[i + 1]
+        alone = oracle.kd_dense(s[a:b], t[a:b], lab[a:b], lay.loss_mask[a:b], tau=2.0)
+        for key in ("kd", "nll_s", "nll_t", "grad"):
+            np.testing.assert_array_equal(alone[key], packed[key][a:b])
+        one = oracle.segment_reduce(alone["kd"], lay.loss_mask[a:b], np.array([0, b - a], np.int32))
+        assert one["sum"][0] == seg["sum"][i] and one["count"][0] == seg["count"][i]
+        assert one["mean"][0] == seg["mean"][i]
+    assert seg["count"].tolist() == [28, 48, 68, 91, 0]
+
+
+# --------------------------------------------------------------------------- Delta-IFD (Eq. 3, Eq. 4, zones)
+
+def _golden_rows():
+    rows = []
+    with open(os.path.join(HERE, "golden", "delta_ifd_zones.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            lhs, rhs = line.split("|")
+            rows.append(([float(v) for v in lhs.split()], [float(v) for v in rhs.split()]))
+    return rows
+
+
+def test_delta_ifd_hand_worked_cases(oracle):
+    rows = _golden_rows()
+    assert len(rows) >= 10
+    for (lsc, lsu, ltc, ltu, nc, nu, lo, hi, flags), (ifs, ift, d, zone, keep) in rows:
+        out = oracle.delta_ifd([lsc, lsu], [ltc, ltu], [int(nc), int(nu)], [0], [1], lo, hi, int(flags))
+        np.testing.assert_array_equal(out["ifd_student"], [ifs])
+        np.testing.assert_array_equal(out["ifd_teacher"], [ift])
+        np.testing.assert_array_equal(out["delta"], [d])
+        assert out["zone"][0] == int(zone) and out["keep"][0] == int(keep) and out["keep_count"] == int(keep)
+
+
+def test_delta_ifd_brute_force_from_token_losses(oracle):
+    # 6 pairs; per-position CE losses -> per-sample means -> ratios, written with python loops
+    P = 6
+    lens_c = RNG.integers(3, 30, P)
+    lens_u = RNG.integers(3, 30, P)
+    cu = np.concatenate([[0], np.cumsum(np.stack([lens_c, lens_u], 1).reshape(-1))]).astype(np.int32)
+    T = int(cu[-1])
+    nll_s, nll_t = RNG.uniform(0.1, 5, T), RNG.uniform(0.1, 5, T)
+    mask = (RNG.random(T) < 0.8).astype(np.uint8)
+    mask[cu[:-1]] = 1
+    ms = oracle.segment_reduce(nll_s, mask, cu)
+    mt = oracle.segment_reduce(nll_t, mask, cu)
+    pc, pu = np.arange(0, 2 * P, 2), np.arange(1, 2 * P, 2)
+    out = oracle.delta_ifd(ms["mean"], mt["mean"], ms["count"], pc, pu, 0.0, 0.8)
+    kept = 0
+    for j in range(P):
+        def mean(x, i):
+            vals = [x[p] for p in range(cu[i], cu[i + 1]) if mask[p]]
+            return sum(vals) / len(vals)
+        ifs = mean(nll_s, pc[j]) / mean(nll_s, pu[j])
+        ift = mean(nll_t, pc[j]) / mean(nll_t, pu[j])
+        d = ift - ifs
+        assert out["ifd_student"][j] == pytest.approx(ifs, rel=1e-12)
+        assert out["ifd_teacher"][j] == pytest.approx(ift, rel=1e-12)
+        assert out["delta"][j] == pytest.approx(d, rel=1e-10, abs=1e-13)
+        zone = 0 if d < 0 else (2 if d > 0.8 else 1)
+        assert out["zone"][j] == zone
+        kept += zone == 1
+    assert out["keep_count"] == kept == int(out["keep"].sum())
+
+
+def test_delta_ifd_symmetries(oracle):
+    S = 10
+    ms, mt = RNG.uniform(0.5, 3, S), RNG.uniform(0.5, 3, S)
+    cnt = np.full(S, 4, np.int32)
+    pc, pu = np.arange(0, S, 2), np.arange(1, S, 2)
+    a = oracle.delta_ifd(ms, mt, cnt, pc, pu, 0.0, 1.0)
+    b = oracle.delta_ifd(mt, ms, cnt, pc, pu, 0.0, 1.0)        # swap teacher and student
+    np.testing.assert_array_equal(a["delta"], -b["delta"])
+    same = oracle.delta_ifd(ms, ms, cnt, pc, pu, 0.0, 0.8)      # teacher == student: delta 0, proximal (closed)
+    assert (same["delta"] == 0).all() and (same["zone"] == 1).all() and same["keep_count"] == len(pc)
+    # IFD > 1 exactly when the instruction makes the response harder to predict
+    assert ((a["ifd_student"] > 1) == (ms[pc] > ms[pu])).all()
