@@ -1,0 +1,7 @@
+"""MI355X-native packed KD loss of Near-Policy Distillation: HIP kernels behind a C ABI (``libnpd.so``).
+
+``binding`` holds the ctypes wrappers (same names as the C entry points); ``synth`` the seeded input
+generators; ``build`` compiles the library.  Nothing here computes on the CPU.
+"""
+from .binding import (NpdError, npd_delta_ifd_score, npd_kd_loss_fwd_bwd, npd_segment_reduce,  # noqa: F401
+                      npd_workspace_bytes, version)

@@ -1,0 +1,199 @@
+// Device-side building blocks shared by the libnpd kernels (gfx950, wave64).
+//
+// Numerics.  All soft-max work is done in the base-2 domain: with c = log2(e) / tau,
+// exp(x / tau) = 2^(x * c).  A partial log-sum-exp is a pair (r, z) meaning
+// sum = z * 2^r; a partial cross term `a` carries the same implicit 2^r.  r is a lane's
+// private reference exponent.  It only moves when an incoming value exceeds it by more
+// than 2^32, so the common case costs one fused multiply-add and one v_exp_f32 per
+// element and no rescaling; terms stay below 2^32 relative to r, far from fp32 overflow.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace npd {
+
+constexpr int kWave = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kRefSlack = 32.0f;  // a lane's reference exponent may lag its largest term by 2^32
+
+__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }  // v_exp_f32
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __builtin_bit_cast(float, w & 0xffff0000u); }
+__device__ __forceinline__ float bf16_one(uint16_t h) { return __builtin_bit_cast(float, (uint32_t)h << 16); }
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// two fp32 -> packed bf16, round to nearest even (v_cvt_pk_bf16_f32); `lo` lands in bits 0..15
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+__device__ __forceinline__ uint16_t one_bf16(float x) { return (uint16_t)(pack_bf16(x, 0.0f) & 0xffffu); }
+
+__device__ __forceinline__ void unpack8(const uint4& v, float x[8]) {
+  x[0] = bf16_lo(v.x); x[1] = bf16_hi(v.x);
+  x[2] = bf16_lo(v.y); x[3] = bf16_hi(v.y);
+  x[4] = bf16_lo(v.z); x[5] = bf16_hi(v.z);
+  x[6] = bf16_lo(v.w); x[7] = bf16_hi(v.w);
+}
+
+__device__ __forceinline__ float max8(const float x[8]) {
+  float m = fmaxf(fmaxf(x[0], x[1]), x[2]);
+  m = fmaxf(fmaxf(m, x[3]), x[4]);
+  m = fmaxf(fmaxf(m, x[5]), x[6]);
+  return fmaxf(m, x[7]);
+}
+
+// Partial log-sum-exp with an optional cross term.
+struct Lse {
+  float r, z, a;
+  __device__ __forceinline__ void init() { r = -INFINITY; z = 0.0f; a = 0.0f; }
+  // raise the reference to `u` if it lags by more than the slack (also the first touch: r = -inf)
+  __device__ __forceinline__ void raise(float u) {
+    if (u > r + kRefSlack) {
+      const float f = exp2_fast(r - u);  // r = -inf gives 0
+      z *= f;
+      a *= f;
+      r = u;
+    }
+  }
+  __device__ __forceinline__ void add8(const float x[8], float c) {
+    raise(max8(x) * c);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) z += exp2_fast(__builtin_fmaf(x[i], c, -r));
+  }
+  // also accumulates a += 2^(x*c - r) * d
+  __device__ __forceinline__ void add8_cross(const float x[8], const float d[8], float c) {
+    raise(max8(x) * c);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float e = exp2_fast(__builtin_fmaf(x[i], c, -r));
+      z += e;
+      a = __builtin_fmaf(e, d[i], a);
+    }
+  }
+  __device__ __forceinline__ void add1(float x, float c) {
+    raise(x * c);
+    z += exp2_fast(__builtin_fmaf(x, c, -r));
+  }
+  __device__ __forceinline__ void add1_cross(float x, float d, float c) {
+    raise(x * c);
+    const float e = exp2_fast(__builtin_fmaf(x, c, -r));
+    z += e;
+    a = __builtin_fmaf(e, d, a);
+  }
+  // merge another partial into this one (same code for every stream, so that two streams fed
+  // identical data stay bitwise identical)
+  __device__ __forceinline__ void merge(float r2, float z2, float a2) {
+    const float R = fmaxf(r, r2);
+    const float f1 = (r == R) ? 1.0f : exp2_fast(r - R);
+    const float f2 = (r2 == R) ? 1.0f : exp2_fast(r2 - R);
+    // explicit products and fused adds: the contraction must not depend on the call site
+    z = __builtin_fmaf(z, f1, __fmul_rn(z2, f2));
+    a = __builtin_fmaf(a, f1, __fmul_rn(a2, f2));
+    r = R;
+  }
+  __device__ __forceinline__ float log2_z() const { return __log2f(z); }
+  __device__ __forceinline__ float log2_sum() const { return r + __log2f(z); }
+};
+
+__device__ __forceinline__ void wave_merge(Lse& v) {
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) {
+    const float r2 = __shfl_xor(v.r, off, kWave);
+    const float z2 = __shfl_xor(v.z, off, kWave);
+    const float a2 = __shfl_xor(v.a, off, kWave);
+    v.merge(r2, z2, a2);
+  }
+}
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) x += __shfl_xor(x, off, kWave);
+  return x;
+}
+
+__device__ __forceinline__ int wave_sum_int(int x) {
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) x += __shfl_xor(x, off, kWave);
+  return x;
+}
+
+// Block-wide merge of N partials; every thread returns with the block totals.
+// smem: at least N * 3 * (BLOCK / 64) floats.  Contains two barriers.
+template <int BLOCK, int N>
+__device__ __forceinline__ void block_merge(Lse (&v)[N], float* smem) {
+  constexpr int NW = BLOCK / kWave;
+  const int lane = threadIdx.x & (kWave - 1), wid = threadIdx.x / kWave;
+#pragma unroll
+  for (int i = 0; i < N; ++i) wave_merge(v[i]);
+  if constexpr (NW > 1) {
+    if (lane == 0) {
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        smem[(i * 3 + 0) * NW + wid] = v[i].r;
+        smem[(i * 3 + 1) * NW + wid] = v[i].z;
+        smem[(i * 3 + 2) * NW + wid] = v[i].a;
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      // every wave folds the NW partials in the same order: identical totals everywhere
+      Lse t;
+      t.r = smem[(i * 3 + 0) * NW];
+      t.z = smem[(i * 3 + 1) * NW];
+      t.a = smem[(i * 3 + 2) * NW];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) t.merge(smem[(i * 3 + 0) * NW + w], smem[(i * 3 + 1) * NW + w], smem[(i * 3 + 2) * NW + w]);
+      v[i] = t;
+    }
+    __syncthreads();
+  } else {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {  // one wave: every lane takes lane 0's totals
+      v[i].r = __shfl(v[i].r, 0, kWave);
+      v[i].z = __shfl(v[i].z, 0, kWave);
+      v[i].a = __shfl(v[i].a, 0, kWave);
+    }
+  }
+}
+
+template <int BLOCK>
+__device__ __forceinline__ float block_sum(float x, float* smem) {
+  constexpr int NW = BLOCK / kWave;
+  const int lane = threadIdx.x & (kWave - 1), wid = threadIdx.x / kWave;
+  x = wave_sum(x);
+  if constexpr (NW > 1) {
+    if (lane == 0) smem[wid] = x;
+    __syncthreads();
+    float t = smem[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) t += smem[w];
+    __syncthreads();
+    x = t;
+  }
+  return x;
+}
+
+template <int BLOCK>
+__device__ __forceinline__ int block_sum_int(int x, int* smem) {
+  constexpr int NW = BLOCK / kWave;
+  const int lane = threadIdx.x & (kWave - 1), wid = threadIdx.x / kWave;
+  x = wave_sum_int(x);
+  if constexpr (NW > 1) {
+    if (lane == 0) smem[wid] = x;
+    __syncthreads();
+    int t = smem[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) t += smem[w];
+    __syncthreads();
+    x = t;
+  }
+  return x;
+}
+
+}  // namespace npd

@@ -1,0 +1,46 @@
+// Host-side launch interface between the C ABI (npd_api.hip) and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace npd {
+
+enum TeacherKind { kDense = 0, kTopk = 1, kNone = 2 };
+
+constexpr int kTopkMax = 4096;  // largest k the top-k kernels stage per row
+
+struct KdArgs {
+  const uint16_t* s;      // student logits, bf16 [T, s_stride]
+  const uint16_t* t;      // dense teacher logits, bf16 [T, t_stride]
+  const int32_t* tidx;    // top-k ids [T, k]
+  const float* tval;      // top-k values [T, k]
+  const int32_t* labels;  // [T] or null
+  const uint8_t* mask;    // [T]
+  uint16_t* g;            // gradient, bf16 [T, s_stride] or null
+  float* kd;
+  float* nll;
+  float* tnll;
+  float* lse;
+  int32_t* status;
+  int64_t T;
+  int64_t s_stride, t_stride;
+  int32_t V, k;
+  int32_t nvec_s;      // 8-element groups of a row that are moved with 128-bit accesses (0: unaligned)
+  float c;             // log2(e) / tau
+  float inv_tau;
+  float gscale;        // grad_scale / tau
+  int32_t need_lse1;   // tau != 1 and a tau = 1 quantity (nll, teacher nll, lse) is wanted
+};
+
+hipError_t launch_kd(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream);
+
+hipError_t launch_segment_reduce(int64_t T, int32_t S, const float* values, const uint8_t* mask, const int32_t* cu,
+                                 float* seg_sum, int32_t* seg_count, float* seg_mean, int32_t* token_to_sample,
+                                 int32_t* status, hipStream_t stream);
+
+hipError_t launch_delta_ifd(int32_t P, int32_t S, const float* ms, const float* mt, const int32_t* cnt,
+                            const int32_t* pc, const int32_t* pu, float lo, float hi, uint32_t flags, float* ifd_s,
+                            float* ifd_t, float* delta, uint8_t* zone, uint8_t* keep, int32_t* keep_count,
+                            hipStream_t stream);
+
+}  // namespace npd

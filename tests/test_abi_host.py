@@ -1,0 +1,172 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports what include/npd.h declares,
+rejects bad arguments before touching HIP, and the synthetic layouts are deterministic."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2605_05940_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, E_NULL, E_SHAPE, E_VALUE, E_ALIAS, E_UNSUP, E_WS, E_HIP = range(8)
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return binding.load()
+
+
+def test_exports_match_header(lib):
+    text = open(os.path.join(ROOT, "include", "npd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(npd_[a-z_0-9]+)\s*\(", text))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert lib.npd_version() >= 100
+    for st in range(8):
+        assert len(lib.npd_status_string(st)) > 0
+    assert lib.npd_status_string(0) == b"ok"
+
+
+def test_desc_layout_matches_header():
+    # n_tokens i64, vocab i32, teacher_kind i32, student_stride i64, teacher_stride i64, topk i32, flags u32,
+    # tau f32, grad_scale f32
+    assert ctypes.sizeof(binding.KdDesc) == 48
+    assert binding.KdDesc.student_stride.offset == 16 and binding.KdDesc.tau.offset == 40
+
+
+FAKE = 0x10000  # a non-null address that is never dereferenced: every call below fails validation first
+
+
+def _desc(**kw):
+    d = binding.KdDesc()
+    d.n_tokens, d.vocab, d.teacher_kind = 16, 64, binding.NPD_TEACHER_DENSE_BF16
+    d.student_stride = d.teacher_stride = 64
+    d.topk, d.flags, d.tau, d.grad_scale = 0, 0, 1.0, 1.0
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def _kd(lib, d, student=FAKE, teacher=FAKE + 0x100000, idx=None, val=None, labels=None, mask=FAKE + 0x200000,
+        grad=FAKE + 0x300000, kd=None, nll=None, tnll=None, lse=None, ws=None, ws_bytes=0):
+    return lib.npd_kd_loss_fwd_bwd(ctypes.byref(d), student, teacher, idx, val, labels, mask, grad, kd, nll, tnll, lse,
+                                   None, ws, ws_bytes, None)
+
+
+def test_kd_argument_validation(lib):
+    assert lib.npd_kd_loss_fwd_bwd(None, *([None] * 13), 0, None) == E_NULL
+    assert _kd(lib, _desc(n_tokens=0)) == E_SHAPE
+    assert _kd(lib, _desc(vocab=0)) == E_SHAPE
+    assert _kd(lib, _desc(student_stride=63)) == E_SHAPE
+    assert _kd(lib, _desc(teacher_stride=10)) == E_SHAPE
+    assert _kd(lib, _desc(tau=0.0)) == E_VALUE
+    assert _kd(lib, _desc(tau=-1.0)) == E_VALUE
+    assert _kd(lib, _desc(tau=float("nan"))) == E_VALUE
+    assert _kd(lib, _desc(tau=float("inf"))) == E_VALUE
+    assert _kd(lib, _desc(grad_scale=float("nan"))) == E_VALUE
+    assert _kd(lib, _desc(teacher_kind=7)) == E_VALUE
+    assert _kd(lib, _desc(flags=64)) == E_VALUE
+    assert _kd(lib, _desc(flags=3)) == E_VALUE                      # forward-only and in-place together
+    assert _kd(lib, _desc(), student=None) == E_NULL
+    assert _kd(lib, _desc(), mask=None) == E_NULL
+    assert _kd(lib, _desc(), teacher=None) == E_NULL
+    assert _kd(lib, _desc(), grad=None) == E_NULL                   # gradient wanted but no buffer
+    assert _kd(lib, _desc(flags=1)) == E_VALUE                      # forward-only with a gradient buffer
+    assert _kd(lib, _desc(), nll=FAKE + 0x400000) == E_NULL         # NLL without labels
+    assert _kd(lib, _desc(), grad=FAKE) == E_ALIAS                  # in place without the flag
+    assert _kd(lib, _desc(flags=2)) == E_ALIAS                      # flag without aliasing
+    assert _kd(lib, _desc(), grad=FAKE + 2) == E_ALIAS              # partial overlap with the student
+    assert _kd(lib, _desc(), grad=FAKE + 0x100000 + 64) == E_ALIAS  # overlap with the teacher
+    assert _kd(lib, _desc(), grad=FAKE + 0x200000 - 8) == E_ALIAS   # overlap with the mask
+    # top-k teacher
+    tk = dict(teacher_kind=binding.NPD_TEACHER_TOPK, topk=8)
+    assert _kd(lib, _desc(**tk), teacher=None, idx=None, val=FAKE + 0x500000) == E_NULL
+    assert _kd(lib, _desc(teacher_kind=1, topk=0), teacher=None, idx=FAKE + 0x500000, val=FAKE + 0x600000) == E_SHAPE
+    assert _kd(lib, _desc(teacher_kind=1, topk=65), teacher=None, idx=FAKE + 0x500000, val=FAKE + 0x600000) == E_SHAPE
+    assert _kd(lib, _desc(**tk), idx=FAKE + 0x500000, val=FAKE + 0x600000) == E_VALUE   # dense tensor given too
+    big = _desc(teacher_kind=1, topk=5000, vocab=8192, student_stride=8192)
+    assert _kd(lib, big, teacher=None, idx=FAKE + 0x500000, val=FAKE + 0x600000) == E_UNSUP
+    # no teacher: forward-only scoring
+    nt = dict(teacher_kind=binding.NPD_TEACHER_NONE)
+    assert _kd(lib, _desc(**nt), teacher=None) == E_VALUE           # gradient without a teacher
+    assert _kd(lib, _desc(flags=1, **nt), teacher=None, grad=None, kd=FAKE + 0x700000) == E_VALUE
+    assert lib.npd_workspace_bytes(ctypes.byref(_desc())) == 0
+
+
+def test_segment_and_ifd_argument_validation(lib):
+    assert lib.npd_segment_reduce(-1, 1, *([FAKE] * 8), None) == E_SHAPE
+    assert lib.npd_segment_reduce(8, -1, *([FAKE] * 8), None) == E_SHAPE
+    assert lib.npd_segment_reduce(8, 2, FAKE, None, FAKE, FAKE, FAKE, FAKE, None, None, None) == E_NULL
+    assert lib.npd_segment_reduce(8, 2, FAKE, FAKE, None, FAKE, FAKE, FAKE, None, None, None) == E_NULL
+    assert lib.npd_segment_reduce(8, 2, None, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, None) == E_NULL
+    args = [FAKE] * 5
+    outs = [None] * 6
+    assert lib.npd_delta_ifd_score(-1, 4, *args, 0.0, 1.0, 0, *outs, None) == E_SHAPE
+    assert lib.npd_delta_ifd_score(2, 4, *args, 1.0, 0.5, 0, *outs, None) == E_VALUE
+    assert lib.npd_delta_ifd_score(2, 4, *args, float("nan"), 0.5, 0, *outs, None) == E_VALUE
+    assert lib.npd_delta_ifd_score(2, 4, *args, 0.0, 1.0, 8, *outs, None) == E_VALUE
+    assert lib.npd_delta_ifd_score(2, 4, None, FAKE, FAKE, FAKE, FAKE, 0.0, 1.0, 0, *outs, None) == E_NULL
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    with pytest.raises(ValueError):
+        binding.npd_kd_loss_fwd_bwd(torch.zeros(4, 8, dtype=torch.bfloat16), torch.ones(4, dtype=torch.uint8))
+
+
+# --------------------------------------------------------------------------- synthetic layouts
+
+def test_layouts_are_deterministic_and_well_formed():
+    for i in range(5):
+        w = synth.config(i)
+        a, b = synth.make_layout(w), synth.make_layout(w)
+        for f in ("cu_seqlens", "loss_mask", "labels", "is_pad_segment", "pair_cond", "pair_uncond"):
+            np.testing.assert_array_equal(getattr(a, f), getattr(b, f))
+        cu = a.cu_seqlens
+        assert cu[0] == 0 and cu[-1] == w.n_tokens and (np.diff(cu) >= 0).all()
+        assert a.loss_mask.shape == (w.n_tokens,) and a.labels.min() >= 0 and a.labels.max() < w.vocab
+        # no sample straddles a row boundary; pad segments are fully masked
+        for s in range(a.n_segments):
+            if cu[s + 1] > cu[s]:
+                assert cu[s] // w.row_len == (cu[s + 1] - 1) // w.row_len
+            if a.is_pad_segment[s]:
+                assert a.loss_mask[cu[s]:cu[s + 1]].sum() == 0
+
+
+def test_config0_and_paired_layout_details():
+    lay = synth.make_layout(synth.config(0))
+    assert lay.cu_seqlens.tolist() == [0, 37, 101, 191, 312, 512]
+    # floor(25 %) of each sample is prompt
+    assert [int(lay.loss_mask[a:b].sum()) for a, b in zip(lay.cu_seqlens[:-1], lay.cu_seqlens[1:])] == [28, 48, 68, 91, 0]
+    w3 = synth.config(3)
+    lay3 = synth.make_layout(w3)
+    assert len(lay3.pair_cond) == len(lay3.pair_uncond) >= 4
+    cu = lay3.cu_seqlens
+    for pc, pu in zip(lay3.pair_cond, lay3.pair_uncond):
+        n = cu[pu + 1] - cu[pu]
+        q = cu[pc + 1] - cu[pc] - n
+        assert w3.prefix_lo <= q <= w3.prefix_hi and w3.length_lo <= n <= w3.length_hi
+        assert lay3.loss_mask[cu[pc]:cu[pc] + q].sum() == 0 and lay3.loss_mask[cu[pc] + q:cu[pc + 1]].all()
+        assert lay3.loss_mask[cu[pu]:cu[pu + 1]].all()
+        np.testing.assert_array_equal(lay3.labels[cu[pc] + q:cu[pc + 1]], lay3.labels[cu[pu]:cu[pu + 1]])
+
+
+def test_cpu_logit_generation_is_reproducible():
+    import torch
+    w = synth.scaled(synth.config(1), n_rows=1, row_len=300, vocab=520)
+    s1 = torch.empty((300, 520), dtype=torch.bfloat16)
+    t1 = torch.empty_like(s1)
+    s2, t2 = torch.empty_like(s1), torch.empty_like(s1)
+    synth.fill_logits(w, s1, t1)
+    synth.fill_logits(w, s2, t2)
+    assert torch.equal(s1, s2) and torch.equal(t1, t2)
+    assert 2.5 < s1.float().std().item() < 3.5
+    w2 = synth.scaled(synth.config(2), n_rows=1, row_len=300, vocab=520, topk=16)
+    idx, val = synth.make_topk_teacher(w2, s1)
+    assert idx.shape == (300, 16) and all(len(set(r.tolist())) == 16 for r in idx)
+    assert idx.min() >= 0 and idx.max() < 520
+    assert torch.allclose(val.double().exp().sum(1), torch.ones(300, dtype=torch.float64), atol=1e-6)

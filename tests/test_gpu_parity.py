@@ -1,0 +1,378 @@
+"""GPU parity: the HIP library, called through its C ABI, against the float64 oracle on the same bits.
+
+Bars (bf16 inputs, fp32 accumulation): per-sample KD loss and mean NLL within 1e-3 relative, gradient max abs
+error <= 2e-3 at grad_scale = 1, all integer / index / zone bookkeeping bit-exact.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_05940_amd import binding, synth
+
+from gpu_util import (Guarded, REL_PER_SAMPLE, compare_kd, dev, guarded_rows, run_gpu_kd)
+
+pytestmark = pytest.mark.gpu
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def _say(msg):
+    print(f"[gpu-parity] {msg}", flush=True)
+
+
+def _inputs(w, stride=None, seed=synth.SEED, dense_teacher=True):
+    """Layout + bf16 logits of workload `w` on the GPU (row stride `stride` elements, default V)."""
+    lay = synth.make_layout(w, seed)
+    T, V = w.n_tokens, w.vocab
+    stride = stride or V
+    s = torch.zeros((T, stride), dtype=torch.bfloat16, device=dev())[:, :V]
+    t = torch.zeros((T, stride), dtype=torch.bfloat16, device=dev())[:, :V] if dense_teacher else None
+    synth.fill_logits(w, s, t, seed)
+    mask = torch.from_numpy(lay.loss_mask).to(dev())
+    labels = torch.from_numpy(lay.labels).to(dev())
+    return lay, s, t, mask, labels
+
+
+def _bits(x):
+    return synth.bf16_bits(x)
+
+
+# --------------------------------------------------------------------------- dense teacher
+
+def test_cfg0_tiny_dense_full(oracle):
+    w = synth.config(0)
+    _say(f"{w.name} T={w.n_tokens} V={w.vocab}")
+    lay, s, t, mask, labels = _inputs(w)
+    gpu = run_gpu_kd(s, mask, t=t, labels=labels, tau=w.tau)
+    ref = oracle.kd_dense(_bits(s), _bits(t), lay.labels, lay.loss_mask, tau=w.tau)
+    assert gpu["status"] == 0
+    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle)
+    # rows of the bf16 gradient sum to ~0 (each element carries up to half a bf16 step)
+    assert np.abs(gpu["grad"].sum(1)).max() < 1e-2
+
+
+@pytest.mark.parametrize("V,stride,tau,scale", [
+    (151936, 151936, 1.0, 1.0),      # the 1B-student vocabulary: 1024-thread path, 18.5 groups per thread
+    (4099, 4104, 2.0, 1.0),          # 256-thread path, ragged 3-element tail, padded rows
+    (4099, 4099, 1.0, -0.5),         # rows not 16-byte aligned: element-wise path; negative scale
+    (1000, 1000, 0.5, 3.0),          # 64-thread path
+    (7, 7, 1.0, 1.0),                # shorter than one 128-bit group
+    (1, 8, 1.0, 1.0),                # single-token vocabulary: KL = 0, grad = 0
+    (262144, 262144, 1.0, 1.0),      # largest vocabulary
+])
+def test_dense_shapes(oracle, V, stride, tau, scale):
+    n_rows, row_len = (2, 96) if V > 100000 else (2, 160)
+    w = synth.scaled(synth.config(1), n_rows=n_rows, row_len=row_len, vocab=V, length_lo=8, length_hi=64)
+    _say(f"dense V={V} stride={stride} tau={tau} scale={scale} T={w.n_tokens}")
+    lay, s, t, mask, labels = _inputs(w, stride)
+    gpu = run_gpu_kd(s, mask, t=t, labels=labels, tau=tau, grad_scale=scale)
+    ref = oracle.kd_dense(_bits(s.contiguous()), _bits(t.contiguous()), lay.labels, lay.loss_mask, tau=tau,
+                          grad_scale=scale)
+    assert gpu["status"] == 0
+    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle, grad_scale=scale, tau=tau)
+
+
+def test_dense_forward_only_and_tau_not_one_nll(oracle):
+    w = synth.scaled(synth.config(1), n_rows=1, row_len=128, vocab=33000, length_lo=8, length_hi=64)
+    lay, s, t, mask, labels = _inputs(w)
+    _say("dense forward only, tau=2 with tau=1 NLLs")
+    gpu = run_gpu_kd(s, mask, t=t, labels=labels, tau=2.0, want_grad=False)
+    ref = oracle.kd_dense(_bits(s), _bits(t), lay.labels, lay.loss_mask, tau=2.0, want_grad=False)
+    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle)
+    # forward-only and forward+backward give identical scalars
+    both = run_gpu_kd(s, mask, t=t, labels=labels, tau=2.0)
+    for key in ("kd", "nll_s", "nll_t", "lse_s"):
+        np.testing.assert_array_equal(gpu[key], both[key])
+
+
+def test_student_equals_teacher_gives_exact_zero(oracle):
+    w = synth.scaled(synth.config(1), n_rows=1, row_len=64, vocab=151936, length_lo=8, length_hi=32)
+    lay, s, _, mask, labels = _inputs(w, dense_teacher=False)
+    t = s.clone()
+    _say("student == teacher")
+    for tau in (1.0, 2.0):
+        gpu = run_gpu_kd(s, mask, t=t, labels=labels, tau=tau)
+        assert (gpu["kd"] == 0.0).all()
+        assert (gpu["grad_bits"] & 0x7fff == 0).all()       # +0 or -0 everywhere
+        np.testing.assert_array_equal(gpu["nll_s"], gpu["nll_t"])
+
+
+def test_inplace_matches_out_of_place_bitwise(oracle):
+    w = synth.scaled(synth.config(4), n_rows=1, row_len=192, vocab=262144, length_lo=16, length_hi=64)
+    _say(f"{w.name} reduced: in-place gradient, heavy tails, V={w.vocab}")
+    lay, s, t, mask, labels = _inputs(w)
+    ref = oracle.kd_dense(_bits(s), _bits(t), lay.labels, lay.loss_mask, tau=1.0)
+    out = run_gpu_kd(s, mask, t=t, labels=labels)
+    compare_kd(out, ref, lay.loss_mask, lay.cu_seqlens, oracle)
+    s2 = s.clone()
+    inp = run_gpu_kd(s2, mask, t=t, labels=labels, inplace=True)
+    np.testing.assert_array_equal(inp["grad_bits"], out["grad_bits"])
+    for key in ("kd", "nll_s", "nll_t", "lse_s"):
+        np.testing.assert_array_equal(inp[key], out[key])
+    assert np.abs(_bits(s).astype(np.int32)).max() > 0 and np.isfinite(out["kd"]).all()
+    # heavy tails really are heavy here: some logit beyond +-100
+    assert np.abs(s.float().cpu().numpy()).max() > 100
+
+
+def test_all_masked_and_single_row(oracle):
+    V = 4104
+    s = torch.randn((5, V), device=dev()).to(torch.bfloat16)
+    t = torch.randn((5, V), device=dev()).to(torch.bfloat16)
+    labels = torch.zeros(5, dtype=torch.int32, device=dev())
+    mask = torch.zeros(5, dtype=torch.uint8, device=dev())
+    gpu = run_gpu_kd(s, mask, t=t, labels=labels)
+    assert (gpu["kd"] == 0).all() and (gpu["nll_s"] == 0).all() and (gpu["grad_bits"] == 0).all()
+    one = run_gpu_kd(s[:1], torch.ones(1, dtype=torch.uint8, device=dev()), t=t[:1], labels=labels[:1])
+    ref = oracle.kd_dense(_bits(s[:1]), _bits(t[:1]), np.zeros(1, np.int32), np.ones(1, np.uint8))
+    compare_kd(one, ref, np.ones(1, np.uint8))
+
+
+def test_zero_scale_and_determinism(oracle):
+    w = synth.scaled(synth.config(1), n_rows=1, row_len=64, vocab=40000, length_lo=8, length_hi=32)
+    lay, s, t, mask, labels = _inputs(w)
+    z = run_gpu_kd(s, mask, t=t, labels=labels, grad_scale=0.0)
+    assert (z["grad_bits"] & 0x7fff == 0).all()
+    a = run_gpu_kd(s, mask, t=t, labels=labels, tau=2.0)
+    b = run_gpu_kd(s, mask, t=t, labels=labels, tau=2.0)
+    np.testing.assert_array_equal(a["grad_bits"], b["grad_bits"])
+    for key in ("kd", "nll_s", "nll_t", "lse_s"):
+        np.testing.assert_array_equal(a[key], b[key])
+
+
+def test_bad_label_sets_status_and_nan(oracle):
+    V = 520
+    s = torch.randn((4, V), device=dev()).to(torch.bfloat16)
+    t = torch.randn((4, V), device=dev()).to(torch.bfloat16)
+    labels = torch.tensor([3, V, -1, 5], dtype=torch.int32, device=dev())
+    mask = torch.tensor([1, 1, 0, 1], dtype=torch.uint8, device=dev())
+    gpu = run_gpu_kd(s, mask, t=t, labels=labels)
+    assert gpu["status"] == binding.NPD_DEV_BAD_LABEL
+    assert np.isnan(gpu["nll_s"][1]) and np.isnan(gpu["nll_t"][1]) and np.isfinite(gpu["nll_s"][[0, 3]]).all()
+    assert gpu["nll_s"][2] == 0 and np.isfinite(gpu["kd"]).all()     # masked bad label is ignored
+
+
+# --------------------------------------------------------------------------- top-k teacher
+
+@pytest.mark.parametrize("V,k,tau,scale,inplace", [
+    (151936, 64, 2.0, 1.0, False),   # config 2's shape
+    (151936, 10, 1.0, 1.0, True),    # the paper's default k, in place
+    (5003, 200, 2.0, -2.0, False),   # k larger than a wave, unaligned rows
+    (300, 300, 1.0, 1.0, False),     # k = V
+    (40000, 1, 1.0, 1.0, False),     # k = 1
+])
+def test_topk_shapes(oracle, V, k, tau, scale, inplace):
+    n_rows, row_len = (2, 96) if V > 100000 else (2, 128)
+    w = synth.scaled(synth.config(2), n_rows=n_rows, row_len=row_len, vocab=V, length_lo=8, length_hi=64, topk=k)
+    _say(f"top-k V={V} k={k} tau={tau} scale={scale} inplace={inplace}")
+    lay, s, _, mask, labels = _inputs(w, dense_teacher=False)
+    idx, val = synth.make_topk_teacher(w, s)
+    ref = oracle.kd_topk(_bits(s), idx.cpu().numpy(), val.cpu().numpy(), lay.labels, lay.loss_mask, tau=tau,
+                         grad_scale=scale)
+    assert ref["bad_index_rows"] == 0
+    gpu = run_gpu_kd(s.clone() if inplace else s, mask, idx=idx, val=val, labels=labels, tau=tau, grad_scale=scale,
+                     inplace=inplace)
+    assert gpu["status"] == 0
+    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle, grad_scale=scale, tau=tau)
+
+
+def test_topk_uniform_closed_form_on_gpu():
+    # uniform student, k equal teacher entries: KL = ln(V / k)
+    V, k = 151936, 64
+    s = torch.zeros((2, V), dtype=torch.bfloat16, device=dev())
+    idx = (torch.arange(k, device=dev(), dtype=torch.int32) * 997 + 5).repeat(2, 1).contiguous()
+    val = torch.full((2, k), -3.0, device=dev())
+    gpu = run_gpu_kd(s, torch.ones(2, dtype=torch.uint8, device=dev()), idx=idx, val=val, want_grad=False)
+    np.testing.assert_allclose(gpu["kd"], np.log(V / k), rtol=1e-5)
+
+
+def test_topk_bad_index_is_flagged():
+    V, k = 1000, 8
+    s = torch.randn((3, V), device=dev()).to(torch.bfloat16)
+    idx = torch.arange(k, dtype=torch.int32, device=dev()).repeat(3, 1).contiguous()
+    idx[1, 3] = V
+    val = torch.zeros((3, k), device=dev())
+    gpu = run_gpu_kd(s, torch.ones(3, dtype=torch.uint8, device=dev()), idx=idx, val=val)
+    assert gpu["status"] == binding.NPD_DEV_BAD_TOPK_INDEX
+    assert np.isnan(gpu["kd"][1]) and np.isfinite(gpu["kd"][[0, 2]]).all()
+    assert np.isnan(gpu["grad"][1]).all() and np.isfinite(gpu["grad"][[0, 2]]).all()
+
+
+# --------------------------------------------------------------------------- scoring pass, segment reduce, Delta-IFD
+
+def _segment_gpu(values, mask, cu, want_t2s=True):
+    T, S = mask.numel(), cu.numel() - 1
+    ssum, scnt, smean = Guarded(S, torch.float32), Guarded(S, torch.int32), Guarded(S, torch.float32)
+    t2s = Guarded(T, torch.int32) if want_t2s else None
+    status = torch.zeros(1, dtype=torch.int32, device=dev())
+    binding.npd_segment_reduce(values, mask, cu, seg_sum=ssum.t, seg_count=scnt.t, seg_mean=smean.t,
+                               token_to_sample=t2s.t if t2s else None, dev_status=status)
+    torch.cuda.synchronize()
+    return dict(sum=ssum.check().cpu().numpy().astype(np.float64), count=scnt.check().cpu().numpy(),
+                mean=smean.check().cpu().numpy().astype(np.float64),
+                token_to_sample=t2s.check().cpu().numpy() if t2s else None, status=int(status.item()),
+                mean_dev=smean.t, count_dev=scnt.t)
+
+
+def _ifd_gpu(ms, mt, cnt, pc, pu, lo, hi, flags=0):
+    P = pc.numel()
+    outs = dict(ifd_student=Guarded(P, torch.float32), ifd_teacher=Guarded(P, torch.float32),
+                delta=Guarded(P, torch.float32), zone=Guarded(P, torch.uint8), keep=Guarded(P, torch.uint8),
+                keep_count=Guarded(1, torch.int32))
+    binding.npd_delta_ifd_score(ms, mt, cnt, pc, pu, lo, hi, flags=flags, **{k: v.t for k, v in outs.items()})
+    torch.cuda.synchronize()
+    return {k: v.check().cpu().numpy() for k, v in outs.items()}
+
+
+def test_segment_reduce_bookkeeping_bit_exact(oracle):
+    rng = np.random.default_rng(7)
+    for T, cu in ((1000, [0, 0, 1, 1, 9, 300, 300, 555, 901]),          # empty, length-1, unowned tail
+                  (5000, np.concatenate([[3], 3 + np.cumsum(rng.integers(0, 40, 300))])),   # starts at 3
+                  (70000, [0, 70000])):                                   # one long sample
+        cu = np.asarray(cu, np.int32)
+        cu = cu[cu <= T]
+        x = rng.normal(size=T).astype(np.float32)
+        m = (rng.random(T) < 0.7).astype(np.uint8)
+        _say(f"segment reduce T={T} S={len(cu) - 1}")
+        gpu = _segment_gpu(torch.from_numpy(x).to(dev()), torch.from_numpy(m).to(dev()), torch.from_numpy(cu).to(dev()))
+        ref = oracle.segment_reduce(x.astype(np.float64), m, cu)
+        assert gpu["status"] == 0
+        np.testing.assert_array_equal(gpu["count"], ref["count"])
+        np.testing.assert_array_equal(gpu["token_to_sample"], ref["token_to_sample"])
+        np.testing.assert_allclose(gpu["sum"], ref["sum"], rtol=1e-5, atol=1e-4)
+        np.testing.assert_allclose(gpu["mean"], ref["mean"], rtol=1e-5, atol=1e-5)
+        assert (gpu["mean"][ref["count"] == 0] == 0).all()
+    # S = 0 only clears token_to_sample; a decreasing cu_seqlens is flagged
+    t2s = torch.zeros(10, dtype=torch.int32, device=dev())
+    binding.npd_segment_reduce(None, torch.ones(10, dtype=torch.uint8, device=dev()),
+                               torch.zeros(1, dtype=torch.int32, device=dev()), token_to_sample=t2s)
+    assert (t2s == -1).all()
+    bad = _segment_gpu(torch.ones(10, device=dev()), torch.ones(10, dtype=torch.uint8, device=dev()),
+                       torch.tensor([0, 6, 4, 11], dtype=torch.int32, device=dev()))
+    assert bad["status"] == binding.NPD_DEV_BAD_CU_SEQLENS
+    assert bad["count"].tolist() == [6, 0, 0] and np.isnan(bad["sum"][1:]).all() and bad["sum"][0] == 6
+
+
+def test_delta_ifd_hand_worked_cases_on_gpu():
+    rows = []
+    with open(os.path.join(HERE, "golden", "delta_ifd_zones.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                lhs, rhs = line.split("|")
+                rows.append(([float(v) for v in lhs.split()], [float(v) for v in rhs.split()]))
+    for (lsc, lsu, ltc, ltu, nc, nu, lo, hi, flags), (ifs, ift, d, zone, keep) in rows:
+        f32 = lambda a: torch.tensor(a, dtype=torch.float32, device=dev())
+        i32 = lambda a: torch.tensor(a, dtype=torch.int32, device=dev())
+        out = _ifd_gpu(f32([lsc, lsu]), f32([ltc, ltu]), i32([int(nc), int(nu)]), i32([0]), i32([1]), lo, hi, int(flags))
+        np.testing.assert_array_equal(out["ifd_student"], np.float32([ifs]))
+        np.testing.assert_array_equal(out["ifd_teacher"], np.float32([ift]))
+        np.testing.assert_array_equal(out["delta"], np.float32([d]))
+        assert out["zone"][0] == int(zone) and out["keep"][0] == int(keep) and out["keep_count"][0] == int(keep)
+
+
+def test_delta_ifd_invalid_pair_index_and_empty():
+    f32 = lambda a: torch.tensor(a, dtype=torch.float32, device=dev())
+    i32 = lambda a: torch.tensor(a, dtype=torch.int32, device=dev())
+    out = _ifd_gpu(f32([1, 2]), f32([1, 2]), i32([3, 3]), i32([0, 5, -1]), i32([1, 1, 0]), 0.0, 1.0)
+    assert out["zone"].tolist() == [1, 3, 3] and out["keep"].tolist() == [1, 0, 0] and out["keep_count"][0] == 1
+    kc = torch.full((1,), 99, dtype=torch.int32, device=dev())
+    binding.npd_delta_ifd_score(f32([1.0]), f32([1.0]), i32([1]), i32([]), i32([]), 0.0, 1.0, keep_count=kc)
+    assert kc.item() == 0
+
+
+def test_cfg3_scoring_pass_reduced(oracle):
+    """The Delta-IFD pass end to end on a reduced config 3: forward-only NLL of student and teacher logits,
+    per-sample means, Delta-IFD, zones, and the middle-80 % filter."""
+    w = synth.scaled(synth.config(3), n_rows=2, row_len=1024, vocab=32000, length_lo=16, length_hi=200)
+    w.prefix_lo, w.prefix_hi = 8, 64
+    lay = synth.make_layout(w)
+    P = len(lay.pair_cond)
+    assert P >= 6
+    _say(f"{w.name} reduced: T={w.n_tokens} V={w.vocab} pairs={P}")
+    T, V = w.n_tokens, w.vocab
+    bs, bt = synth.delta_ifd_boosts(w, lay)
+    s = torch.zeros((T, V), dtype=torch.bfloat16, device=dev())
+    t = torch.zeros((T, V), dtype=torch.bfloat16, device=dev())
+    labels = torch.from_numpy(lay.labels).to(dev())
+    synth.fill_logits(w, s, t, label_boost=(labels, torch.from_numpy(bs).to(dev()), torch.from_numpy(bt).to(dev())))
+    mask = torch.from_numpy(lay.loss_mask).to(dev())
+    cu = torch.from_numpy(lay.cu_seqlens).to(dev())
+
+    gs = run_gpu_kd(s, mask, labels=labels, want_grad=False)       # teacher kind NONE: NLL only
+    gt = run_gpu_kd(t, mask, labels=labels, want_grad=False)
+    rs = oracle.nll(_bits(s), lay.labels, lay.loss_mask)
+    rt = oracle.nll(_bits(t), lay.labels, lay.loss_mask)
+    compare_kd(dict(nll_s=gs["nll_s"], lse_s=gs["lse_s"]), dict(nll_s=rs["nll"], lse_s=rs["lse"]), lay.loss_mask,
+               lay.cu_seqlens, oracle)
+    compare_kd(dict(nll_s=gt["nll_s"]), dict(nll_s=rt["nll"]), lay.loss_mask, lay.cu_seqlens, oracle)
+
+    seg_s = _segment_gpu(torch.from_numpy(gs["nll_s"].astype(np.float32)).to(dev()), mask, cu)
+    seg_t = _segment_gpu(torch.from_numpy(gt["nll_s"].astype(np.float32)).to(dev()), mask, cu)
+    ref_s = oracle.segment_reduce(rs["nll"], lay.loss_mask, lay.cu_seqlens)
+    ref_t = oracle.segment_reduce(rt["nll"], lay.loss_mask, lay.cu_seqlens)
+    np.testing.assert_array_equal(seg_s["count"], ref_s["count"])
+    np.testing.assert_array_equal(seg_s["token_to_sample"], ref_s["token_to_sample"])
+    nz = ref_s["count"] > 0
+    assert (np.abs(seg_s["mean"][nz] - ref_s["mean"][nz]) <= REL_PER_SAMPLE * np.abs(ref_s["mean"][nz])).all()
+    assert (np.abs(seg_t["mean"][nz] - ref_t["mean"][nz]) <= REL_PER_SAMPLE * np.abs(ref_t["mean"][nz])).all()
+
+    # thresholds: the paper's fixed [0, 0.8], and the middle 80 % of the oracle's own Delta values
+    ref0 = oracle.delta_ifd(ref_s["mean"], ref_t["mean"], ref_s["count"], lay.pair_cond, lay.pair_uncond, 0.0, 0.8)
+    d_sorted = np.sort(ref0["delta"])
+    n_cut = max(1, int(round(0.1 * P)))
+    lo = float(0.5 * (d_sorted[n_cut - 1] + d_sorted[n_cut]))
+    hi = float(0.5 * (d_sorted[P - n_cut - 1] + d_sorted[P - n_cut]))
+    pc, pu = torch.from_numpy(lay.pair_cond).to(dev()), torch.from_numpy(lay.pair_uncond).to(dev())
+    for (a, b) in ((0.0, 0.8), (lo, hi)):
+        ref = oracle.delta_ifd(ref_s["mean"], ref_t["mean"], ref_s["count"], lay.pair_cond, lay.pair_uncond, a, b)
+        gpu = _ifd_gpu(seg_s["mean_dev"], seg_t["mean_dev"], seg_s["count_dev"], pc, pu, a, b)
+        np.testing.assert_allclose(gpu["delta"], ref["delta"], rtol=0, atol=2e-3)
+        np.testing.assert_allclose(gpu["ifd_student"], ref["ifd_student"], rtol=REL_PER_SAMPLE)
+        np.testing.assert_allclose(gpu["ifd_teacher"], ref["ifd_teacher"], rtol=REL_PER_SAMPLE)
+        # pairs whose Delta sits within 1e-5 of a threshold may legitimately fall on either side
+        clear = (np.abs(ref["delta"] - a) > 1e-5) & (np.abs(ref["delta"] - b) > 1e-5)
+        np.testing.assert_array_equal(gpu["zone"][clear], ref["zone"][clear])
+        np.testing.assert_array_equal(gpu["keep"][clear], ref["keep"][clear])
+        assert gpu["keep_count"][0] == int(gpu["keep"].sum())
+        if clear.all():
+            assert gpu["keep_count"][0] == ref["keep_count"]
+    assert ref["keep_count"] == P - 2 * n_cut     # the middle 80 %
+    assert len(set(ref0["zone"].tolist())) >= 2   # the synthetic IFDs do spread over more than one zone
+
+
+# --------------------------------------------------------------------------- full benchmark size, sampled rows
+
+def test_cfg1_full_size_sampled_rows(oracle):
+    """Config 1 at its real size (32,768 x 151,936, the launch bench.py times): a sample of rows is checked
+    element by element, every row through properties that hold at any size."""
+    w = synth.config(1)
+    lay, s, t, mask, labels = _inputs(w)
+    T, V = w.n_tokens, w.vocab
+    _say(f"{w.name} full size T={T} V={V}")
+    g = torch.empty((T, V), dtype=torch.bfloat16, device=dev())
+    kd = torch.empty(T, device=dev())
+    nll = torch.empty(T, device=dev())
+    tnll = torch.empty(T, device=dev())
+    status = torch.zeros(1, dtype=torch.int32, device=dev())
+    binding.npd_kd_loss_fwd_bwd(s, mask, teacher_dense=t, labels=labels, grad_out=g, kd_tok=kd, nll_tok=nll,
+                                teacher_nll_tok=tnll, dev_status=status)
+    torch.cuda.synchronize()
+    assert status.item() == 0
+    m = mask.bool()
+    assert (kd[~m] == 0).all() and (kd[m] > 0).all() and torch.isfinite(kd).all()
+    assert (nll[~m] == 0).all() and (nll[m] > 0).all()
+    # masked rows zero-filled; every gradient row sums to ~0 (bf16 rounding noise only)
+    rs = torch.empty(T, device=dev())
+    for r0 in range(0, T, 2048):
+        rs[r0:r0 + 2048] = g[r0:r0 + 2048].float().sum(1)
+    assert (rs[~m] == 0).all() and rs.abs().max().item() < 2e-2
+    rng = np.random.default_rng(5)
+    scored = np.flatnonzero(lay.loss_mask)
+    rows = np.sort(np.concatenate([rng.choice(scored, 44, replace=False), [scored[0], scored[-1]],
+                                   np.flatnonzero(lay.loss_mask == 0)[:2]]))
+    ridx = torch.from_numpy(rows).to(dev())
+    ref = oracle.kd_dense(_bits(s[ridx]), _bits(t[ridx]), lay.labels[rows], lay.loss_mask[rows])
+    gpu = dict(kd=kd[ridx].cpu().numpy().astype(np.float64), nll_s=nll[ridx].cpu().numpy().astype(np.float64),
+               nll_t=tnll[ridx].cpu().numpy().astype(np.float64), grad=g[ridx].float().cpu().numpy().astype(np.float64))
+    compare_kd(gpu, ref, lay.loss_mask[rows])
