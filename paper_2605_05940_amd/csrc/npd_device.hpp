@@ -65,14 +65,14 @@ struct Lse {
 #pragma unroll
     for (int i = 0; i < 8; ++i) z += exp2_fast(__builtin_fmaf(x[i], c, -r));
   }
-  // also accumulates a += 2^(x*c - r) * d
-  __device__ __forceinline__ void add8_cross(const float x[8], const float d[8], float c) {
+  // also accumulates a += 2^(x*c - r) * (x - y)
+  __device__ __forceinline__ void add8_cross(const float x[8], const float y[8], float c) {
     raise(max8(x) * c);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const float e = exp2_fast(__builtin_fmaf(x[i], c, -r));
       z += e;
-      a = __builtin_fmaf(e, d[i], a);
+      a = __builtin_fmaf(e, x[i] - y[i], a);
     }
   }
   __device__ __forceinline__ void add1(float x, float c) {

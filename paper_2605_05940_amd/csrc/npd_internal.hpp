@@ -34,6 +34,10 @@ struct KdArgs {
 
 hipError_t launch_kd(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream);
 
+// row-resident kernels for large vocabularies (npd_kd_cached.hip)
+bool cached_path_applies(const KdArgs& a);
+hipError_t launch_kd_cached(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream);
+
 hipError_t launch_segment_reduce(int64_t T, int32_t S, const float* values, const uint8_t* mask, const int32_t* cu,
                                  float* seg_sum, int32_t* seg_count, float* seg_mean, int32_t* token_to_sample,
                                  int32_t* status, hipStream_t stream);

@@ -70,11 +70,9 @@ __global__ __launch_bounds__(BLOCK) void kd_rows_kernel(const KdArgs a) {
     float xs[8];
     unpack8(reinterpret_cast<const uint4*>(srow)[i], xs);
     if constexpr (TEACHER == kDense) {
-      float xt[8], d[8];
+      float xt[8];
       unpack8(reinterpret_cast<const uint4*>(trow)[i], xt);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) d[j] = xt[j] - xs[j];
-      acc[1].add8_cross(xt, d, c);
+      acc[1].add8_cross(xt, xs, c);
       if (lse1_t) acc[3].add8(xt, kLog2e);
     }
     acc[0].add8(xs, c);
@@ -221,6 +219,7 @@ static hipError_t launch_teacher(const KdArgs& a, bool want_grad, hipStream_t st
 }
 
 hipError_t launch_kd(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream) {
+  if (cached_path_applies(a)) return launch_kd_cached(a, teacher_kind, want_grad && teacher_kind != kNone, stream);
   switch (teacher_kind) {
     case kDense: return launch_teacher<kDense>(a, want_grad, stream);
     case kTopk: return launch_teacher<kTopk>(a, want_grad, stream);
