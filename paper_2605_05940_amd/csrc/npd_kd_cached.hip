@@ -1,6 +1,6 @@
 // Row-resident variant of the fused KD loss + gradient kernel for large vocabularies (gfx950).
 //
-// A token row of ~150k bf16 logits (student + teacher = 608 KB) does not fit one CU, but most of it
+// One persistent workgroup per compute unit walks over token rows.  A token row of ~150k bf16 logits (student + teacher = 608 KB) does not fit one CU, but most of it
 // does: 1024 threads x CS 128-bit groups of the student row stay in VGPRs (packed bf16, as loaded),
 // the first CT groups-per-thread of the teacher row are parked in LDS, and only the remaining teacher
 // groups are read a second time -- last-read-first, so they come from the XCD's L2, not from HBM.
@@ -18,8 +18,34 @@
 namespace npd {
 
 constexpr int kCB = 1024;  // threads per workgroup: one workgroup owns a CU's whole register file
+constexpr int kGroupBytes = kCB * 16;  // one 128-bit group per thread
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Rows are addressed through buffer resources: the row base and its length live in scalar registers, a
+// thread contributes the same tid * 16 for every group and the group offset is a scalar constant, so
+// no per-group address registers or 64-bit vector adds are needed.  The hardware drops accesses past the
+// end of the row (loads return 0, stores do nothing), but its range check sees only the vector part of
+// the offset: the one group that can be ragged (the last of the CS) therefore carries its group offset in
+// the vector part (`checked`), all others -- always inside the row -- in the scalar part.
+// The resource spans the whole 128-bit groups of a row only: a lane of the ragged group that has no whole
+// group left is out of range as a whole (the sub-group tail is handled element-wise).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t row_rsrc(const uint16_t* row, int nvec) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(row), 0, nvec * 16, 0x00020000);
+}
+__device__ __forceinline__ uint4 ld_group(__amdgpu_buffer_rsrc_t r, int voff, int it, bool checked) {
+  const u32x4 v = checked ? __builtin_amdgcn_raw_buffer_load_b128(r, voff + it * kGroupBytes, 0, 0)
+                          : __builtin_amdgcn_raw_buffer_load_b128(r, voff, it * kGroupBytes, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void st_group_stream(__amdgpu_buffer_rsrc_t r, int voff, int it, bool checked,
+                                                const uint4& v) {
+  const u32x4 w = {v.x, v.y, v.z, v.w};
+  if (checked)
+    __builtin_amdgcn_raw_buffer_store_b128(w, r, voff + it * kGroupBytes, 0, 2);  // 2 = non-temporal
+  else
+    __builtin_amdgcn_raw_buffer_store_b128(w, r, voff, it * kGroupBytes, 2);
+}
 
 __device__ __forceinline__ uint4 ld16(const uint16_t* row, int group) {
   return reinterpret_cast<const uint4*>(row)[group];
@@ -80,219 +106,273 @@ __device__ __forceinline__ void accum8(const uint4& vs, const uint4& vt, float c
   if constexpr (LSE1) acc[2].add8(xs, kLog2e);
 }
 
-template <int CS, int CT, int D, int TEACHER, bool GRAD, bool LSE1>
+template <int CS, int CSR, int CT, int D, int TEACHER, bool GRAD, bool LSE1, bool PERSIST>
 __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
-  extern __shared__ uint4 lds_t[];  // [CT][1024] teacher groups (dense teacher)
+  // teacher groups parked for sweep 2, [1024][CT]: a thread's CT groups are contiguous, so one base register
+  // plus an immediate offset addresses them all; the 16 * CT byte lane stride (144 B) is conflict-free for
+  // 128-bit LDS accesses
+  extern __shared__ uint4 lds_t[];
   __shared__ float red[4 * 3 * (kCB / kWave)];
   __shared__ uint16_t patch[TEACHER == kTopk && GRAD ? kTopkMax : 1];
-  static_assert(CT <= CS && D >= 1 && D <= CS, "bad cache shape");
+  static_assert(CT <= CS && CSR <= CS && D >= 1 && D <= CS, "bad cache shape");
   const int tid = threadIdx.x;
-  const int64_t row = blockIdx.x;
-  const int V = a.V, nvec = a.nvec_s;  // this kernel is only launched with 16-byte aligned rows: nvec = V / 8
-  uint16_t* grow = GRAD ? a.g + row * a.s_stride : nullptr;
-
-  if (!a.mask[row]) {
-    if (tid == 0) {
-      if (a.kd) a.kd[row] = 0.0f;
-      if (a.nll) a.nll[row] = 0.0f;
-      if (a.tnll) a.tnll[row] = 0.0f;
-      if (a.lse) a.lse[row] = 0.0f;
-    }
-    if constexpr (GRAD) {
-      const uint4 z = make_uint4(0, 0, 0, 0);
-      for (int i = tid; i < nvec; i += kCB) st16_stream(grow, i, z);
-      for (int e = nvec * 8 + tid; e < V; e += kCB) grow[e] = 0;
-    }
-    return;
-  }
-
-  const uint16_t* srow = a.s + row * a.s_stride;
-  const uint16_t* trow = TEACHER == kDense ? a.t + row * a.t_stride : nullptr;
+  const int voff = tid * 16;
+  const int V = a.V, nvec = a.nvec_s;  // only launched with 16-byte aligned rows: nvec = V / 8
+  const int64_t T = a.T;
+  const int64_t G = gridDim.x;
   const float c = a.c;
   const bool lse1_t = LSE1 && a.tnll != nullptr;
-  // launched only for rows of more than (CS - 1) * 1024 groups: every cached group is full except,
-  // when the row has at most CS * 1024 groups, the last one
+  // launched only for rows of more than (CS - 1) * 1024 groups: every one of the first CS groups per
+  // thread is full except, when the row has at most CS * 1024 groups, the last one
   const int nit = (nvec + kCB - 1) / kCB;  // 128-bit groups per thread
 
-  int y = -1;
-  float s_y = 0.0f, t_y = 0.0f;
-  if (a.labels) {
-    y = a.labels[row];
-    if ((unsigned)y < (unsigned)V) {
-      s_y = bf16_one(srow[y]);
-      if (TEACHER == kDense) t_y = bf16_one(trow[y]);
+  // A persistent workgroup owns rows blockIdx.x, blockIdx.x + G, ...; rows that are not scored are dealt
+  // with on the way (scalars 0, gradient row zero-filled, logits never read).
+  auto next_scored = [&](int64_t r) -> int64_t {
+    while (r < T && !a.mask[r]) {
+      if (tid == 0) {
+        if (a.kd) a.kd[r] = 0.0f;
+        if (a.nll) a.nll[r] = 0.0f;
+        if (a.tnll) a.tnll[r] = 0.0f;
+        if (a.lse) a.lse[r] = 0.0f;
+      }
+      if constexpr (GRAD) {
+        uint16_t* grow0 = a.g + r * a.s_stride;
+        const uint4 z = make_uint4(0, 0, 0, 0);
+        for (int i = tid; i < nvec; i += kCB) st16_stream(grow0, i, z);
+        for (int e = nvec * 8 + tid; e < V; e += kCB) grow0[e] = 0;
+      }
+      r += G;
     }
-  }
+    return r;
+  };
 
-  constexpr int NS = LSE1 ? 4 : 2;  // 0 student / tau, 1 teacher / tau (+ cross), 2 student tau = 1, 3 teacher tau = 1
-  Lse acc[NS];
+  uint4 sreg[CSR > 0 ? CSR : 1];  // the first CSR groups of the student row, as loaded (packed bf16)
+  uint4 sst[D], tst[D];           // student groups beyond CSR / teacher groups in flight
+  auto request_student = [&](__amdgpu_buffer_rsrc_t rs) {
 #pragma unroll
-  for (int i = 0; i < NS; ++i) acc[i].init();
+    for (int it = 0; it < CSR; ++it) sreg[it] = ld_group(rs, voff, it, (it) == CS - 1);
+  };
 
-  uint4 sreg[CS];  // the student row, as loaded
-  uint4 tst[D];    // teacher groups in flight
-  const int last = nvec - 1;
-  // out-of-row lanes of the ragged group load the row's last group (in bounds) and are skipped in compute
+  int64_t row = next_scored(blockIdx.x);
+  if (PERSIST && row < T) request_student(row_rsrc(a.s + row * a.s_stride, nvec));
 
-  // ---- sweep 1, cached part: request D groups ahead
-#pragma unroll
-  for (int d = 0; d < D; ++d) {
-    const int i = min(d * kCB + tid, last);
-    sreg[d] = ld16(srow, i);
-    if constexpr (TEACHER == kDense) tst[d] = ld16(trow, i);
-  }
-#pragma unroll
-  for (int it = 0; it < CS; ++it) {
-    const uint4 vt = TEACHER == kDense ? tst[it % D] : make_uint4(0, 0, 0, 0);
-    if (it + D < CS) {
-      const int nx = it + D < CS ? it + D : 0;  // constant once the loop is unrolled
-      const int i = min(nx * kCB + tid, last);
-      sreg[nx] = ld16(srow, i);
-      if constexpr (TEACHER == kDense) tst[it % D] = ld16(trow, i);
-    }
-    if (it < CS - 1 || it * kCB + tid < nvec) accum8<TEACHER, LSE1>(sreg[it], vt, c, lse1_t, acc);
-    if constexpr (TEACHER == kDense)
-      if (it < CT) lds_t[it * kCB + tid] = vt;
-    __builtin_amdgcn_sched_barrier(0);  // keep the instruction scheduler from piling all loads up front
-  }
-  // ---- sweep 1, streamed part (rows longer than the cache) and the sub-group tail
-  for (int i = CS * kCB + tid; i < nvec; i += kCB) {
-    const uint4 vs = ld16(srow, i);
-    const uint4 vt = TEACHER == kDense ? ld16(trow, i) : make_uint4(0, 0, 0, 0);
-    accum8<TEACHER, LSE1>(vs, vt, c, lse1_t, acc);
-  }
-  for (int e = nvec * 8 + tid; e < V; e += kCB) {
-    const float xs = bf16_one(srow[e]);
-    if constexpr (TEACHER == kDense) {
-      const float xt = bf16_one(trow[e]);
-      acc[1].add1_cross(xt, xt - xs, c);
-      if constexpr (LSE1)
-        if (lse1_t) acc[3].add1(xt, kLog2e);
-    }
-    acc[0].add1(xs, c);
-    if constexpr (LSE1) acc[2].add1(xs, kLog2e);
-  }
-  int bad_index = 0;
-  if constexpr (TEACHER == kTopk) {
-    const int32_t* irow = a.tidx + row * (int64_t)a.k;
-    const float* vrow = a.tval + row * (int64_t)a.k;
-    for (int j = tid; j < a.k; j += kCB) {
-      if ((unsigned)irow[j] >= (unsigned)V) bad_index = 1;
-      acc[1].add1(vrow[j], c);
-    }
-  }
+  while (row < T) {
+    const int64_t nrow = PERSIST ? next_scored(row + G) : T;
+    const uint16_t* srow = a.s + row * a.s_stride;
+    const uint16_t* trow = TEACHER == kDense ? a.t + row * a.t_stride : nullptr;
+    uint16_t* grow = GRAD ? a.g + row * a.s_stride : nullptr;
+    const __amdgpu_buffer_rsrc_t rs = row_rsrc(srow, nvec);
+    const __amdgpu_buffer_rsrc_t rt = row_rsrc(TEACHER == kDense ? trow : srow, nvec);
+    const __amdgpu_buffer_rsrc_t rg = row_rsrc(GRAD ? grow : srow, nvec);
+    // the student row to request while this row's gradient is written (this row again if it is the last)
+    const __amdgpu_buffer_rsrc_t rnext = row_rsrc(a.s + (nrow < T ? nrow : row) * a.s_stride, nvec);
 
-  // teacher groups that were not parked in LDS are requested again now, newest first; the first D of
-  // them travel while the partial sums are merged
-  constexpr int NRE = (TEACHER == kDense && GRAD) ? CS - CT : 0;  // re-read groups per thread (at most)
-  if constexpr (NRE > 0) {
-#pragma unroll
-    for (int d = 0; d < D && d < NRE; ++d) tst[d] = ld16(trow, min((CS - 1 - d) * kCB + tid, last));
-  }
-
-  block_merge<kCB, NS>(acc, red);
-
-  const float Ls = acc[0].log2_sum();
-  const float Lt = TEACHER == kNone ? 0.0f : acc[1].log2_sum();
-  const float lse1_s = __fmul_rn(LSE1 ? acc[NS - 2].log2_sum() : Ls, kLn2);
-  float kd = 0.0f;
-  if constexpr (TEACHER == kDense) {
-    kd = (acc[1].a / acc[1].z) * a.inv_tau + ((acc[0].r - acc[1].r) + (acc[0].log2_z() - acc[1].log2_z())) * kLn2;
-    kd = kd < 0.0f ? 0.0f : kd;
-  }
-  if constexpr (TEACHER == kTopk) {
-    bad_index = __syncthreads_or(bad_index);
-    const int32_t* irow = a.tidx + row * (int64_t)a.k;
-    const float* vrow = a.tval + row * (int64_t)a.k;
-    const float ws = a.gscale / acc[0].z, ratio = acc[0].z / acc[1].z;
-    float part = 0.0f;
-    if (!bad_index) {
-      for (int j = tid; j < a.k; j += kCB) {
-        const float b = vrow[j] * c;
-        const float sj = bf16_one(srow[irow[j]]);
-        const float lpt = b - Lt;
-        const float lps = __builtin_fmaf(sj, c, -Ls);
-        part = __builtin_fmaf(exp2_fast(lpt), (lpt - lps) * kLn2, part);
-        if constexpr (GRAD) {
-          const float gj =
-              __builtin_fmaf(-exp2_fast(b - acc[1].r), ratio, exp2_fast(__builtin_fmaf(sj, c, -acc[0].r))) * ws;
-          patch[j] = one_bf16(gj);
-        }
+    int y = -1;
+    float s_y = 0.0f, t_y = 0.0f;
+    if (a.labels) {  // label logits are fetched before an in-place gradient can overwrite them
+      y = a.labels[row];
+      if ((unsigned)y < (unsigned)V) {
+        s_y = bf16_one(srow[y]);
+        if (TEACHER == kDense) t_y = bf16_one(trow[y]);
       }
     }
-    kd = block_sum<kCB>(part, red);
-    kd = kd < 0.0f ? 0.0f : kd;
-    if (bad_index) kd = __builtin_nanf("");
-  }
 
-  if (tid == 0) {
-    int flags = 0;
-    if (bad_index) flags |= 2;
-    const bool bad_label = a.labels && (unsigned)y >= (unsigned)V;
-    if (bad_label && (a.nll || a.tnll)) flags |= 1;
-    if (a.kd) a.kd[row] = kd;
-    if (a.nll) a.nll[row] = bad_label ? __builtin_nanf("") : __fsub_rn(lse1_s, s_y);
-    if (TEACHER == kDense && a.tnll) {
-      const float lse1_tt = __fmul_rn(LSE1 ? acc[NS - 1].log2_sum() : Lt, kLn2);
-      a.tnll[row] = bad_label ? __builtin_nanf("") : __fsub_rn(lse1_tt, t_y);
-    }
-    if (a.lse) a.lse[row] = lse1_s;
-    if (flags && a.status) atomicOr(a.status, flags);
-  }
+    constexpr int NS = LSE1 ? 4 : 2;  // 0 student / tau, 1 teacher / tau (+ cross), 2 student tau = 1, 3 teacher tau = 1
+    Lse acc[NS];
+#pragma unroll
+    for (int i = 0; i < NS; ++i) acc[i].init();
 
-  // ---- sweep 2
-  if constexpr (GRAD) {
-    Sweep2Coef k;
-    k.c = c;
-    k.rs = acc[0].r;
-    k.rt = acc[1].r;
-    k.ws = a.gscale / acc[0].z;
-    k.ratio = TEACHER == kDense ? acc[0].z / acc[1].z : 0.0f;
-    if (TEACHER == kTopk && bad_index) {
-      const uint16_t qnan = 0x7fc0;
-      for (int e = tid; e < V; e += kCB) grow[e] = qnan;
-      return;
+    // ---- sweep 1, first CS groups per thread: the register-resident student groups are requested first
+    // (or already were, during the previous row); the other student groups and the teacher groups are
+    // requested D ahead of their use
+    if constexpr (!PERSIST) request_student(rs);
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+      if constexpr (TEACHER == kDense) tst[d] = ld_group(rt, voff, d, (d) == CS - 1);
+      if (d >= CSR) sst[d] = ld_group(rs, voff, d, (d) == CS - 1);
     }
-    // sub-group tail and streamed part first (most recently read), then the cached groups backwards
-    for (int e = nvec * 8 + tid; e < V; e += kCB) {
-      float gv = exp2_fast(__builtin_fmaf(bf16_one(srow[e]), c, -k.rs));
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int it = 0; it < CS; ++it) {
+      const uint4 vs = it < CSR ? sreg[it < CSR ? it : 0] : sst[it % D];
+      const uint4 vt = TEACHER == kDense ? tst[it % D] : make_uint4(0, 0, 0, 0);
+      if (it + D < CS) {
+        if constexpr (TEACHER == kDense) tst[it % D] = ld_group(rt, voff, it + D, (it + D) == CS - 1);
+        if (it + D >= CSR) sst[it % D] = ld_group(rs, voff, it + D, (it + D) == CS - 1);
+      }
+      if (it < CS - 1 || it * kCB + tid < nvec) accum8<TEACHER, LSE1>(vs, vt, c, lse1_t, acc);
       if constexpr (TEACHER == kDense)
-        gv = __builtin_fmaf(-exp2_fast(__builtin_fmaf(bf16_one(trow[e]), c, -k.rt)), k.ratio, gv);
-      grow[e] = one_bf16(gv * k.ws);
+        if (it < CT) lds_t[tid * CT + it] = vt;
+      __builtin_amdgcn_sched_barrier(0);  // keep the instruction scheduler from piling all loads up front
     }
-    for (int i = (nit - 1) * kCB + tid; i >= CS * kCB; i -= kCB) {
-      if (i < nvec) {
-        const uint4 vs = ld16(srow, i);
-        const uint4 vt = TEACHER == kDense ? ld16(trow, i) : make_uint4(0, 0, 0, 0);
-        st16_stream(grow, i, grad8<TEACHER>(vs, vt, k));
-      }
+    // ---- sweep 1, streamed part (rows longer than the cache) and the sub-group tail
+    for (int i = CS * kCB + tid; i < nvec; i += kCB) {
+      const uint4 vs = ld16(srow, i);
+      const uint4 vt = TEACHER == kDense ? ld16(trow, i) : make_uint4(0, 0, 0, 0);
+      accum8<TEACHER, LSE1>(vs, vt, c, lse1_t, acc);
     }
-#pragma unroll
-    for (int q = 0; q < CS; ++q) {
-      const int it = CS - 1 - q;
-      uint4 vt = make_uint4(0, 0, 0, 0);
+    for (int e = nvec * 8 + tid; e < V; e += kCB) {
+      const float xs = bf16_one(srow[e]);
       if constexpr (TEACHER == kDense) {
-        if (it < CT) {
-          vt = lds_t[it * kCB + tid];
-        } else {
-          vt = tst[q % D];  // requested D visits ago
-          if (it - D >= CT) tst[q % D] = ld16(trow, (it - D) * kCB + tid);
-        }
+        const float xt = bf16_one(trow[e]);
+        acc[1].add1_cross(xt, xt - xs, c);
+        if constexpr (LSE1)
+          if (lse1_t) acc[3].add1(xt, kLog2e);
       }
-      const int i = it * kCB + tid;
-      opaque(sreg[it]);
-      if (it < CS - 1 || i < nvec) st16_stream(grow, i, grad8<TEACHER>(sreg[it], vt, k));
-      __builtin_amdgcn_sched_barrier(0);
+      acc[0].add1(xs, c);
+      if constexpr (LSE1) acc[2].add1(xs, kLog2e);
+    }
+    int bad_index = 0;
+    if constexpr (TEACHER == kTopk) {
+      const int32_t* irow = a.tidx + row * (int64_t)a.k;
+      const float* vrow = a.tval + row * (int64_t)a.k;
+      for (int j = tid; j < a.k; j += kCB) {
+        if ((unsigned)irow[j] >= (unsigned)V) bad_index = 1;
+        acc[1].add1(vrow[j], c);
+      }
+    }
+
+    // groups that are neither in registers nor in LDS are requested a second time, newest first (they are
+    // still in cache); the first D of them travel while the partial sums are merged
+    if constexpr (GRAD) {
+#pragma unroll
+      for (int d = 0; d < D; ++d) {
+        const int it = CS - 1 - d;
+        if (TEACHER == kDense && it >= CT) tst[d] = ld_group(rt, voff, it, (it) == CS - 1);
+        if (it >= CSR) sst[d] = ld_group(rs, voff, it, (it) == CS - 1);
+      }
+    }
+
+    block_merge<kCB, NS>(acc, red);
+
+    const float Ls = acc[0].log2_sum();
+    const float Lt = TEACHER == kNone ? 0.0f : acc[1].log2_sum();
+    const float lse1_s = __fmul_rn(LSE1 ? acc[NS - 2].log2_sum() : Ls, kLn2);
+    float kd = 0.0f;
+    if constexpr (TEACHER == kDense) {
+      kd = (acc[1].a / acc[1].z) * a.inv_tau + ((acc[0].r - acc[1].r) + (acc[0].log2_z() - acc[1].log2_z())) * kLn2;
+      kd = kd < 0.0f ? 0.0f : kd;
     }
     if constexpr (TEACHER == kTopk) {
-      __syncthreads();
+      bad_index = __syncthreads_or(bad_index);
       const int32_t* irow = a.tidx + row * (int64_t)a.k;
-      for (int j = tid; j < a.k; j += kCB) grow[irow[j]] = patch[j];
+      const float* vrow = a.tval + row * (int64_t)a.k;
+      const float ws = a.gscale / acc[0].z, ratio = acc[0].z / acc[1].z;
+      float part = 0.0f;
+      if (!bad_index) {
+        for (int j = tid; j < a.k; j += kCB) {
+          const float b = vrow[j] * c;
+          const float sj = bf16_one(srow[irow[j]]);
+          const float lpt = b - Lt;
+          const float lps = __builtin_fmaf(sj, c, -Ls);
+          part = __builtin_fmaf(exp2_fast(lpt), (lpt - lps) * kLn2, part);
+          if constexpr (GRAD) {
+            const float gj =
+                __builtin_fmaf(-exp2_fast(b - acc[1].r), ratio, exp2_fast(__builtin_fmaf(sj, c, -acc[0].r))) * ws;
+            patch[j] = one_bf16(gj);
+          }
+        }
+      }
+      kd = block_sum<kCB>(part, red);
+      kd = kd < 0.0f ? 0.0f : kd;
+      if (bad_index) kd = __builtin_nanf("");
     }
+
+    if (tid == 0) {
+      int flags = 0;
+      if (bad_index) flags |= 2;
+      const bool bad_label = a.labels && (unsigned)y >= (unsigned)V;
+      if (bad_label && (a.nll || a.tnll)) flags |= 1;
+      if (a.kd) a.kd[row] = kd;
+      if (a.nll) a.nll[row] = bad_label ? __builtin_nanf("") : __fsub_rn(lse1_s, s_y);
+      if (TEACHER == kDense && a.tnll) {
+        const float lse1_tt = __fmul_rn(LSE1 ? acc[NS - 1].log2_sum() : Lt, kLn2);
+        a.tnll[row] = bad_label ? __builtin_nanf("") : __fsub_rn(lse1_tt, t_y);
+      }
+      if (a.lse) a.lse[row] = lse1_s;
+      if (flags && a.status) atomicOr(a.status, flags);
+    }
+
+    // ---- sweep 2
+    if constexpr (GRAD) {
+      Sweep2Coef k;
+      k.c = c;
+      k.rs = acc[0].r;
+      k.rt = acc[1].r;
+      k.ws = a.gscale / acc[0].z;
+      k.ratio = TEACHER == kDense ? acc[0].z / acc[1].z : 0.0f;
+      if (TEACHER == kTopk && bad_index) {  // uniform
+        const uint16_t qnan = 0x7fc0;
+        for (int e = tid; e < V; e += kCB) grow[e] = qnan;
+        if constexpr (PERSIST) request_student(rnext);
+      } else {
+        // sub-group tail and streamed part first (read most recently), then the first CS groups backwards
+        for (int e = nvec * 8 + tid; e < V; e += kCB) {
+          float gv = exp2_fast(__builtin_fmaf(bf16_one(srow[e]), c, -k.rs));
+          if constexpr (TEACHER == kDense)
+            gv = __builtin_fmaf(-exp2_fast(__builtin_fmaf(bf16_one(trow[e]), c, -k.rt)), k.ratio, gv);
+          grow[e] = one_bf16(gv * k.ws);
+        }
+        for (int i = (nit - 1) * kCB + tid; i >= CS * kCB; i -= kCB) {
+          if (i < nvec) {
+            const uint4 vs = ld16(srow, i);
+            const uint4 vt = TEACHER == kDense ? ld16(trow, i) : make_uint4(0, 0, 0, 0);
+            st16_stream(grow, i, grad8<TEACHER>(vs, vt, k));
+          }
+        }
+        // a register-resident student group makes room, once used, for the same group of the next row
+#pragma unroll
+        for (int q = 0; q < CS; ++q) {
+          const int it = CS - 1 - q;
+          uint4 vs, vt = make_uint4(0, 0, 0, 0);
+          if (it < CSR) {
+            opaque(sreg[it < CSR ? it : 0]);
+            vs = sreg[it < CSR ? it : 0];
+          } else {
+            vs = sst[q % D];  // requested D visits ago
+            if (it - D >= CSR) sst[q % D] = ld_group(rs, voff, it - D, (it - D) == CS - 1);
+          }
+          if constexpr (TEACHER == kDense) {
+            if (it < CT) {
+              vt = lds_t[tid * CT + it];
+            } else {
+              vt = tst[q % D];
+              if (it - D >= CT) tst[q % D] = ld_group(rt, voff, it - D, (it - D) == CS - 1);
+            }
+          }
+          {
+            const uint4 gq = grad8<TEACHER>(vs, vt, k);
+            if (it < CS - 1 || it * kCB + tid < nvec) st16_stream(grow, it * kCB + tid, gq);
+          }
+          if (PERSIST && it < CSR) sreg[it < CSR ? it : 0] = ld_group(rnext, voff, it, (it) == CS - 1);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (TEACHER == kTopk) {
+          __syncthreads();
+          const int32_t* irow = a.tidx + row * (int64_t)a.k;
+          for (int j = tid; j < a.k; j += kCB) grow[irow[j]] = patch[j];
+        }
+      }
+    }
+    row = nrow;
   }
 }
 
-template <int CS, int CT, int D, int TEACHER, bool GRAD>
+// compute units of the current device (queried once per device, no allocation)
+static int compute_units() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
+template <int CS, int CSR, int CT, int D, int TEACHER, bool GRAD, bool PERSIST>
 static hipError_t launch_cached_lse1(const KdArgs& a, hipStream_t stream) {
   const size_t lds_bytes = (size_t)CT * kCB * sizeof(uint4);
   auto launch = [&](auto kernel) -> hipError_t {
@@ -301,13 +381,25 @@ static hipError_t launch_cached_lse1(const KdArgs& a, hipStream_t stream) {
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
       if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kernel, dim3((unsigned)a.T), dim3(kCB), lds_bytes, stream, a);
+    // persistent: one workgroup per compute unit (a workgroup takes a CU's whole register file)
+    const int64_t cus = compute_units();
+    const unsigned grid = (unsigned)(!PERSIST || a.T < cus ? a.T : cus);
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kCB), lds_bytes, stream, a);
     return hipGetLastError();
   };
-  if (a.need_lse1) return launch(kd_cached_kernel<CS, CT, D, TEACHER, GRAD, true>);
-  return launch(kd_cached_kernel<CS, CT, D, TEACHER, GRAD, false>);
+  if (a.need_lse1) return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, true, PERSIST>);
+  return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, false, PERSIST>);
 }
 
+#ifndef NPD_CSR
+#define NPD_CSR 16
+#endif
+#ifndef NPD_TD
+#define NPD_TD 2
+#endif
+#ifndef NPD_PERSIST
+#define NPD_PERSIST false
+#endif
 constexpr int kCachedGroups = 19;  // covers vocabularies of 147,464 .. 155,648 tokens entirely, larger ones partly
 
 // Row-resident path: 16-byte aligned rows of more than (kCachedGroups - 1) * 1024 groups.
@@ -316,13 +408,13 @@ bool cached_path_applies(const KdArgs& a) { return a.nvec_s > (kCachedGroups - 1
 hipError_t launch_kd_cached(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream) {
   switch (teacher_kind) {
     case kDense:
-      return want_grad ? launch_cached_lse1<kCachedGroups, 9, 2, kDense, true>(a, stream)
-                       : launch_cached_lse1<kCachedGroups, 0, 3, kDense, false>(a, stream);
+      return want_grad ? launch_cached_lse1<kCachedGroups, NPD_CSR, 9, NPD_TD, kDense, true, NPD_PERSIST>(a, stream)
+                       : launch_cached_lse1<kCachedGroups, 0, 0, 4, kDense, false, false>(a, stream);
     case kTopk:
-      return want_grad ? launch_cached_lse1<kCachedGroups, 0, 3, kTopk, true>(a, stream)
-                       : launch_cached_lse1<kCachedGroups, 0, 3, kTopk, false>(a, stream);
+      return want_grad ? launch_cached_lse1<kCachedGroups, 16, 0, 3, kTopk, true, false>(a, stream)
+                       : launch_cached_lse1<kCachedGroups, 0, 0, 4, kTopk, false, false>(a, stream);
     default:
-      return launch_cached_lse1<kCachedGroups, 0, 3, kNone, false>(a, stream);
+      return launch_cached_lse1<kCachedGroups, 0, 0, 4, kNone, false, false>(a, stream);
   }
 }
 
