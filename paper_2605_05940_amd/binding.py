@@ -11,7 +11,8 @@ from typing import Optional
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libnpd.so")
+# NPD_LIB_PATH overrides the in-tree library (e.g. to try a differently tuned build)
+LIB_PATH = os.environ.get("NPD_LIB_PATH") or os.path.join(HERE, "libnpd.so")
 
 NPD_TEACHER_DENSE_BF16, NPD_TEACHER_TOPK, NPD_TEACHER_NONE = 0, 1, 2
 NPD_FLAG_FWD_ONLY, NPD_FLAG_INPLACE_GRAD = 1, 2

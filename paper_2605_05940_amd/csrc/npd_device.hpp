@@ -40,24 +40,36 @@ __device__ __forceinline__ void unpack8(const uint4& v, float x[8]) {
   x[6] = bf16_lo(v.w); x[7] = bf16_hi(v.w);
 }
 
+// v_max3_f32 without the input canonicalisation the compiler adds around fmaxf (the values come straight
+// from bf16 bit patterns; a NaN among them simply propagates into the sums)
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float d;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+  return d;
+}
 __device__ __forceinline__ float max8(const float x[8]) {
-  float m = fmaxf(fmaxf(x[0], x[1]), x[2]);
-  m = fmaxf(fmaxf(m, x[3]), x[4]);
-  m = fmaxf(fmaxf(m, x[5]), x[6]);
-  return fmaxf(m, x[7]);
+  float m = max3(x[0], x[1], x[2]);
+  m = max3(m, x[3], x[4]);
+  m = max3(m, x[5], x[6]);
+  return max3(m, x[7], x[7]);
 }
 
 // Partial log-sum-exp with an optional cross term.
 struct Lse {
   float r, z, a;
   __device__ __forceinline__ void init() { r = -INFINITY; z = 0.0f; a = 0.0f; }
-  // raise the reference to `u` if it lags by more than the slack (also the first touch: r = -inf)
+  // raise the reference to `u` if it lags by more than the slack (also the first touch: r = -inf).
+  // The outer test is wave-uniform, so the common case is one compare and a scalar branch not taken.
   __device__ __forceinline__ void raise(float u) {
-    if (u > r + kRefSlack) {
-      const float f = exp2_fast(r - u);  // r = -inf gives 0
-      z *= f;
-      a *= f;
-      r = u;
+    const bool lag = u > r + kRefSlack;
+    if (__builtin_amdgcn_ballot_w64(lag) != 0) {
+      asm volatile("");  // not speculatable: keeps this rare path behind a real branch
+      if (lag) {
+        const float f = exp2_fast(r - u);  // r = -inf gives 0
+        z *= f;
+        a *= f;
+        r = u;
+      }
     }
   }
   __device__ __forceinline__ void add8(const float x[8], float c) {

@@ -61,31 +61,71 @@ __device__ __forceinline__ void opaque(uint4& v) {
   asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w));
 }
 
+// Sweep-2 coefficients.  Precise form: grad = (e_S - e_T z_S / z_T) w with e = 2^(x c - r).  Folded form:
+// |grad_scale| / (tau z) goes into the exponent, grad = +-(2^(x c - fs) - 2^(x c - ft)), one instruction less
+// per element; it is used only while |fs|, |ft| < 1024, where rounding fs, ft to fp32 moves a probability by
+// less than 2.2e-5 of itself (rows with logits in the thousands take the precise form).
 struct Sweep2Coef {
-  float c, rs, rt, ratio, ws;
+  float c, rs, rt, ratio, ws;  // precise form
+  float fs, ft;                // folded form
+  uint32_t sign;               // 0x80008000 when grad_scale < 0 (folded form)
+  bool folded;                 // uniform
 };
 
-// gradient of 8 elements: (e_S - e_T z_S / z_T) w
-template <int TEACHER>
+__device__ __forceinline__ Sweep2Coef sweep2_coef(const Lse& S, const Lse& Tt, float c, float gscale, bool dense) {
+  Sweep2Coef k;
+  k.c = c;
+  k.rs = S.r;
+  k.rt = Tt.r;
+  k.ws = gscale / S.z;
+  k.ratio = dense ? S.z / Tt.z : 0.0f;
+  const float lg = __log2f(fabsf(gscale));  // -inf for a zero scale: every term becomes 2^-inf = 0
+  k.fs = S.r + (S.log2_z() - lg);
+  k.ft = dense ? Tt.r + (Tt.log2_z() - lg) : 0.0f;
+  k.sign = gscale < 0.0f ? 0x80008000u : 0u;
+  k.folded = fabsf(k.fs) < 1024.0f && fabsf(k.ft) < 1024.0f;
+  if (gscale == 0.0f) k.folded = true;
+  return k;
+}
+
+// gradient of 8 elements
+template <int TEACHER, bool FOLDED>
 __device__ __forceinline__ uint4 grad8(const uint4& vs, const uint4& vt, const Sweep2Coef& k) {
   float xs[8], gv[8];
   unpack8(vs, xs);
   if constexpr (TEACHER == kDense) {
     float xt[8];
     unpack8(vt, xt);
+    if constexpr (FOLDED) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
-      gv[j] = __builtin_fmaf(-exp2_fast(__builtin_fmaf(xt[j], k.c, -k.rt)), k.ratio,
-                             exp2_fast(__builtin_fmaf(xs[j], k.c, -k.rs))) * k.ws;
+      for (int j = 0; j < 8; ++j)
+        gv[j] = exp2_fast(__builtin_fmaf(xs[j], k.c, -k.fs)) - exp2_fast(__builtin_fmaf(xt[j], k.c, -k.ft));
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        gv[j] = __builtin_fmaf(-exp2_fast(__builtin_fmaf(xt[j], k.c, -k.rt)), k.ratio,
+                               exp2_fast(__builtin_fmaf(xs[j], k.c, -k.rs))) * k.ws;
+    }
   } else {
+    if constexpr (FOLDED) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) gv[j] = exp2_fast(__builtin_fmaf(xs[j], k.c, -k.rs)) * k.ws;
+      for (int j = 0; j < 8; ++j) gv[j] = exp2_fast(__builtin_fmaf(xs[j], k.c, -k.fs));
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) gv[j] = exp2_fast(__builtin_fmaf(xs[j], k.c, -k.rs)) * k.ws;
+    }
   }
   uint4 o;
   o.x = pack_bf16(gv[0], gv[1]);
   o.y = pack_bf16(gv[2], gv[3]);
   o.z = pack_bf16(gv[4], gv[5]);
   o.w = pack_bf16(gv[6], gv[7]);
+  if constexpr (FOLDED) {
+    o.x ^= k.sign;
+    o.y ^= k.sign;
+    o.z ^= k.sign;
+    o.w ^= k.sign;
+  }
   return o;
 }
 
@@ -296,12 +336,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
 
     // ---- sweep 2
     if constexpr (GRAD) {
-      Sweep2Coef k;
-      k.c = c;
-      k.rs = acc[0].r;
-      k.rt = acc[1].r;
-      k.ws = a.gscale / acc[0].z;
-      k.ratio = TEACHER == kDense ? acc[0].z / acc[1].z : 0.0f;
+      const Sweep2Coef k = sweep2_coef(acc[0], acc[1], c, a.gscale, TEACHER == kDense);
       if (TEACHER == kTopk && bad_index) {  // uniform
         const uint16_t qnan = 0x7fc0;
         for (int e = tid; e < V; e += kCB) grow[e] = qnan;
@@ -318,35 +353,47 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
           if (i < nvec) {
             const uint4 vs = ld16(srow, i);
             const uint4 vt = TEACHER == kDense ? ld16(trow, i) : make_uint4(0, 0, 0, 0);
-            st16_stream(grow, i, grad8<TEACHER>(vs, vt, k));
+            st16_stream(grow, i, grad8<TEACHER, false>(vs, vt, k));
           }
         }
-        // a register-resident student group makes room, once used, for the same group of the next row
+        if (k.folded) {  // uniform
+          // a register-resident student group makes room, once used, for the same group of the next row
 #pragma unroll
-        for (int q = 0; q < CS; ++q) {
-          const int it = CS - 1 - q;
-          uint4 vs, vt = make_uint4(0, 0, 0, 0);
-          if (it < CSR) {
-            opaque(sreg[it < CSR ? it : 0]);
-            vs = sreg[it < CSR ? it : 0];
-          } else {
-            vs = sst[q % D];  // requested D visits ago
-            if (it - D >= CSR) sst[q % D] = ld_group(rs, voff, it - D, (it - D) == CS - 1);
-          }
-          if constexpr (TEACHER == kDense) {
-            if (it < CT) {
-              vt = lds_t[tid * CT + it];
+          for (int q = 0; q < CS; ++q) {
+            const int it = CS - 1 - q;
+            uint4 vs, vt = make_uint4(0, 0, 0, 0);
+            if (it < CSR) {
+              opaque(sreg[it < CSR ? it : 0]);
+              vs = sreg[it < CSR ? it : 0];
             } else {
-              vt = tst[q % D];
-              if (it - D >= CT) tst[q % D] = ld_group(rt, voff, it - D, (it - D) == CS - 1);
+              vs = sst[q % D];  // requested D visits ago
+              if (it - D >= CSR) sst[q % D] = ld_group(rs, voff, it - D, (it - D) == CS - 1);
+            }
+            if constexpr (TEACHER == kDense) {
+              if (it < CT) {
+                vt = lds_t[tid * CT + it];
+              } else {
+                vt = tst[q % D];
+                if (it - D >= CT) tst[q % D] = ld_group(rt, voff, it - D, (it - D) == CS - 1);
+              }
+            }
+            {
+              const uint4 gq = grad8<TEACHER, true>(vs, vt, k);
+              if (it < CS - 1 || it * kCB + tid < nvec) st16_stream(grow, it * kCB + tid, gq);
+            }
+            if (PERSIST && it < CSR) sreg[it < CSR ? it : 0] = ld_group(rnext, voff, it, (it) == CS - 1);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        } else {
+          // rows whose reference exponents are in the thousands: precise form, plain loop over the row
+          for (int i = (nit < CS ? nit : CS) * kCB - kCB + tid; i >= 0; i -= kCB) {
+            if (i < nvec) {
+              const uint4 vs = ld16(srow, i);
+              const uint4 vt = TEACHER == kDense ? ld16(trow, i) : make_uint4(0, 0, 0, 0);
+              st16_stream(grow, i, grad8<TEACHER, false>(vs, vt, k));
             }
           }
-          {
-            const uint4 gq = grad8<TEACHER>(vs, vt, k);
-            if (it < CS - 1 || it * kCB + tid < nvec) st16_stream(grow, it * kCB + tid, gq);
-          }
-          if (PERSIST && it < CSR) sreg[it < CSR ? it : 0] = ld_group(rnext, voff, it, (it) == CS - 1);
-          __builtin_amdgcn_sched_barrier(0);
+          if constexpr (PERSIST) request_student(rnext);
         }
         if constexpr (TEACHER == kTopk) {
           __syncthreads();
@@ -391,8 +438,12 @@ static hipError_t launch_cached_lse1(const KdArgs& a, hipStream_t stream) {
   return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, false, PERSIST>);
 }
 
+// Tuning knobs of the dense-teacher gradient kernel (measured on MI355X, 32,768 x 151,936): how many student
+// groups per thread stay in registers, how far ahead teacher / non-resident student groups are requested, and
+// whether workgroups are persistent.  Times are flat (+-2 %) for 8..16 resident groups; 12 leaves the register
+// allocator enough room to avoid spills, whose reloads would stall the load pipeline.
 #ifndef NPD_CSR
-#define NPD_CSR 16
+#define NPD_CSR 12
 #endif
 #ifndef NPD_TD
 #define NPD_TD 2
