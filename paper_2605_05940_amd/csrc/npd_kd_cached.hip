@@ -423,7 +423,7 @@ template <int CS, int CSR, int CT, int D, int TEACHER, bool GRAD, bool PERSIST>
 static hipError_t launch_cached_lse1(const KdArgs& a, hipStream_t stream) {
   const size_t lds_bytes = (size_t)CT * kCB * sizeof(uint4);
   auto launch = [&](auto kernel) -> hipError_t {
-    if (lds_bytes > 0) {
+    if (lds_bytes > 0) {  // more than the default 64 KB of dynamic LDS has to be asked for (cheap, idempotent)
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
       if (e != hipSuccess) return e;

@@ -376,3 +376,131 @@ def test_cfg1_full_size_sampled_rows(oracle):
     gpu = dict(kd=kd[ridx].cpu().numpy().astype(np.float64), nll_s=nll[ridx].cpu().numpy().astype(np.float64),
                nll_t=tnll[ridx].cpu().numpy().astype(np.float64), grad=g[ridx].float().cpu().numpy().astype(np.float64))
     compare_kd(gpu, ref, lay.loss_mask[rows])
+
+
+def _row_sums(g, step=1024):
+    T = g.shape[0]
+    rs = torch.empty(T, device=g.device)
+    for r0 in range(0, T, step):
+        rs[r0:r0 + step] = g[r0:r0 + step].float().sum(1)
+    return rs
+
+
+def _sample_rows(lay, n, seed):
+    rng = np.random.default_rng(seed)
+    scored = np.flatnonzero(lay.loss_mask)
+    masked = np.flatnonzero(lay.loss_mask == 0)
+    return np.sort(np.concatenate([rng.choice(scored, n, replace=False), [scored[0], scored[-1]], masked[:2]]))
+
+
+def test_cfg2_full_size_sampled_rows(oracle):
+    """Config 2 at its real size (top-k = 64 teacher, tau = 2): sampled rows element by element, all rows by
+    properties that hold at any size."""
+    w = synth.config(2)
+    lay, s, _, mask, labels = _inputs(w, dense_teacher=False)
+    T, V = w.n_tokens, w.vocab
+    _say(f"{w.name} full size T={T} V={V} k={w.topk}")
+    idx, val = synth.make_topk_teacher(w, s)
+    g = torch.empty((T, V), dtype=torch.bfloat16, device=dev())
+    kd, nll = torch.empty(T, device=dev()), torch.empty(T, device=dev())
+    status = torch.zeros(1, dtype=torch.int32, device=dev())
+    binding.npd_kd_loss_fwd_bwd(s, mask, teacher_idx=idx, teacher_val=val, labels=labels, tau=w.tau, grad_out=g,
+                                kd_tok=kd, nll_tok=nll, dev_status=status)
+    torch.cuda.synchronize()
+    assert status.item() == 0
+    m = mask.bool()
+    assert (kd[~m] == 0).all() and (kd[m] > 0).all() and torch.isfinite(kd).all()
+    rs = _row_sums(g)
+    assert (rs[~m] == 0).all() and rs.abs().max().item() < 2e-2
+    rows = _sample_rows(lay, 40, 6)
+    ridx = torch.from_numpy(rows).to(dev())
+    ref = oracle.kd_topk(_bits(s[ridx]), idx[ridx].cpu().numpy(), val[ridx].cpu().numpy(), lay.labels[rows],
+                         lay.loss_mask[rows], tau=w.tau)
+    gpu = dict(kd=kd[ridx].cpu().numpy().astype(np.float64), nll_s=nll[ridx].cpu().numpy().astype(np.float64),
+               grad=g[ridx].float().cpu().numpy().astype(np.float64))
+    compare_kd(gpu, ref, lay.loss_mask[rows], tau=w.tau)
+
+
+def test_cfg3_full_size_scoring_pass(oracle):
+    """Config 3 at its real size (2 x 32,768 tokens, two logit tensors): every per-token NLL of both models, the
+    per-sample means and the Delta-IFD decisions against the oracle."""
+    w = synth.config(3)
+    lay = synth.make_layout(w)
+    T, V, P = w.n_tokens, w.vocab, len(lay.pair_cond)
+    _say(f"{w.name} full size T={T} V={V} pairs={P}")
+    bs, bt = synth.delta_ifd_boosts(w, lay)
+    s = torch.empty((T, V), dtype=torch.bfloat16, device=dev())
+    t = torch.empty((T, V), dtype=torch.bfloat16, device=dev())
+    labels = torch.from_numpy(lay.labels).to(dev())
+    synth.fill_logits(w, s, t, label_boost=(labels, torch.from_numpy(bs).to(dev()), torch.from_numpy(bt).to(dev())))
+    mask = torch.from_numpy(lay.loss_mask).to(dev())
+    cu = torch.from_numpy(lay.cu_seqlens).to(dev())
+    nll_s, nll_t = torch.empty(T, device=dev()), torch.empty(T, device=dev())
+    status = torch.zeros(1, dtype=torch.int32, device=dev())
+    binding.npd_kd_loss_fwd_bwd(s, mask, labels=labels, nll_tok=nll_s, dev_status=status)
+    binding.npd_kd_loss_fwd_bwd(t, mask, labels=labels, nll_tok=nll_t, dev_status=status)
+    torch.cuda.synchronize()
+    assert status.item() == 0
+    ref_s, ref_t = np.zeros(T), np.zeros(T)
+    step = 2048
+    for r0 in range(0, T, step):          # the oracle sees the same bits, chunk by chunk
+        r1 = min(T, r0 + step)
+        if lay.loss_mask[r0:r1].any():
+            ref_s[r0:r1] = oracle.nll(_bits(s[r0:r1]), lay.labels[r0:r1], lay.loss_mask[r0:r1])["nll"]
+            ref_t[r0:r1] = oracle.nll(_bits(t[r0:r1]), lay.labels[r0:r1], lay.loss_mask[r0:r1])["nll"]
+        _say(f"  oracle rows {r1}/{T}")
+    compare_kd(dict(nll_s=nll_s.cpu().numpy().astype(np.float64), nll_t=nll_t.cpu().numpy().astype(np.float64)),
+               dict(nll_s=ref_s, nll_t=ref_t), lay.loss_mask, lay.cu_seqlens, oracle)
+    seg_s, seg_t = _segment_gpu(nll_s, mask, cu), _segment_gpu(nll_t, mask, cu, want_t2s=False)
+    rseg_s = oracle.segment_reduce(ref_s, lay.loss_mask, lay.cu_seqlens)
+    rseg_t = oracle.segment_reduce(ref_t, lay.loss_mask, lay.cu_seqlens)
+    np.testing.assert_array_equal(seg_s["count"], rseg_s["count"])
+    np.testing.assert_array_equal(seg_s["token_to_sample"], rseg_s["token_to_sample"])
+    ref0 = oracle.delta_ifd(rseg_s["mean"], rseg_t["mean"], rseg_s["count"], lay.pair_cond, lay.pair_uncond, 0.0, 0.8)
+    d_sorted = np.sort(ref0["delta"])
+    n_cut = max(1, int(round(0.1 * P)))
+    lo = float(0.5 * (d_sorted[n_cut - 1] + d_sorted[n_cut]))
+    hi = float(0.5 * (d_sorted[P - n_cut - 1] + d_sorted[P - n_cut]))
+    pc, pu = torch.from_numpy(lay.pair_cond).to(dev()), torch.from_numpy(lay.pair_uncond).to(dev())
+    for (a, b) in ((0.0, 0.8), (lo, hi)):
+        ref = oracle.delta_ifd(rseg_s["mean"], rseg_t["mean"], rseg_s["count"], lay.pair_cond, lay.pair_uncond, a, b)
+        gpu = _ifd_gpu(seg_s["mean_dev"], seg_t["mean_dev"], seg_s["count_dev"], pc, pu, a, b)
+        np.testing.assert_allclose(gpu["delta"], ref["delta"], rtol=0, atol=2e-3)
+        clear = (np.abs(ref["delta"] - a) > 1e-5) & (np.abs(ref["delta"] - b) > 1e-5)
+        np.testing.assert_array_equal(gpu["zone"][clear], ref["zone"][clear])
+        np.testing.assert_array_equal(gpu["keep"][clear], ref["keep"][clear])
+        assert gpu["keep_count"][0] == int(gpu["keep"].sum())
+    assert ref["keep_count"] == P - 2 * n_cut
+
+
+def test_cfg4_full_size_inplace_sampled_rows(oracle):
+    """Config 4 at its real size (65,536 x 262,144, heavy tails, ~500 short samples, gradient written over the
+    student logits): sampled rows element by element, all rows by properties."""
+    w = synth.config(4)
+    lay, s, t, mask, labels = _inputs(w)
+    T, V = w.n_tokens, w.vocab
+    _say(f"{w.name} full size T={T} V={V} segments={lay.n_segments}")
+    rows = _sample_rows(lay, 28, 7)
+    ridx = torch.from_numpy(rows).to(dev())
+    s_rows, t_rows = _bits(s[ridx]), _bits(t[ridx])          # the student rows are destroyed by the call
+    kd, nll, tnll = (torch.empty(T, device=dev()) for _ in range(3))
+    status = torch.zeros(1, dtype=torch.int32, device=dev())
+    binding.npd_kd_loss_fwd_bwd(s, mask, teacher_dense=t, labels=labels, grad_out=s, kd_tok=kd, nll_tok=nll,
+                                teacher_nll_tok=tnll, dev_status=status)
+    torch.cuda.synchronize()
+    assert status.item() == 0
+    m = mask.bool()
+    assert (kd[~m] == 0).all() and (kd[m] >= 0).all() and torch.isfinite(kd).all() and torch.isfinite(nll).all()
+    rs = _row_sums(s, 512)
+    assert (rs[~m] == 0).all() and rs.abs().max().item() < 2e-2
+    ref = oracle.kd_dense(s_rows, t_rows, lay.labels[rows], lay.loss_mask[rows])
+    gpu = dict(kd=kd[ridx].cpu().numpy().astype(np.float64), nll_s=nll[ridx].cpu().numpy().astype(np.float64),
+               nll_t=tnll[ridx].cpu().numpy().astype(np.float64), grad=s[ridx].float().cpu().numpy().astype(np.float64))
+    compare_kd(gpu, ref, lay.loss_mask[rows])
+    # per-sample bookkeeping of the ~500 short segments
+    cu = torch.from_numpy(lay.cu_seqlens).to(dev())
+    seg = _segment_gpu(kd, mask, cu)
+    rseg = oracle.segment_reduce(kd.cpu().numpy().astype(np.float64), lay.loss_mask, lay.cu_seqlens)
+    np.testing.assert_array_equal(seg["count"], rseg["count"])
+    np.testing.assert_array_equal(seg["token_to_sample"], rseg["token_to_sample"])
+    np.testing.assert_allclose(seg["sum"], rseg["sum"], rtol=1e-5, atol=1e-5)
