@@ -19,6 +19,9 @@
  *   - gradient of Eq. 2 with respect to the student logits (implied by the
  *     parameter update of Alg. 1): (1/tau) * (p_S(c) - p_T(c) [c in support])
  *     (p_T sums to 1 over its support, by construction of the softmax)
+ *   - gradient of the composite loss of Eq. 1, L_total = (1 - lambda) L_CE + lambda L_KD:
+ *     the KD gradient times grad_scale plus ce_grad_scale * (Softmax(O_S)(c) - [c == label])
+ *     (the caller sets grad_scale = lambda * w and ce_grad_scale = (1 - lambda) * w)
  *   - per-sample reduction over cu_seqlens under the response mask
  *   - IFD (Eq. 3), Delta-IFD (Eq. 4) and the three curation zones of Sec. 3.2
  *
@@ -77,6 +80,19 @@ static double logsumexp(const double *a, int64_t n) {
 static double row_nll(const double *o, int64_t V, int32_t label) {
   if (label < 0 || label >= V) return NAN;
   return logsumexp(o, V) - o[label];
+}
+
+/*
+ * Adds the gradient of the CE loss of one position (L_CE of Eq. 1, no temperature) to grad:
+ * ce_scale * (Softmax(s)(c) - [c == label]).  An out-of-range label poisons the row with NaN.
+ */
+static void row_add_ce_grad(const double *s, int64_t V, int32_t label, double ce_scale, double *grad) {
+  if (label < 0 || label >= V) {
+    for (int64_t c = 0; c < V; ++c) grad[c] = NAN;
+    return;
+  }
+  const double lse = logsumexp(s, V);
+  for (int64_t c = 0; c < V; ++c) grad[c] += ce_scale * (exp(s[c] - lse) - (c == label ? 1.0 : 0.0));
 }
 
 /*
@@ -150,14 +166,14 @@ static int row_kd_topk(const double *s, int64_t V, const int32_t *idx, const dou
 
 /*
  * Dense-teacher KD over T positions.  s, t: [T, V] doubles, row-major, contiguous.
- * labels may be NULL (then nll_s / nll_t must be NULL); mask is required.
+ * labels may be NULL (then nll_s / nll_t must be NULL and ce_grad_scale 0); mask is required.
  * Masked positions give kd = nll = 0 and a zero gradient row.
  * Outputs (each may be NULL): kd[T], nll_s[T], nll_t[T], lse_s[T] (log-sum-exp of the
  * raw student logits, tau = 1), grad[T, V].
  */
 void npd_oracle_kd_dense_f64(int64_t T, int64_t V, const double *s, const double *t, const int32_t *labels,
-                             const uint8_t *mask, double tau, double grad_scale, double *kd, double *nll_s,
-                             double *nll_t, double *lse_s, double *grad) {
+                             const uint8_t *mask, double tau, double grad_scale, double ce_grad_scale, double *kd,
+                             double *nll_s, double *nll_t, double *lse_s, double *grad) {
 #pragma omp parallel
   {
     double *a = (double *)malloc(sizeof(double) * (size_t)V);
@@ -176,6 +192,7 @@ void npd_oracle_kd_dense_f64(int64_t T, int64_t V, const double *s, const double
       }
       const double *sr = s + r * V, *tr = t + r * V;
       row_kd_dense(sr, tr, V, tau, grad_scale, a, b, kd ? kd + r : NULL, g);
+      if (g && ce_grad_scale != 0.0) row_add_ce_grad(sr, V, labels[r], ce_grad_scale, g);
       if (nll_s) nll_s[r] = row_nll(sr, V, labels[r]);
       if (nll_t) nll_t[r] = row_nll(tr, V, labels[r]);
       if (lse_s) lse_s[r] = logsumexp(sr, V);
@@ -191,7 +208,8 @@ void npd_oracle_kd_dense_f64(int64_t T, int64_t V, const double *s, const double
  */
 int64_t npd_oracle_kd_topk_f64(int64_t T, int64_t V, int32_t k, const double *s, const int32_t *idx,
                                const double *val, const int32_t *labels, const uint8_t *mask, double tau,
-                               double grad_scale, double *kd, double *nll_s, double *lse_s, double *grad) {
+                               double grad_scale, double ce_grad_scale, double *kd, double *nll_s, double *lse_s,
+                               double *grad) {
   int64_t bad = 0;
 #pragma omp parallel reduction(+ : bad)
   {
@@ -211,6 +229,7 @@ int64_t npd_oracle_kd_topk_f64(int64_t T, int64_t V, int32_t k, const double *s,
       const double *sr = s + r * V;
       bad += row_kd_topk(sr, V, idx + r * (int64_t)k, val + r * (int64_t)k, k, tau, grad_scale, a, b,
                          kd ? kd + r : NULL, g);
+      if (g && ce_grad_scale != 0.0) row_add_ce_grad(sr, V, labels[r], ce_grad_scale, g);
       if (nll_s) nll_s[r] = row_nll(sr, V, labels[r]);
       if (lse_s) lse_s[r] = logsumexp(sr, V);
     }
@@ -243,8 +262,8 @@ void npd_oracle_nll_f64(int64_t T, int64_t V, const double *o, const int32_t *la
 
 void npd_oracle_kd_dense_bf16(int64_t T, int64_t V, const uint16_t *s, int64_t s_stride, const uint16_t *t,
                               int64_t t_stride, const int32_t *labels, const uint8_t *mask, double tau,
-                              double grad_scale, double *kd, double *nll_s, double *nll_t, double *lse_s,
-                              double *grad) {
+                              double grad_scale, double ce_grad_scale, double *kd, double *nll_s, double *nll_t,
+                              double *lse_s, double *grad) {
 #pragma omp parallel
   {
     double *sr = (double *)malloc(sizeof(double) * (size_t)V);
@@ -266,6 +285,7 @@ void npd_oracle_kd_dense_bf16(int64_t T, int64_t V, const uint16_t *s, int64_t s
       for (int64_t c = 0; c < V; ++c) sr[c] = bf16_to_double(s[r * s_stride + c]);
       for (int64_t c = 0; c < V; ++c) tr[c] = bf16_to_double(t[r * t_stride + c]);
       row_kd_dense(sr, tr, V, tau, grad_scale, a, b, kd ? kd + r : NULL, g);
+      if (g && ce_grad_scale != 0.0) row_add_ce_grad(sr, V, labels[r], ce_grad_scale, g);
       if (nll_s) nll_s[r] = row_nll(sr, V, labels[r]);
       if (nll_t) nll_t[r] = row_nll(tr, V, labels[r]);
       if (lse_s) lse_s[r] = logsumexp(sr, V);
@@ -279,8 +299,8 @@ void npd_oracle_kd_dense_bf16(int64_t T, int64_t V, const uint16_t *s, int64_t s
 
 int64_t npd_oracle_kd_topk_bf16(int64_t T, int64_t V, int32_t k, const uint16_t *s, int64_t s_stride,
                                 const int32_t *idx, const float *val, const int32_t *labels,
-                                const uint8_t *mask, double tau, double grad_scale, double *kd, double *nll_s,
-                                double *lse_s, double *grad) {
+                                const uint8_t *mask, double tau, double grad_scale, double ce_grad_scale, double *kd,
+                                double *nll_s, double *lse_s, double *grad) {
   int64_t bad = 0;
 #pragma omp parallel reduction(+ : bad)
   {
@@ -302,6 +322,7 @@ int64_t npd_oracle_kd_topk_bf16(int64_t T, int64_t V, int32_t k, const uint16_t 
       for (int64_t c = 0; c < V; ++c) sr[c] = bf16_to_double(s[r * s_stride + c]);
       for (int32_t j = 0; j < k; ++j) vr[j] = (double)val[r * (int64_t)k + j];
       bad += row_kd_topk(sr, V, idx + r * (int64_t)k, vr, k, tau, grad_scale, a, b, kd ? kd + r : NULL, g);
+      if (g && ce_grad_scale != 0.0) row_add_ce_grad(sr, V, labels[r], ce_grad_scale, g);
       if (nll_s) nll_s[r] = row_nll(sr, V, labels[r]);
       if (lse_s) lse_s[r] = logsumexp(sr, V);
     }

@@ -26,16 +26,16 @@ def lib():
         L = ctypes.CDLL(path)
         L.npd_oracle_threads.restype = ctypes.c_int
         L.npd_oracle_kd_dense_f64.restype = None
-        L.npd_oracle_kd_dense_f64.argtypes = [_i64, _i64, _p, _p, _p, _p, _f64, _f64, _p, _p, _p, _p, _p]
+        L.npd_oracle_kd_dense_f64.argtypes = [_i64, _i64, _p, _p, _p, _p, _f64, _f64, _f64, _p, _p, _p, _p, _p]
         L.npd_oracle_kd_topk_f64.restype = _i64
-        L.npd_oracle_kd_topk_f64.argtypes = [_i64, _i64, _i32, _p, _p, _p, _p, _p, _f64, _f64, _p, _p, _p, _p]
+        L.npd_oracle_kd_topk_f64.argtypes = [_i64, _i64, _i32, _p, _p, _p, _p, _p, _f64, _f64, _f64, _p, _p, _p, _p]
         L.npd_oracle_nll_f64.restype = None
         L.npd_oracle_nll_f64.argtypes = [_i64, _i64, _p, _p, _p, _p, _p]
         L.npd_oracle_kd_dense_bf16.restype = None
-        L.npd_oracle_kd_dense_bf16.argtypes = [_i64, _i64, _p, _i64, _p, _i64, _p, _p, _f64, _f64,
+        L.npd_oracle_kd_dense_bf16.argtypes = [_i64, _i64, _p, _i64, _p, _i64, _p, _p, _f64, _f64, _f64,
                                                _p, _p, _p, _p, _p]
         L.npd_oracle_kd_topk_bf16.restype = _i64
-        L.npd_oracle_kd_topk_bf16.argtypes = [_i64, _i64, _i32, _p, _i64, _p, _p, _p, _p, _f64, _f64,
+        L.npd_oracle_kd_topk_bf16.argtypes = [_i64, _i64, _i32, _p, _i64, _p, _p, _p, _p, _f64, _f64, _f64,
                                               _p, _p, _p, _p]
         L.npd_oracle_nll_bf16.restype = None
         L.npd_oracle_nll_bf16.argtypes = [_i64, _i64, _p, _i64, _p, _p, _p, _p]
@@ -69,11 +69,13 @@ def _labels_mask(T, labels, mask):
     return labels, mask
 
 
-def kd_dense(s, t, labels=None, mask=None, tau=1.0, grad_scale=1.0, want_grad=True):
+def kd_dense(s, t, labels=None, mask=None, tau=1.0, grad_scale=1.0, want_grad=True, ce_grad_scale=0.0):
     """Dense-teacher KD.  ``s``, ``t``: [T, V] float64, or uint16 (bf16 bits; may be strided views).
 
+    ``grad`` is grad_scale * d kd / d s  +  ce_grad_scale * d nll_s / d s  (the composite loss of Eq. 1).
     Returns dict(kd, nll_s, nll_t, lse_s, grad) of float64 arrays (None where not computed).
     """
+    assert ce_grad_scale == 0.0 or labels is not None
     T, V = s.shape
     assert t.shape == (T, V)
     labels, mask = _labels_mask(T, labels, mask)
@@ -85,17 +87,17 @@ def kd_dense(s, t, labels=None, mask=None, tau=1.0, grad_scale=1.0, want_grad=Tr
     if s.dtype == np.uint16:
         assert t.dtype == np.uint16 and s.strides[1] == 2 and t.strides[1] == 2
         lib().npd_oracle_kd_dense_bf16(T, V, s.ctypes.data, s.strides[0] // 2, t.ctypes.data, t.strides[0] // 2,
-                                       _ptr(labels), _ptr(mask), tau, grad_scale,
+                                       _ptr(labels), _ptr(mask), tau, grad_scale, ce_grad_scale,
                                        _ptr(kd), _ptr(nll_s), _ptr(nll_t), _ptr(lse), _ptr(grad))
     else:
         s = _c(s, np.float64)
         t = _c(t, np.float64)
-        lib().npd_oracle_kd_dense_f64(T, V, _ptr(s), _ptr(t), _ptr(labels), _ptr(mask), tau, grad_scale,
+        lib().npd_oracle_kd_dense_f64(T, V, _ptr(s), _ptr(t), _ptr(labels), _ptr(mask), tau, grad_scale, ce_grad_scale,
                                       _ptr(kd), _ptr(nll_s), _ptr(nll_t), _ptr(lse), _ptr(grad))
     return dict(kd=kd, nll_s=nll_s, nll_t=nll_t, lse_s=lse, grad=grad)
 
 
-def kd_topk(s, idx, val, labels=None, mask=None, tau=1.0, grad_scale=1.0, want_grad=True):
+def kd_topk(s, idx, val, labels=None, mask=None, tau=1.0, grad_scale=1.0, want_grad=True, ce_grad_scale=0.0):
     """Top-k-teacher KD.  ``s``: [T, V] float64 or uint16 bf16 bits; ``idx`` int32 [T, k]; ``val`` [T, k]."""
     T, V = s.shape
     idx = _c(idx, np.int32)
@@ -110,13 +112,13 @@ def kd_topk(s, idx, val, labels=None, mask=None, tau=1.0, grad_scale=1.0, want_g
         assert s.strides[1] == 2
         val = _c(val, np.float32)
         bad = lib().npd_oracle_kd_topk_bf16(T, V, k, s.ctypes.data, s.strides[0] // 2, _ptr(idx), _ptr(val),
-                                            _ptr(labels), _ptr(mask), tau, grad_scale,
+                                            _ptr(labels), _ptr(mask), tau, grad_scale, ce_grad_scale,
                                             _ptr(kd), _ptr(nll_s), _ptr(lse), _ptr(grad))
     else:
         s = _c(s, np.float64)
         val = _c(val, np.float64)
         bad = lib().npd_oracle_kd_topk_f64(T, V, k, _ptr(s), _ptr(idx), _ptr(val), _ptr(labels), _ptr(mask),
-                                           tau, grad_scale, _ptr(kd), _ptr(nll_s), _ptr(lse), _ptr(grad))
+                                           tau, grad_scale, ce_grad_scale, _ptr(kd), _ptr(nll_s), _ptr(lse), _ptr(grad))
     return dict(kd=kd, nll_s=nll_s, lse_s=lse, grad=grad, bad_index_rows=int(bad))
 
 

@@ -402,3 +402,56 @@ def test_delta_ifd_symmetries(oracle):
     assert (same["delta"] == 0).all() and (same["zone"] == 1).all() and same["keep_count"] == len(pc)
     # IFD > 1 exactly when the instruction makes the response harder to predict
     assert ((a["ifd_student"] > 1) == (ms[pc] > ms[pu])).all()
+
+
+# --------------------------------------------------------------------------- composite loss (Eq. 1)
+
+@pytest.mark.parametrize("tau", [1.0, 2.0])
+def test_composite_gradient_finite_differences(oracle, tau):
+    # L_total = (1 - lambda) L_CE + lambda L_KD (Eq. 1): its gradient from the oracle vs central differences of
+    # the oracle's own per-position kd and nll outputs (which are pinned separately above)
+    T, V, h, lam, w = 2, 40, 1e-6, 0.9, 0.7
+    s, t = _rand(T, V), _rand(T, V)
+    lab = RNG.integers(0, V, T)
+    g = oracle.kd_dense(s, t, lab, tau=tau, grad_scale=lam * w, ce_grad_scale=(1 - lam) * w)["grad"]
+
+    def total(x, r):
+        o = oracle.kd_dense(x, t, lab, tau=tau, want_grad=False)
+        return w * (lam * o["kd"][r] + (1 - lam) * o["nll_s"][r])
+    for r in range(T):
+        for c in range(V):
+            sp, sm = s.copy(), s.copy()
+            sp[r, c] += h
+            sm[r, c] -= h
+            assert g[r, c] == pytest.approx((total(sp, r) - total(sm, r)) / (2 * h), rel=2e-6, abs=1e-9)
+
+
+def test_composite_gradient_matches_autograd_and_sums_to_zero(oracle):
+    T, V, k = 6, 300, 12
+    s, t = _rand(T, V, 3.0), _rand(T, V, 3.0)
+    lab = RNG.integers(0, V, T)
+    mask = np.array([1, 1, 0, 1, 1, 1], np.uint8)
+    ts = torch.from_numpy(s).requires_grad_(True)
+    F.cross_entropy(ts, torch.from_numpy(lab), reduction="sum").backward()     # library CE gradient, float64
+    ce = ts.grad.numpy()
+    kd_only = oracle.kd_dense(s, t, lab, mask, tau=2.0, grad_scale=0.4)["grad"]
+    both = oracle.kd_dense(s, t, lab, mask, tau=2.0, grad_scale=0.4, ce_grad_scale=0.25)["grad"]
+    m = mask.astype(bool)
+    np.testing.assert_allclose((both - kd_only)[m], 0.25 * ce[m], rtol=1e-10, atol=1e-15)
+    assert (both[~m] == 0).all()
+    assert np.abs(both.sum(1)).max() < 1e-12 * V
+    # CE only (lambda = 0): the gradient is softmax - onehot whatever the teacher is
+    ce_only = oracle.kd_dense(s, t, lab, tau=1.0, grad_scale=0.0, ce_grad_scale=1.0)["grad"]
+    np.testing.assert_allclose(ce_only, ce, rtol=1e-10, atol=1e-15)
+    # top-k teacher: same CE term
+    idx = np.stack([RNG.choice(V, k, replace=False) for _ in range(T)]).astype(np.int32)
+    idx[0, 0] = lab[0]                                   # the label inside the teacher's support
+    val = _rand(T, k)
+    a = oracle.kd_topk(s, idx, val, lab, mask, tau=2.0, grad_scale=0.4)["grad"]
+    b = oracle.kd_topk(s, idx, val, lab, mask, tau=2.0, grad_scale=0.4, ce_grad_scale=0.25)["grad"]
+    np.testing.assert_allclose((b - a)[m], 0.25 * ce[m], rtol=1e-10, atol=1e-15)
+    # an out-of-range label poisons that row's gradient only
+    bad = lab.copy()
+    bad[1] = V
+    g = oracle.kd_dense(s, t, bad, tau=1.0, ce_grad_scale=1.0)["grad"]
+    assert np.isnan(g[1]).all() and np.isfinite(g[[0, 2, 3]]).all()
