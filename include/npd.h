@@ -86,8 +86,11 @@ typedef struct {
   int32_t topk;           /* k in [1, V] for NPD_TEACHER_TOPK, else ignored                        */
   uint32_t flags;         /* NPD_FLAG_*                                                            */
   float tau;              /* KD temperature, finite, > 0; divides student and teacher logits alike */
-  float grad_scale;       /* finite; multiplies every gradient element (the caller folds the loss
-                             weight lambda of Eq. 1, a tau^2 factor or 1/N_tokens in here)         */
+  float grad_scale;       /* finite; multiplies the KD gradient (the caller folds the loss weight
+                             lambda of Eq. 1, a tau^2 factor or 1/N_tokens in here)                */
+  float ce_grad_scale;    /* finite; weight of the hard-label CE gradient of Eq. 1 (the caller sets
+                             (1 - lambda) / N_tokens); 0 = KD gradient only.  Non-zero needs labels
+                             and a gradient buffer                                                 */
 } npd_kd_desc;
 
 /* Library version (major * 100 + minor). */
@@ -111,6 +114,8 @@ size_t npd_workspace_bytes(const npd_kd_desc* desc);
  *                                                      top-k: over the k stored entries only
  *   kd_tok[p]  = sum_{c in support} p_T(c) * log(p_T(c) / p_S(c))        (Eq. 2; support = V or top-k)
  *   grad[p, c] = grad_scale / tau * (p_S(c) - p_T(c) * [c in support])   (d kd_tok / d student logit)
+ *              + ce_grad_scale * (Softmax(student[p, :])(c) - [c == labels[p]])   (d nll_tok / d student logit;
+ *                together the gradient of L_total = (1 - lambda) L_CE + lambda L_KD of Eq. 1)
  *   nll_tok[p]         = logsumexp(student[p, :]) - student[p, labels[p]]   (tau = 1 always)
  *   teacher_nll_tok[p] = logsumexp(teacher[p, :]) - teacher[p, labels[p]]   (dense teacher only)
  *   lse_tok[p]         = logsumexp(student[p, :])                           (tau = 1)
@@ -123,7 +128,7 @@ size_t npd_workspace_bytes(const npd_kd_desc* desc);
  *   teacher_idx      int32 [T, k], unique per row, in [0, V); required iff TOPK, else NULL
  *   teacher_val      fp32 [T, k] logits or log-probabilities at tau = 1 (a per-row additive
  *                    constant changes nothing); required iff TOPK, else NULL
- *   labels           int32 [T]; required iff nll_tok or teacher_nll_tok is given
+ *   labels           int32 [T]; required iff nll_tok or teacher_nll_tok is given or ce_grad_scale != 0
  *   loss_mask        uint8 [T], required
  *   grad_out         bf16 [T, student_stride]; NULL iff NPD_FLAG_FWD_ONLY or teacher NONE; may equal
  *                    student_logits iff NPD_FLAG_INPLACE_GRAD (then the student logits are

@@ -35,7 +35,7 @@ class KdDesc(ctypes.Structure):
     _fields_ = [("n_tokens", ctypes.c_int64), ("vocab", ctypes.c_int32), ("teacher_kind", ctypes.c_int32),
                 ("student_stride", ctypes.c_int64), ("teacher_stride", ctypes.c_int64),
                 ("topk", ctypes.c_int32), ("flags", ctypes.c_uint32),
-                ("tau", ctypes.c_float), ("grad_scale", ctypes.c_float)]
+                ("tau", ctypes.c_float), ("grad_scale", ctypes.c_float), ("ce_grad_scale", ctypes.c_float)]
 
 
 _lib = None
@@ -99,7 +99,7 @@ def npd_kd_loss_fwd_bwd(student_logits: torch.Tensor, loss_mask: torch.Tensor, *
                         teacher_dense: Optional[torch.Tensor] = None,
                         teacher_idx: Optional[torch.Tensor] = None, teacher_val: Optional[torch.Tensor] = None,
                         labels: Optional[torch.Tensor] = None, tau: float = 1.0, grad_scale: float = 1.0,
-                        grad_out: Optional[torch.Tensor] = None, kd_tok: Optional[torch.Tensor] = None,
+                        ce_grad_scale: float = 0.0, grad_out: Optional[torch.Tensor] = None, kd_tok: Optional[torch.Tensor] = None,
                         nll_tok: Optional[torch.Tensor] = None, teacher_nll_tok: Optional[torch.Tensor] = None,
                         lse_tok: Optional[torch.Tensor] = None, dev_status: Optional[torch.Tensor] = None,
                         workspace: Optional[torch.Tensor] = None) -> None:
@@ -112,7 +112,7 @@ def npd_kd_loss_fwd_bwd(student_logits: torch.Tensor, loss_mask: torch.Tensor, *
     d = KdDesc()
     d.n_tokens, d.vocab = T, V
     d.student_stride = _row_stride(student_logits)
-    d.tau, d.grad_scale = tau, grad_scale
+    d.tau, d.grad_scale, d.ce_grad_scale = tau, grad_scale, ce_grad_scale
     if teacher_dense is not None:
         d.teacher_kind, d.teacher_stride = NPD_TEACHER_DENSE_BF16, _row_stride(teacher_dense)
         if teacher_dense.shape != (T, V):
@@ -151,7 +151,7 @@ def npd_workspace_bytes(n_tokens: int, vocab: int, teacher_kind: int = NPD_TEACH
     d = KdDesc()
     d.n_tokens, d.vocab, d.teacher_kind, d.topk, d.flags = n_tokens, vocab, teacher_kind, topk, flags
     d.student_stride = d.teacher_stride = vocab
-    d.tau, d.grad_scale = tau, 1.0
+    d.tau, d.grad_scale, d.ce_grad_scale = tau, 1.0, 0.0
     return int(load().npd_workspace_bytes(ctypes.byref(d)))
 
 

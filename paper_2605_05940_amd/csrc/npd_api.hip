@@ -35,7 +35,9 @@ npd_status check_desc(const npd_kd_desc* d) {
   if (d->teacher_kind == NPD_TEACHER_DENSE_BF16 && d->teacher_stride < d->vocab) return NPD_ERR_SHAPE;
   if (d->teacher_kind == NPD_TEACHER_TOPK && (d->topk < 1 || d->topk > d->vocab)) return NPD_ERR_SHAPE;
   if (!(d->tau > 0.0f) || !isfinite(d->tau)) return NPD_ERR_VALUE;
-  if (!isfinite(d->grad_scale)) return NPD_ERR_VALUE;
+  if (!isfinite(d->grad_scale) || !isfinite(d->ce_grad_scale)) return NPD_ERR_VALUE;
+  if (d->ce_grad_scale != 0.0f && ((d->flags & NPD_FLAG_FWD_ONLY) || d->teacher_kind == NPD_TEACHER_NONE))
+    return NPD_ERR_VALUE;  // a CE gradient needs a gradient buffer
   if (d->flags & ~(uint32_t)(NPD_FLAG_FWD_ONLY | NPD_FLAG_INPLACE_GRAD)) return NPD_ERR_VALUE;
   if ((d->flags & NPD_FLAG_FWD_ONLY) && (d->flags & NPD_FLAG_INPLACE_GRAD)) return NPD_ERR_VALUE;
   if (d->n_tokens > 0x7fffffffLL) return NPD_ERR_UNSUPPORTED;  // one workgroup per position, 1-D grid
@@ -47,7 +49,7 @@ npd_status check_desc(const npd_kd_desc* d) {
 
 extern "C" {
 
-int npd_version(void) { return 100; }
+int npd_version(void) { return 101; }
 
 const char* npd_status_string(npd_status st) {
   switch (st) {
@@ -92,7 +94,7 @@ npd_status npd_kd_loss_fwd_bwd(const npd_kd_desc* desc, const void* student_logi
     if (teacher_dense || teacher_idx || teacher_val || teacher_nll_tok || kd_tok) return NPD_ERR_VALUE;
     if (!fwd_only || grad_out) return NPD_ERR_VALUE;  // nothing to differentiate without a teacher
   }
-  if ((nll_tok || teacher_nll_tok) && !labels) return NPD_ERR_NULL;
+  if ((nll_tok || teacher_nll_tok || d.ce_grad_scale != 0.0f) && !labels) return NPD_ERR_NULL;
   if (fwd_only) {
     if (grad_out) return NPD_ERR_VALUE;
   } else {
@@ -143,7 +145,8 @@ npd_status npd_kd_loss_fwd_bwd(const npd_kd_desc* desc, const void* student_logi
   a.c = (float)(1.4426950408889634 / (double)d.tau);
   a.inv_tau = 1.0f / d.tau;
   a.gscale = (float)((double)d.grad_scale / (double)d.tau);
-  a.need_lse1 = (d.tau != 1.0f && (nll_tok || teacher_nll_tok || lse_tok)) ? 1 : 0;
+  a.cscale = d.ce_grad_scale;
+  a.need_lse1 = (d.tau != 1.0f && (nll_tok || teacher_nll_tok || lse_tok || d.ce_grad_scale != 0.0f)) ? 1 : 0;
 
   const hipError_t e = npd::launch_kd(a, d.teacher_kind, !fwd_only, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? NPD_OK : NPD_ERR_HIP;

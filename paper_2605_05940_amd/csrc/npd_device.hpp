@@ -112,6 +112,54 @@ struct Lse {
   __device__ __forceinline__ float log2_sum() const { return r + __log2f(z); }
 };
 
+// Coefficients of the gradient write (sweep 2), precise form:
+//   grad_scale / tau * (p_S - p_T) = (e_S - e_T z_S / z_T) w_S,   e = 2^(x c - r),  w_S = grad_scale / (tau z_S)
+// (exactly 0 when teacher and student coincide), plus, for the composite loss of Eq. 1, the hard-label CE term
+//   ce_grad_scale * Softmax(s)(c) = 2^(x log2(e) - r1) w_C,   w_C = ce_grad_scale / z1,
+// whose softmax has no temperature; at tau = 1 it shares e_S with the KD term.
+struct GradCoef {
+  float c, rs, rt, ratio, ws;
+  float r1, wc;
+  bool ce;         // uniform: CE term present
+  bool ce_shared;  // tau = 1
+};
+
+__device__ __forceinline__ GradCoef make_grad_coef(const Lse& S, const Lse& Tt, const Lse& S1, float c, float gscale,
+                                                   float cscale, bool has_teacher_stream, bool lse1) {
+  GradCoef k;
+  k.c = c;
+  k.rs = S.r;
+  k.rt = Tt.r;
+  k.ws = gscale / S.z;
+  k.ratio = has_teacher_stream ? S.z / Tt.z : 0.0f;
+  k.ce = cscale != 0.0f;
+  k.ce_shared = !lse1;
+  k.r1 = lse1 ? S1.r : S.r;
+  k.wc = k.ce ? cscale / (lse1 ? S1.z : S.z) : 0.0f;
+  return k;
+}
+
+// e_S-only part (no teacher term): the dense part of a top-k row
+__device__ __forceinline__ float grad_student_elem(float xs, const GradCoef& k) {
+  const float es = exp2_fast(__builtin_fmaf(xs, k.c, -k.rs));
+  float g = es * k.ws;
+  if (k.ce) g = __builtin_fmaf(k.ce_shared ? es : exp2_fast(__builtin_fmaf(xs, kLog2e, -k.r1)), k.wc, g);
+  return g;
+}
+// with a teacher term e_T = 2^(bt - rt) given by its scaled exponent argument bt = (teacher value) * c
+__device__ __forceinline__ float grad_pair_elem(float xs, float bt, const GradCoef& k) {
+  const float es = exp2_fast(__builtin_fmaf(xs, k.c, -k.rs));
+  float g = __builtin_fmaf(-exp2_fast(bt - k.rt), k.ratio, es) * k.ws;
+  if (k.ce) g = __builtin_fmaf(k.ce_shared ? es : exp2_fast(__builtin_fmaf(xs, kLog2e, -k.r1)), k.wc, g);
+  return g;
+}
+__device__ __forceinline__ float grad_dense_elem(float xs, float xt, const GradCoef& k) {
+  const float es = exp2_fast(__builtin_fmaf(xs, k.c, -k.rs));
+  float g = __builtin_fmaf(-exp2_fast(__builtin_fmaf(xt, k.c, -k.rt)), k.ratio, es) * k.ws;
+  if (k.ce) g = __builtin_fmaf(k.ce_shared ? es : exp2_fast(__builtin_fmaf(xs, kLog2e, -k.r1)), k.wc, g);
+  return g;
+}
+
 __device__ __forceinline__ void wave_merge(Lse& v) {
 #pragma unroll
   for (int off = kWave / 2; off > 0; off >>= 1) {

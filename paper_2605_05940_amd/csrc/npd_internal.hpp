@@ -29,6 +29,7 @@ struct KdArgs {
   float c;             // log2(e) / tau
   float inv_tau;
   float gscale;        // grad_scale / tau
+  float cscale;        // ce_grad_scale (weight of the hard-label CE gradient; 0 = none)
   int32_t need_lse1;   // tau != 1 and a tau = 1 quantity (nll, teacher nll, lse) is wanted
 };
 

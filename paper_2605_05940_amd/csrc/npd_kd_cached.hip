@@ -61,30 +61,33 @@ __device__ __forceinline__ void opaque(uint4& v) {
   asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w));
 }
 
-// Sweep-2 coefficients.  Precise form: grad = (e_S - e_T z_S / z_T) w with e = 2^(x c - r).  Folded form:
-// |grad_scale| / (tau z) goes into the exponent, grad = +-(2^(x c - fs) - 2^(x c - ft)), one instruction less
-// per element; it is used only while |fs|, |ft| < 1024, where rounding fs, ft to fp32 moves a probability by
-// less than 2.2e-5 of itself (rows with logits in the thousands take the precise form).
+// Sweep-2 coefficients.  Precise form: see GradCoef.  Folded form: the weights go into the exponents,
+//   grad = +-(2^(x c - fs) - 2^(x c - ft)),   fs = r_S + log2(z_S / |A|),  ft = r_T + log2(z_T / |B|),
+// with A = grad_scale / tau + ce_grad_scale (weight of p_S; the CE softmax shares e_S, so tau = 1 whenever
+// ce_grad_scale != 0 here) and B = grad_scale / tau (weight of p_T): one instruction less per element.  It is used
+// only while A and B do not differ in sign and |fs|, |ft| < 1024, where rounding fs, ft to fp32 moves a probability
+// by less than 2.2e-5 of itself (rows with logits in the thousands take the precise form).
 struct Sweep2Coef {
-  float c, rs, rt, ratio, ws;  // precise form
-  float fs, ft;                // folded form
-  uint32_t sign;               // 0x80008000 when grad_scale < 0 (folded form)
-  bool folded;                 // uniform
+  GradCoef p;     // precise form
+  float c, fs, ft;
+  uint32_t sign;  // 0x80008000 when the weights are negative (folded form)
+  bool folded;    // uniform
 };
 
-__device__ __forceinline__ Sweep2Coef sweep2_coef(const Lse& S, const Lse& Tt, float c, float gscale, bool dense) {
+__device__ __forceinline__ Sweep2Coef sweep2_coef(const Lse& S, const Lse& Tt, float c, float gscale, float cscale,
+                                                  bool has_teacher_stream, bool dense) {
   Sweep2Coef k;
+  k.p = make_grad_coef(S, Tt, S, c, gscale, cscale, has_teacher_stream, false);
   k.c = c;
-  k.rs = S.r;
-  k.rt = Tt.r;
-  k.ws = gscale / S.z;
-  k.ratio = dense ? S.z / Tt.z : 0.0f;
-  const float lg = __log2f(fabsf(gscale));  // -inf for a zero scale: every term becomes 2^-inf = 0
-  k.fs = S.r + (S.log2_z() - lg);
-  k.ft = dense ? Tt.r + (Tt.log2_z() - lg) : 0.0f;
-  k.sign = gscale < 0.0f ? 0x80008000u : 0u;
-  k.folded = fabsf(k.fs) < 1024.0f && fabsf(k.ft) < 1024.0f;
-  if (gscale == 0.0f) k.folded = true;
+  const float A = gscale + cscale, B = dense ? gscale : 0.0f;
+  // log2(0) = -inf: the term becomes 2^-inf = 0
+  k.fs = S.r + (S.log2_z() - __log2f(fabsf(A)));
+  k.ft = dense ? Tt.r + (Tt.log2_z() - __log2f(fabsf(B))) : 0.0f;
+  k.sign = (A < 0.0f || B < 0.0f) ? 0x80008000u : 0u;
+  const bool same_sign = (A >= 0.0f && B >= 0.0f) || (A <= 0.0f && B <= 0.0f);
+  const bool small_s = A == 0.0f || fabsf(k.fs) < 1024.0f;
+  const bool small_t = !dense || B == 0.0f || fabsf(k.ft) < 1024.0f;
+  k.folded = same_sign && small_s && small_t;
   return k;
 }
 
@@ -102,9 +105,7 @@ __device__ __forceinline__ uint4 grad8(const uint4& vs, const uint4& vt, const S
         gv[j] = exp2_fast(__builtin_fmaf(xs[j], k.c, -k.fs)) - exp2_fast(__builtin_fmaf(xt[j], k.c, -k.ft));
     } else {
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        gv[j] = __builtin_fmaf(-exp2_fast(__builtin_fmaf(xt[j], k.c, -k.rt)), k.ratio,
-                               exp2_fast(__builtin_fmaf(xs[j], k.c, -k.rs))) * k.ws;
+      for (int j = 0; j < 8; ++j) gv[j] = grad_dense_elem(xs[j], xt[j], k.p);
     }
   } else {
     if constexpr (FOLDED) {
@@ -112,7 +113,7 @@ __device__ __forceinline__ uint4 grad8(const uint4& vs, const uint4& vt, const S
       for (int j = 0; j < 8; ++j) gv[j] = exp2_fast(__builtin_fmaf(xs[j], k.c, -k.fs));
     } else {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) gv[j] = exp2_fast(__builtin_fmaf(xs[j], k.c, -k.rs)) * k.ws;
+      for (int j = 0; j < 8; ++j) gv[j] = grad_student_elem(xs[j], k.p);
     }
   }
   uint4 o;
@@ -154,6 +155,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
   extern __shared__ uint4 lds_t[];
   __shared__ float red[4 * 3 * (kCB / kWave)];
   __shared__ uint16_t patch[TEACHER == kTopk && GRAD ? kTopkMax : 1];
+  __shared__ int y_in_support;  // top-k teacher: the label is one of the k support positions of this row
   static_assert(CT <= CS && CSR <= CS && D >= 1 && D <= CS, "bad cache shape");
   const int tid = threadIdx.x;
   const int voff = tid * 16;
@@ -204,7 +206,6 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
     uint16_t* grow = GRAD ? a.g + row * a.s_stride : nullptr;
     const __amdgpu_buffer_rsrc_t rs = row_rsrc(srow, nvec);
     const __amdgpu_buffer_rsrc_t rt = row_rsrc(TEACHER == kDense ? trow : srow, nvec);
-    const __amdgpu_buffer_rsrc_t rg = row_rsrc(GRAD ? grow : srow, nvec);
     // the student row to request while this row's gradient is written (this row again if it is the last)
     const __amdgpu_buffer_rsrc_t rnext = row_rsrc(a.s + (nrow < T ? nrow : row) * a.s_stride, nvec);
 
@@ -294,11 +295,15 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
       kd = (acc[1].a / acc[1].z) * a.inv_tau + ((acc[0].r - acc[1].r) + (acc[0].log2_z() - acc[1].log2_z())) * kLn2;
       kd = kd < 0.0f ? 0.0f : kd;
     }
+    const bool ce = GRAD && a.cscale != 0.0f;                       // uniform (tau = 1 here whenever it is set)
+    const bool bad_label = a.labels && (unsigned)y >= (unsigned)V;  // uniform
+    const Sweep2Coef k = sweep2_coef(acc[0], acc[1], c, a.gscale, a.cscale, TEACHER != kNone, TEACHER == kDense);
     if constexpr (TEACHER == kTopk) {
       bad_index = __syncthreads_or(bad_index);
+      if (tid == 0) y_in_support = 0;
+      __syncthreads();
       const int32_t* irow = a.tidx + row * (int64_t)a.k;
       const float* vrow = a.tval + row * (int64_t)a.k;
-      const float ws = a.gscale / acc[0].z, ratio = acc[0].z / acc[1].z;
       float part = 0.0f;
       if (!bad_index) {
         for (int j = tid; j < a.k; j += kCB) {
@@ -308,8 +313,11 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
           const float lps = __builtin_fmaf(sj, c, -Ls);
           part = __builtin_fmaf(exp2_fast(lpt), (lpt - lps) * kLn2, part);
           if constexpr (GRAD) {
-            const float gj =
-                __builtin_fmaf(-exp2_fast(b - acc[1].r), ratio, exp2_fast(__builtin_fmaf(sj, c, -acc[0].r))) * ws;
+            float gj = grad_pair_elem(sj, b, k.p);
+            if (ce && irow[j] == y) {
+              gj -= a.cscale;
+              y_in_support = 1;
+            }
             patch[j] = one_bf16(gj);
           }
         }
@@ -322,8 +330,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
     if (tid == 0) {
       int flags = 0;
       if (bad_index) flags |= 2;
-      const bool bad_label = a.labels && (unsigned)y >= (unsigned)V;
-      if (bad_label && (a.nll || a.tnll)) flags |= 1;
+      if (bad_label && (a.nll || a.tnll || ce)) flags |= 1;
       if (a.kd) a.kd[row] = kd;
       if (a.nll) a.nll[row] = bad_label ? __builtin_nanf("") : __fsub_rn(lse1_s, s_y);
       if (TEACHER == kDense && a.tnll) {
@@ -336,18 +343,16 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
 
     // ---- sweep 2
     if constexpr (GRAD) {
-      const Sweep2Coef k = sweep2_coef(acc[0], acc[1], c, a.gscale, TEACHER == kDense);
-      if (TEACHER == kTopk && bad_index) {  // uniform
+      if ((TEACHER == kTopk && bad_index) || (ce && bad_label)) {  // uniform: the row cannot be differentiated
         const uint16_t qnan = 0x7fc0;
         for (int e = tid; e < V; e += kCB) grow[e] = qnan;
         if constexpr (PERSIST) request_student(rnext);
       } else {
         // sub-group tail and streamed part first (read most recently), then the first CS groups backwards
         for (int e = nvec * 8 + tid; e < V; e += kCB) {
-          float gv = exp2_fast(__builtin_fmaf(bf16_one(srow[e]), c, -k.rs));
-          if constexpr (TEACHER == kDense)
-            gv = __builtin_fmaf(-exp2_fast(__builtin_fmaf(bf16_one(trow[e]), c, -k.rt)), k.ratio, gv);
-          grow[e] = one_bf16(gv * k.ws);
+          const float xs = bf16_one(srow[e]);
+          grow[e] =
+              one_bf16(TEACHER == kDense ? grad_dense_elem(xs, bf16_one(trow[e]), k.p) : grad_student_elem(xs, k.p));
         }
         for (int i = (nit - 1) * kCB + tid; i >= CS * kCB; i -= kCB) {
           if (i < nvec) {
@@ -395,10 +400,18 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
           }
           if constexpr (PERSIST) request_student(rnext);
         }
-        if constexpr (TEACHER == kTopk) {
+        if (TEACHER == kTopk || ce) {  // uniform
+          // the k support positions and the label position get their final values once the dense stores of the
+          // whole workgroup are ordered before them
           __syncthreads();
-          const int32_t* irow = a.tidx + row * (int64_t)a.k;
-          for (int j = tid; j < a.k; j += kCB) grow[irow[j]] = patch[j];
+          if constexpr (TEACHER == kTopk) {
+            const int32_t* irow = a.tidx + row * (int64_t)a.k;
+            for (int j = tid; j < a.k; j += kCB) grow[irow[j]] = patch[j];
+          }
+          if (ce && tid == 0 && !(TEACHER == kTopk && y_in_support)) {
+            const float gy = TEACHER == kDense ? grad_dense_elem(s_y, t_y, k.p) : grad_student_elem(s_y, k.p);
+            grow[y] = one_bf16(gy - a.cscale);
+          }
         }
       }
     }
@@ -454,7 +467,11 @@ static hipError_t launch_cached_lse1(const KdArgs& a, hipStream_t stream) {
 constexpr int kCachedGroups = 19;  // covers vocabularies of 147,464 .. 155,648 tokens entirely, larger ones partly
 
 // Row-resident path: 16-byte aligned rows of more than (kCachedGroups - 1) * 1024 groups.
-bool cached_path_applies(const KdArgs& a) { return a.nvec_s > (kCachedGroups - 1) * kCB; }
+// (The CE softmax of the composite loss has no temperature; this path covers it at tau = 1, where it shares the
+// student's exponentials.)
+bool cached_path_applies(const KdArgs& a) {
+  return a.nvec_s > (kCachedGroups - 1) * kCB && !(a.cscale != 0.0f && a.need_lse1);
+}
 
 hipError_t launch_kd_cached(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream) {
   switch (teacher_kind) {

@@ -28,6 +28,7 @@ template <int BLOCK, int TEACHER, bool GRAD>
 __global__ __launch_bounds__(BLOCK) void kd_rows_kernel(const KdArgs a) {
   __shared__ float red[4 * 3 * (BLOCK / kWave)];
   __shared__ uint16_t patch[TEACHER == kTopk && GRAD ? kTopkMax : 1];
+  __shared__ int y_in_support;  // top-k teacher: the label is one of the k support positions of this row
   const int tid = threadIdx.x;
   const int64_t row = blockIdx.x;
   const int V = a.V, nvec = a.nvec_s;
@@ -112,11 +113,16 @@ __global__ __launch_bounds__(BLOCK) void kd_rows_kernel(const KdArgs a) {
     kd = kd < 0.0f ? 0.0f : kd;  // a KL divergence is >= 0; NaN passes through
   }
 
+  const bool ce = GRAD && a.cscale != 0.0f;                           // uniform: hard-label CE gradient wanted
+  const bool bad_label = a.labels && (unsigned)y >= (unsigned)V;      // uniform
+  const GradCoef gk = make_grad_coef(acc[0], acc[1], acc[2], c, a.gscale, a.cscale, TEACHER != kNone, lse1);
+
   if constexpr (TEACHER == kTopk) {
     bad_index = __syncthreads_or(bad_index);
+    if (tid == 0) y_in_support = 0;
+    __syncthreads();
     const int32_t* irow = a.tidx + row * (int64_t)a.k;
     const float* vrow = a.tval + row * (int64_t)a.k;
-    const float ws = a.gscale / acc[0].z, ratio = acc[0].z / acc[1].z;
     float part = 0.0f;
     if (!bad_index) {
       for (int j = tid; j < a.k; j += BLOCK) {
@@ -127,8 +133,11 @@ __global__ __launch_bounds__(BLOCK) void kd_rows_kernel(const KdArgs a) {
         part = __builtin_fmaf(exp2_fast(lpt), (lpt - lps) * kLn2, part);
         if constexpr (GRAD) {
           // the value this position finally holds, from fp32, rounded once
-          const float gj =
-              __builtin_fmaf(-exp2_fast(b - acc[1].r), ratio, exp2_fast(__builtin_fmaf(sj, c, -acc[0].r))) * ws;
+          float gj = grad_pair_elem(sj, b, gk);
+          if (ce && irow[j] == y) {
+            gj -= a.cscale;
+            y_in_support = 1;
+          }
           patch[j] = one_bf16(gj);
         }
       }
@@ -141,8 +150,7 @@ __global__ __launch_bounds__(BLOCK) void kd_rows_kernel(const KdArgs a) {
   if (tid == 0) {
     int flags = 0;
     if (bad_index) flags |= 2;  // NPD_DEV_BAD_TOPK_INDEX
-    const bool bad_label = a.labels && (unsigned)y >= (unsigned)V;
-    if (bad_label && (a.nll || a.tnll)) flags |= 1;  // NPD_DEV_BAD_LABEL
+    if (bad_label && (a.nll || a.tnll || ce)) flags |= 1;  // NPD_DEV_BAD_LABEL
     if (a.kd) a.kd[row] = kd;
     if (a.nll) a.nll[row] = bad_label ? __builtin_nanf("") : __fsub_rn(lse1_s, s_y);
     if (TEACHER == kDense && a.tnll) {
@@ -155,20 +163,14 @@ __global__ __launch_bounds__(BLOCK) void kd_rows_kernel(const KdArgs a) {
 
   // ---- sweep 2: gradient, last group first
   if constexpr (GRAD) {
-    const float rs = acc[0].r, rt = acc[1].r;
-    const float ws = a.gscale / acc[0].z;
-    const float ratio = TEACHER == kDense ? acc[0].z / acc[1].z : 0.0f;
-    if (TEACHER == kTopk && bad_index) {
+    if ((TEACHER == kTopk && bad_index) || (ce && bad_label)) {  // uniform: the row cannot be differentiated
       const uint16_t qnan = 0x7fc0;
       for (int e = tid; e < V; e += BLOCK) grow[e] = qnan;
       return;
     }
     for (int e = nvec * 8 + tid; e < V; e += BLOCK) {
-      float gv = exp2_fast(__builtin_fmaf(bf16_one(srow[e]), c, -rs)) * ws;
-      if constexpr (TEACHER == kDense)
-        gv = __builtin_fmaf(-exp2_fast(__builtin_fmaf(bf16_one(trow[e]), c, -rt)), ratio,
-                            exp2_fast(__builtin_fmaf(bf16_one(srow[e]), c, -rs))) * ws;
-      grow[e] = one_bf16(gv);
+      const float xs = bf16_one(srow[e]);
+      grow[e] = one_bf16(TEACHER == kDense ? grad_dense_elem(xs, bf16_one(trow[e]), gk) : grad_student_elem(xs, gk));
     }
     for (int i = nvec - 1 - tid; i >= 0; i -= BLOCK) {
       float xs[8], gv[8];
@@ -177,12 +179,10 @@ __global__ __launch_bounds__(BLOCK) void kd_rows_kernel(const KdArgs a) {
         float xt[8];
         unpack8(reinterpret_cast<const uint4*>(trow)[i], xt);
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-          gv[j] = __builtin_fmaf(-exp2_fast(__builtin_fmaf(xt[j], c, -rt)), ratio,
-                                 exp2_fast(__builtin_fmaf(xs[j], c, -rs))) * ws;
+        for (int j = 0; j < 8; ++j) gv[j] = grad_dense_elem(xs[j], xt[j], gk);
       } else {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) gv[j] = exp2_fast(__builtin_fmaf(xs[j], c, -rs)) * ws;
+        for (int j = 0; j < 8; ++j) gv[j] = grad_student_elem(xs[j], gk);
       }
       uint4 o;
       o.x = pack_bf16(gv[0], gv[1]);
@@ -191,12 +191,18 @@ __global__ __launch_bounds__(BLOCK) void kd_rows_kernel(const KdArgs a) {
       o.w = pack_bf16(gv[6], gv[7]);
       reinterpret_cast<uint4*>(grow)[i] = o;
     }
-    if constexpr (TEACHER == kTopk) {
-      // the k support positions are overwritten with their final values once the dense stores of
-      // the whole workgroup are ordered before them
+    if (TEACHER == kTopk || ce) {  // uniform
+      // the k support positions and the label position are overwritten with their final values once the dense
+      // stores of the whole workgroup are ordered before them
       __syncthreads();
-      const int32_t* irow = a.tidx + row * (int64_t)a.k;
-      for (int j = tid; j < a.k; j += BLOCK) grow[irow[j]] = patch[j];
+      if constexpr (TEACHER == kTopk) {
+        const int32_t* irow = a.tidx + row * (int64_t)a.k;
+        for (int j = tid; j < a.k; j += BLOCK) grow[irow[j]] = patch[j];
+      }
+      if (ce && tid == 0 && !(TEACHER == kTopk && y_in_support)) {
+        const float gy = TEACHER == kDense ? grad_dense_elem(s_y, t_y, gk) : grad_student_elem(s_y, gk);
+        grow[y] = one_bf16(gy - a.cscale);
+      }
     }
   }
 }

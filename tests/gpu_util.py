@@ -62,7 +62,7 @@ def check_row_canaries(full, T, V, stride):
 
 
 def run_gpu_kd(s, mask, *, t=None, idx=None, val=None, labels=None, tau=1.0, grad_scale=1.0, want_grad=True,
-               inplace=False, want_tnll=None):
+               inplace=False, want_tnll=None, ce_grad_scale=0.0):
     """Call npd_kd_loss_fwd_bwd with guarded outputs.  Returns a dict of host numpy arrays."""
     T, V = s.shape
     stride = s.stride(0)
@@ -81,7 +81,7 @@ def run_gpu_kd(s, mask, *, t=None, idx=None, val=None, labels=None, tau=1.0, gra
         else:
             gfull, g = guarded_rows(T, V, stride)
     binding.npd_kd_loss_fwd_bwd(s, mask, teacher_dense=t, teacher_idx=idx, teacher_val=val, labels=labels, tau=tau,
-                                grad_scale=grad_scale, grad_out=g, kd_tok=kd.t if kd else None,
+                                grad_scale=grad_scale, ce_grad_scale=ce_grad_scale, grad_out=g, kd_tok=kd.t if kd else None,
                                 nll_tok=nll.t if nll else None, teacher_nll_tok=tnll.t if tnll else None,
                                 lse_tok=lse.t, dev_status=status)
     torch.cuda.synchronize()

@@ -25,7 +25,7 @@ def test_exports_match_header(lib):
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None
-    assert lib.npd_version() >= 100
+    assert lib.npd_version() >= 101
     for st in range(8):
         assert len(lib.npd_status_string(st)) > 0
     assert lib.npd_status_string(0) == b"ok"
@@ -33,8 +33,8 @@ def test_exports_match_header(lib):
 
 def test_desc_layout_matches_header():
     # n_tokens i64, vocab i32, teacher_kind i32, student_stride i64, teacher_stride i64, topk i32, flags u32,
-    # tau f32, grad_scale f32
-    assert ctypes.sizeof(binding.KdDesc) == 48
+    # tau f32, grad_scale f32, ce_grad_scale f32 (+ tail padding)
+    assert ctypes.sizeof(binding.KdDesc) == 56 and binding.KdDesc.ce_grad_scale.offset == 48
     assert binding.KdDesc.student_stride.offset == 16 and binding.KdDesc.tau.offset == 40
 
 
@@ -45,7 +45,7 @@ def _desc(**kw):
     d = binding.KdDesc()
     d.n_tokens, d.vocab, d.teacher_kind = 16, 64, binding.NPD_TEACHER_DENSE_BF16
     d.student_stride = d.teacher_stride = 64
-    d.topk, d.flags, d.tau, d.grad_scale = 0, 0, 1.0, 1.0
+    d.topk, d.flags, d.tau, d.grad_scale, d.ce_grad_scale = 0, 0, 1.0, 1.0, 0.0
     for k, v in kw.items():
         setattr(d, k, v)
     return d
@@ -77,6 +77,9 @@ def test_kd_argument_validation(lib):
     assert _kd(lib, _desc(), grad=None) == E_NULL                   # gradient wanted but no buffer
     assert _kd(lib, _desc(flags=1)) == E_VALUE                      # forward-only with a gradient buffer
     assert _kd(lib, _desc(), nll=FAKE + 0x400000) == E_NULL         # NLL without labels
+    assert _kd(lib, _desc(ce_grad_scale=0.1)) == E_NULL             # CE gradient without labels
+    assert _kd(lib, _desc(ce_grad_scale=float("inf")), labels=FAKE + 0x800000) == E_VALUE
+    assert _kd(lib, _desc(ce_grad_scale=0.1, flags=1), labels=FAKE + 0x800000, grad=None) == E_VALUE
     assert _kd(lib, _desc(), grad=FAKE) == E_ALIAS                  # in place without the flag
     assert _kd(lib, _desc(flags=2)) == E_ALIAS                      # flag without aliasing
     assert _kd(lib, _desc(), grad=FAKE + 2) == E_ALIAS              # partial overlap with the student

@@ -504,3 +504,59 @@ def test_cfg4_full_size_inplace_sampled_rows(oracle):
     np.testing.assert_array_equal(seg["count"], rseg["count"])
     np.testing.assert_array_equal(seg["token_to_sample"], rseg["token_to_sample"])
     np.testing.assert_allclose(seg["sum"], rseg["sum"], rtol=1e-5, atol=1e-5)
+
+
+# --------------------------------------------------------------------------- composite loss of Eq. 1 (KD + hard-label CE)
+
+@pytest.mark.parametrize("V,tau,gs,cs,inplace", [
+    (151936, 1.0, 0.9, 0.1, False),    # lambda = 0.9 (the paper's default): row-resident kernel, folded weights
+    (151936, 1.0, 0.0, 1.0, True),     # CE only, in place
+    (151936, 1.0, -0.5, 1.0, False),   # weights of opposite sign: precise form
+    (151936, 2.0, 0.9, 0.1, False),    # tau != 1: the CE softmax needs its own exponentials
+    (4099, 1.0, 0.9, 0.1, False),      # small vocabulary, ragged tail
+    (1000, 2.0, 0.5, 0.5, True),
+])
+def test_composite_gradient_dense(oracle, V, tau, gs, cs, inplace):
+    n_rows, row_len = (2, 64) if V > 100000 else (2, 160)
+    w = synth.scaled(synth.config(1), n_rows=n_rows, row_len=row_len, vocab=V, length_lo=8, length_hi=64)
+    _say(f"composite dense V={V} tau={tau} grad_scale={gs} ce_grad_scale={cs} inplace={inplace}")
+    lay, s, t, mask, labels = _inputs(w)
+    ref = oracle.kd_dense(_bits(s), _bits(t), lay.labels, lay.loss_mask, tau=tau, grad_scale=gs, ce_grad_scale=cs)
+    gpu = run_gpu_kd(s.clone() if inplace else s, mask, t=t, labels=labels, tau=tau, grad_scale=gs, ce_grad_scale=cs,
+                     inplace=inplace)
+    assert gpu["status"] == 0
+    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle, grad_scale=abs(gs) + abs(cs) * tau, tau=tau)
+    # the label position carries the -ce_grad_scale of the one-hot target: a sizeable negative entry there
+    if cs > 0 and gs >= 0:
+        rows = np.flatnonzero(lay.loss_mask)[:8]
+        assert (gpu["grad"][rows, lay.labels[rows]] < -0.5 * cs).all()
+
+
+@pytest.mark.parametrize("V,k,tau,inplace", [(151936, 64, 1.0, False), (151936, 10, 2.0, True), (5003, 20, 1.0, False)])
+def test_composite_gradient_topk(oracle, V, k, tau, inplace):
+    n_rows, row_len = (2, 64) if V > 100000 else (2, 128)
+    w = synth.scaled(synth.config(2), n_rows=n_rows, row_len=row_len, vocab=V, length_lo=8, length_hi=64, topk=k)
+    _say(f"composite top-k V={V} k={k} tau={tau} inplace={inplace}")
+    lay, s, _, mask, labels = _inputs(w, dense_teacher=False)
+    idx, val = synth.make_topk_teacher(w, s)
+    # every other row: the label is one of the teacher's support positions (unless it already is)
+    for r in range(0, w.n_tokens, 2):
+        if not (idx[r] == int(lay.labels[r])).any():
+            idx[r, r % k] = int(lay.labels[r])
+    ref = oracle.kd_topk(_bits(s), idx.cpu().numpy(), val.cpu().numpy(), lay.labels, lay.loss_mask, tau=tau,
+                         grad_scale=0.9, ce_grad_scale=0.1)
+    gpu = run_gpu_kd(s.clone() if inplace else s, mask, idx=idx, val=val, labels=labels, tau=tau, grad_scale=0.9,
+                     ce_grad_scale=0.1, inplace=inplace)
+    assert gpu["status"] == 0 and ref["bad_index_rows"] == 0
+    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle, grad_scale=0.9 + 0.1 * tau, tau=tau)
+
+
+def test_composite_gradient_bad_label_poisons_row():
+    V = 151936
+    s = torch.randn((3, V), device=dev()).to(torch.bfloat16)
+    t = torch.randn((3, V), device=dev()).to(torch.bfloat16)
+    labels = torch.tensor([5, V, 7], dtype=torch.int32, device=dev())
+    mask = torch.ones(3, dtype=torch.uint8, device=dev())
+    gpu = run_gpu_kd(s, mask, t=t, labels=labels, grad_scale=0.9, ce_grad_scale=0.1)
+    assert gpu["status"] == binding.NPD_DEV_BAD_LABEL
+    assert np.isnan(gpu["grad"][1]).all() and np.isfinite(gpu["grad"][[0, 2]]).all() and np.isfinite(gpu["kd"]).all()
