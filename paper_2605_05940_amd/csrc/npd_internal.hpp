@@ -36,7 +36,7 @@ struct KdArgs {
 hipError_t launch_kd(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream);
 
 // row-resident kernels for large vocabularies (npd_kd_cached.hip)
-bool cached_path_applies(const KdArgs& a);
+bool cached_path_applies(const KdArgs& a, int teacher_kind, bool want_grad);
 hipError_t launch_kd_cached(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream);
 
 hipError_t launch_segment_reduce(int64_t T, int32_t S, const float* values, const uint8_t* mask, const int32_t* cu,

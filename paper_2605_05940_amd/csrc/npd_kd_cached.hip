@@ -464,25 +464,44 @@ static hipError_t launch_cached_lse1(const KdArgs& a, hipStream_t stream) {
 #ifndef NPD_PERSIST
 #define NPD_PERSIST false
 #endif
-constexpr int kCachedGroups = 19;  // covers vocabularies of 147,464 .. 155,648 tokens entirely, larger ones partly
+// Groups per thread that the unrolled part of the kernel covers.  19 fits vocabularies of 147,464 .. 155,648
+// tokens entirely (larger ones stream the remainder twice); 16 and 13 do the same for the gradient kernels at
+// ~131k and ~104k tokens.  A row must have more than (CS - 1) * 1024 groups for the CS variant.
+static int unrolled_groups(const KdArgs& a, bool want_grad) {
+  const int nit = (a.nvec_s + kCB - 1) / kCB;
+  if (nit >= 19) return 19;
+  if (want_grad && nit >= 16) return 16;
+  if (want_grad && nit >= 13) return 13;
+  return 0;
+}
 
-// Row-resident path: 16-byte aligned rows of more than (kCachedGroups - 1) * 1024 groups.
-// (The CE softmax of the composite loss has no temperature; this path covers it at tau = 1, where it shares the
-// student's exponentials.)
-bool cached_path_applies(const KdArgs& a) {
-  return a.nvec_s > (kCachedGroups - 1) * kCB && !(a.cscale != 0.0f && a.need_lse1);
+// Row-resident path: 16-byte aligned rows that are long enough.  (The CE softmax of the composite loss has no
+// temperature; this path covers it at tau = 1, where it shares the student's exponentials.)
+bool cached_path_applies(const KdArgs& a, int teacher_kind, bool want_grad) {
+  const bool grad = want_grad && teacher_kind != kNone;
+  return unrolled_groups(a, grad) > 0 && !(a.cscale != 0.0f && a.need_lse1);
+}
+
+template <int CS>
+static hipError_t launch_grad_variants(const KdArgs& a, int teacher_kind, hipStream_t stream) {
+  constexpr int CSR = NPD_CSR < CS ? NPD_CSR : CS;
+  if (teacher_kind == kDense) return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, NPD_PERSIST>(a, stream);
+  return launch_cached_lse1<CS, (CS < 16 ? CS : 16), 0, 3, kTopk, true, false>(a, stream);
 }
 
 hipError_t launch_kd_cached(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream) {
+  const bool grad = want_grad && teacher_kind != kNone;
+  if (grad) {
+    switch (unrolled_groups(a, true)) {
+      case 19: return launch_grad_variants<19>(a, teacher_kind, stream);
+      case 16: return launch_grad_variants<16>(a, teacher_kind, stream);
+      default: return launch_grad_variants<13>(a, teacher_kind, stream);
+    }
+  }
   switch (teacher_kind) {
-    case kDense:
-      return want_grad ? launch_cached_lse1<kCachedGroups, NPD_CSR, 9, NPD_TD, kDense, true, NPD_PERSIST>(a, stream)
-                       : launch_cached_lse1<kCachedGroups, 0, 0, 4, kDense, false, false>(a, stream);
-    case kTopk:
-      return want_grad ? launch_cached_lse1<kCachedGroups, 16, 0, 3, kTopk, true, false>(a, stream)
-                       : launch_cached_lse1<kCachedGroups, 0, 0, 4, kTopk, false, false>(a, stream);
-    default:
-      return launch_cached_lse1<kCachedGroups, 0, 0, 4, kNone, false, false>(a, stream);
+    case kDense: return launch_cached_lse1<19, 0, 0, 4, kDense, false, false>(a, stream);
+    case kTopk: return launch_cached_lse1<19, 0, 0, 4, kTopk, false, false>(a, stream);
+    default: return launch_cached_lse1<19, 0, 0, 4, kNone, false, false>(a, stream);
   }
 }
 

@@ -60,6 +60,10 @@ def test_cfg0_tiny_dense_full(oracle):
     (7, 7, 1.0, 1.0),                # shorter than one 128-bit group
     (1, 8, 1.0, 1.0),                # single-token vocabulary: KL = 0, grad = 0
     (262144, 262144, 1.0, 1.0),      # largest vocabulary
+    (128256, 128256, 1.0, 1.0),      # 16 groups per thread, the last one ragged
+    (131072, 131072, 2.0, 1.0),      # exactly 16 full groups per thread
+    (102400, 102400, 1.0, 1.0),      # 13 groups per thread
+    (124000, 124000, 1.0, 1.0),      # 16 > 15.1 groups: the 13-group variant streams the rest twice
 ])
 def test_dense_shapes(oracle, V, stride, tau, scale):
     n_rows, row_len = (2, 96) if V > 100000 else (2, 160)
@@ -157,6 +161,7 @@ def test_bad_label_sets_status_and_nan(oracle):
 @pytest.mark.parametrize("V,k,tau,scale,inplace", [
     (151936, 64, 2.0, 1.0, False),   # config 2's shape
     (151936, 10, 1.0, 1.0, True),    # the paper's default k, in place
+    (128256, 64, 2.0, 1.0, False),   # 16 groups per thread
     (5003, 200, 2.0, -2.0, False),   # k larger than a wave, unaligned rows
     (300, 300, 1.0, 1.0, False),     # k = V
     (40000, 1, 1.0, 1.0, False),     # k = 1
@@ -560,3 +565,15 @@ def test_composite_gradient_bad_label_poisons_row():
     gpu = run_gpu_kd(s, mask, t=t, labels=labels, grad_scale=0.9, ce_grad_scale=0.1)
     assert gpu["status"] == binding.NPD_DEV_BAD_LABEL
     assert np.isnan(gpu["grad"][1]).all() and np.isfinite(gpu["grad"][[0, 2]]).all() and np.isfinite(gpu["kd"]).all()
+
+
+def test_policy_lag_monitor_is_the_same_entry_point_with_roles_swapped(oracle):
+    """The paper tracks KL(pi_learner || pi_generator) per step: forward-only npd_kd_loss_fwd_bwd with the learner's
+    logits in the teacher slot and the generator's in the student slot, then a per-sample mean."""
+    w = synth.scaled(synth.config(1), n_rows=1, row_len=96, vocab=151936, length_lo=8, length_hi=48)
+    lay, gen, learner, mask, labels = _inputs(w)
+    gpu = run_gpu_kd(gen, mask, t=learner, want_grad=False)
+    ref = oracle.kd_dense(_bits(gen), _bits(learner), None, lay.loss_mask, want_grad=False)
+    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle)
+    rev = oracle.kd_dense(_bits(learner), _bits(gen), None, lay.loss_mask, want_grad=False)
+    assert np.abs(rev["kd"] - ref["kd"]).max() > 1e-3      # the direction matters
