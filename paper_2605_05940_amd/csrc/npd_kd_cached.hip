@@ -458,6 +458,9 @@ static hipError_t launch_cached_lse1(const KdArgs& a, hipStream_t stream) {
 #ifndef NPD_CSR
 #define NPD_CSR 12
 #endif
+#ifndef NPD_TOPK_CSR
+#define NPD_TOPK_CSR 12
+#endif
 #ifndef NPD_TD
 #define NPD_TD 2
 #endif
@@ -486,7 +489,7 @@ template <int CS>
 static hipError_t launch_grad_variants(const KdArgs& a, int teacher_kind, hipStream_t stream) {
   constexpr int CSR = NPD_CSR < CS ? NPD_CSR : CS;
   if (teacher_kind == kDense) return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, NPD_PERSIST>(a, stream);
-  return launch_cached_lse1<CS, (CS < 16 ? CS : 16), 0, 3, kTopk, true, false>(a, stream);
+  return launch_cached_lse1<CS, (CS < NPD_TOPK_CSR ? CS : NPD_TOPK_CSR), 0, 3, kTopk, true, false>(a, stream);
 }
 
 hipError_t launch_kd_cached(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream) {
