@@ -445,3 +445,51 @@ int32_t npd_oracle_delta_ifd(int32_t P, const double *mean_nll_student, const do
   }
   return kept;
 }
+
+/* ------------------------------------------------------------------------- */
+/* Teacher-side top-k record (Sec. 3.1, "record only the top-k logits").      */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * For every scored position: the k vocabulary ids with the largest teacher logits, largest
+ * first, equal logits in order of increasing id, by k plain selection scans.  val holds the
+ * logits themselves, or (log_probs != 0) their log-softmax over the k selected entries, which
+ * is the teacher distribution Eq. 2 uses.  Unscored positions get ids 0..k-1 and values 0.
+ * t: [T, stride] bf16 bit patterns.  taken: caller-independent scratch is allocated per thread.
+ */
+void npd_oracle_teacher_topk_bf16(int64_t T, int64_t V, int32_t k, const uint16_t *t, int64_t t_stride,
+                                  const uint8_t *mask, int log_probs, int32_t *idx, double *val) {
+#pragma omp parallel
+  {
+    double *row = (double *)malloc(sizeof(double) * (size_t)V);
+    uint8_t *taken = (uint8_t *)malloc((size_t)V);
+#pragma omp for schedule(dynamic, 1)
+    for (int64_t r = 0; r < T; ++r) {
+      int32_t *ir = idx + r * (int64_t)k;
+      double *vr = val + r * (int64_t)k;
+      if (mask && !mask[r]) {
+        for (int32_t j = 0; j < k; ++j) {
+          ir[j] = j;
+          vr[j] = 0.0;
+        }
+        continue;
+      }
+      for (int64_t c = 0; c < V; ++c) row[c] = bf16_to_double(t[r * t_stride + c]);
+      memset(taken, 0, (size_t)V);
+      for (int32_t j = 0; j < k; ++j) {
+        int64_t best = -1;
+        for (int64_t c = 0; c < V; ++c)
+          if (!taken[c] && (best < 0 || row[c] > row[best])) best = c; /* first of equals wins */
+        taken[best] = 1;
+        ir[j] = (int32_t)best;
+        vr[j] = row[best];
+      }
+      if (log_probs) {
+        const double lse = logsumexp(vr, k);
+        for (int32_t j = 0; j < k; ++j) vr[j] -= lse;
+      }
+    }
+    free(row);
+    free(taken);
+  }
+}

@@ -39,6 +39,8 @@ def lib():
                                               _p, _p, _p, _p]
         L.npd_oracle_nll_bf16.restype = None
         L.npd_oracle_nll_bf16.argtypes = [_i64, _i64, _p, _i64, _p, _p, _p, _p]
+        L.npd_oracle_teacher_topk_bf16.restype = None
+        L.npd_oracle_teacher_topk_bf16.argtypes = [_i64, _i64, _i32, _p, _i64, _p, ctypes.c_int, _p, _p]
         L.npd_oracle_segment_reduce.restype = ctypes.c_int
         L.npd_oracle_segment_reduce.argtypes = [_i64, _i32, _p, _p, _p, _p, _p, _p, _p]
         L.npd_oracle_delta_ifd.restype = _i32
@@ -136,6 +138,21 @@ def nll(o, labels, mask=None):
         o = _c(o, np.float64)
         lib().npd_oracle_nll_f64(T, V, _ptr(o), _ptr(labels), _ptr(mask), _ptr(out), _ptr(lse))
     return dict(nll=out, lse=lse)
+
+
+def teacher_topk(t_bits, k, mask=None, log_probs=True):
+    """Top-k record of teacher logits ``t_bits`` (uint16 bf16 bits [T, V]): ids int32 [T, k] (largest logit first,
+    equal logits by increasing id) and float64 values [T, k] (the logits, or their log-softmax over the k)."""
+    T, V = t_bits.shape
+    assert t_bits.dtype == np.uint16 and t_bits.strides[1] == 2 and 1 <= k <= V
+    if mask is not None:
+        mask = _c(mask, np.uint8)
+        assert mask.shape == (T,)
+    idx = np.empty((T, k), np.int32)
+    val = np.empty((T, k))
+    lib().npd_oracle_teacher_topk_bf16(T, V, k, t_bits.ctypes.data, t_bits.strides[0] // 2, _ptr(mask),
+                                       1 if log_probs else 0, _ptr(idx), _ptr(val))
+    return dict(idx=idx, val=val)
 
 
 def segment_reduce(x, mask, cu_seqlens, want_token_to_sample=True):

@@ -455,3 +455,53 @@ def test_composite_gradient_matches_autograd_and_sums_to_zero(oracle):
     bad[1] = V
     g = oracle.kd_dense(s, t, bad, tau=1.0, ce_grad_scale=1.0)["grad"]
     assert np.isnan(g[1]).all() and np.isfinite(g[[0, 2, 3]]).all()
+
+
+# --------------------------------------------------------------------------- teacher-side top-k record (Sec. 3.1)
+
+def _bf16_bits(x):
+    return torch.from_numpy(np.asarray(x, np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+def test_teacher_topk_against_library_sort_and_ties(oracle):
+    T, V, k = 6, 3000, 17
+    x = RNG.normal(0, 3, size=(T, V))
+    x[1, :] = 0.5                                  # a constant row: the k lowest ids
+    x[2, 100:140] = x[2].max() + 1.0               # forty equal maxima: ids 100..116
+    bits = _bf16_bits(x)
+    vals = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).double().numpy()   # what bf16 really holds
+    out = oracle.teacher_topk(bits, k, log_probs=False)
+    for r in range(T):
+        order = np.lexsort((np.arange(V), -vals[r]))[:k]         # library: value descending, then id ascending
+        np.testing.assert_array_equal(out["idx"][r], order)
+        np.testing.assert_array_equal(out["val"][r], vals[r][order])
+    assert out["idx"][1].tolist() == list(range(k)) and out["idx"][2].tolist() == list(range(100, 117))
+    tv = torch.topk(torch.from_numpy(vals), k, dim=1).values.numpy()             # values agree with torch.topk
+    np.testing.assert_array_equal(out["val"], tv)
+    # k = 1 is the arg-max (first of equals); k = V is a full stable sort
+    np.testing.assert_array_equal(oracle.teacher_topk(bits, 1, log_probs=False)["idx"][:, 0], vals.argmax(1))
+    full = oracle.teacher_topk(bits[:2, :50].copy(), 50, log_probs=False)
+    assert sorted(full["idx"][0].tolist()) == list(range(50))
+
+
+def test_teacher_topk_log_probs_and_consistency_with_eq2(oracle):
+    T, V, k = 4, 500, 9
+    s, t = _rand(T, V, 3.0), _rand(T, V, 3.0)
+    sb, tb = _bf16_bits(s), _bf16_bits(t)
+    raw = oracle.teacher_topk(tb, k, log_probs=False)
+    lp = oracle.teacher_topk(tb, k, log_probs=True)
+    np.testing.assert_array_equal(raw["idx"], lp["idx"])
+    np.testing.assert_allclose(np.exp(lp["val"]).sum(1), 1.0, atol=1e-12)
+    np.testing.assert_allclose(lp["val"], torch.log_softmax(torch.from_numpy(raw["val"]), 1).numpy(), atol=1e-12)
+    # Eq. 2 does not care whether the record holds logits or renormalised log-probabilities
+    a = oracle.kd_topk(sb, raw["idx"], raw["val"].astype(np.float32), tau=2.0)
+    b = oracle.kd_topk(sb, lp["idx"], lp["val"].astype(np.float32), tau=2.0)
+    np.testing.assert_allclose(a["kd"], b["kd"], rtol=1e-6)
+    # with k = V the record reproduces the dense-teacher loss
+    full = oracle.teacher_topk(tb, V, log_probs=False)
+    np.testing.assert_allclose(oracle.kd_topk(sb, full["idx"], full["val"].astype(np.float32))["kd"],
+                               oracle.kd_dense(sb, tb)["kd"], rtol=1e-9)
+    # unscored positions: ids 0..k-1, values 0
+    m = oracle.teacher_topk(tb, k, mask=np.array([1, 0, 1, 1], np.uint8))
+    assert m["idx"][1].tolist() == list(range(k)) and (m["val"][1] == 0).all()
+    np.testing.assert_array_equal(m["idx"][[0, 2, 3]], lp["idx"][[0, 2, 3]])
