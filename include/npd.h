@@ -150,6 +150,26 @@ npd_status npd_kd_loss_fwd_bwd(const npd_kd_desc* desc, const void* student_logi
                                float* teacher_nll_tok, float* lse_tok, int32_t* dev_status, void* workspace,
                                size_t workspace_bytes, void* stream);
 
+/* npd_teacher_topk flags */
+enum { NPD_TOPK_LOG_PROBS = 1u /* values = log-softmax of the k selected logits instead of the logits */ };
+
+/*
+ * Teacher-side top-k record (Sec. 3.1, "record only the top-k logits"; Alg. 1, Phase 2): for every
+ * scored position p the k vocabulary ids with the largest teacher logits and their values, in the
+ * format npd_kd_loss_fwd_bwd takes as NPD_TEACHER_TOPK.
+ *
+ *   topk_idx[p, 0..k)  ids, largest logit first; equal logits in order of increasing id (exact, deterministic)
+ *   topk_val[p, 0..k)  the logits (as fp32), or with NPD_TOPK_LOG_PROBS their log-softmax over the k entries
+ *                      (the renormalised teacher distribution of Eq. 2)
+ *   positions with loss_mask[p] == 0 get ids 0..k-1 and values 0 (their logits are not read)
+ *
+ *   teacher_logits bf16 [T, teacher_stride] (finite), loss_mask uint8 [T] or NULL (all scored),
+ *   topk_idx int32 [T, k], topk_val fp32 [T, k].  1 <= k <= min(V, 4096) (larger k: NPD_ERR_UNSUPPORTED).
+ */
+npd_status npd_teacher_topk(int64_t n_tokens, int32_t vocab, int64_t teacher_stride, int32_t k, uint32_t flags,
+                            const void* teacher_logits, const uint8_t* loss_mask, int32_t* topk_idx,
+                            float* topk_val, void* stream);
+
 /*
  * Per-sample reduction of a per-position quantity over the packed layout (the
  * per-sample losses behind Eq. 1-3): for sample i in [0, S)

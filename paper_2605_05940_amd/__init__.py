@@ -4,4 +4,4 @@
 generators; ``build`` compiles the library.  Nothing here computes on the CPU.
 """
 from .binding import (NpdError, npd_delta_ifd_score, npd_kd_loss_fwd_bwd, npd_segment_reduce,  # noqa: F401
-                      npd_workspace_bytes, version)
+                      npd_teacher_topk, npd_workspace_bytes, version)

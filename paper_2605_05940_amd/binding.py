@@ -19,9 +19,10 @@ NPD_FLAG_FWD_ONLY, NPD_FLAG_INPLACE_GRAD = 1, 2
 NPD_DEV_BAD_LABEL, NPD_DEV_BAD_TOPK_INDEX, NPD_DEV_BAD_CU_SEQLENS = 1, 2, 4
 NPD_ZONE_DEGENERATE, NPD_ZONE_PROXIMAL, NPD_ZONE_DISCONNECT, NPD_ZONE_INVALID = 0, 1, 2, 3
 NPD_IFD_REQUIRE_TEACHER_LE_1 = 1
+NPD_TOPK_LOG_PROBS = 1
 
 EXPORTS = ("npd_version", "npd_status_string", "npd_workspace_bytes", "npd_kd_loss_fwd_bwd",
-           "npd_segment_reduce", "npd_delta_ifd_score")
+           "npd_segment_reduce", "npd_delta_ifd_score", "npd_teacher_topk")
 
 
 class NpdError(RuntimeError):
@@ -62,6 +63,9 @@ def load() -> ctypes.CDLL:
         L.npd_delta_ifd_score.restype = ctypes.c_int
         L.npd_delta_ifd_score.argtypes = ([ctypes.c_int32, ctypes.c_int32] + [_vp] * 5 +
                                           [ctypes.c_float, ctypes.c_float, ctypes.c_uint32] + [_vp] * 7)
+        L.npd_teacher_topk.restype = ctypes.c_int
+        L.npd_teacher_topk.argtypes = ([ctypes.c_int64, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
+                                        ctypes.c_uint32] + [_vp] * 5)
         _lib = L
     return _lib
 
@@ -192,3 +196,17 @@ def npd_delta_ifd_score(mean_nll_student: torch.Tensor, mean_nll_teacher: torch.
         lo, hi, flags, _ptr(ifd_student, torch.float32), _ptr(ifd_teacher, torch.float32),
         _ptr(delta, torch.float32), _ptr(zone, torch.uint8), _ptr(keep, torch.uint8),
         _ptr(keep_count, torch.int32), _stream()))
+
+
+def npd_teacher_topk(teacher_logits: torch.Tensor, k: int, *, topk_idx: torch.Tensor, topk_val: torch.Tensor,
+                     loss_mask: Optional[torch.Tensor] = None, log_probs: bool = True) -> None:
+    """Enqueue the teacher-side top-k extraction on the current stream (see ``npd_teacher_topk`` in npd.h)."""
+    T, V = teacher_logits.shape
+    for name, t in (("topk_idx", topk_idx), ("topk_val", topk_val)):
+        if t.shape != (T, k) or not t.is_contiguous():
+            raise ValueError(f"{name} must be contiguous [T, k]")
+    if loss_mask is not None and (loss_mask.numel() != T or not loss_mask.is_contiguous()):
+        raise ValueError("loss_mask must be contiguous with T elements")
+    _check(load().npd_teacher_topk(T, V, _row_stride(teacher_logits), k, NPD_TOPK_LOG_PROBS if log_probs else 0,
+                                   _ptr(teacher_logits, torch.bfloat16), _ptr(loss_mask, torch.uint8),
+                                   _ptr(topk_idx, torch.int32), _ptr(topk_val, torch.float32), _stream()))

@@ -49,7 +49,7 @@ npd_status check_desc(const npd_kd_desc* d) {
 
 extern "C" {
 
-int npd_version(void) { return 101; }
+int npd_version(void) { return 102; }
 
 const char* npd_status_string(npd_status st) {
   switch (st) {
@@ -149,6 +149,19 @@ npd_status npd_kd_loss_fwd_bwd(const npd_kd_desc* desc, const void* student_logi
   a.need_lse1 = (d.tau != 1.0f && (nll_tok || teacher_nll_tok || lse_tok || d.ce_grad_scale != 0.0f)) ? 1 : 0;
 
   const hipError_t e = npd::launch_kd(a, d.teacher_kind, !fwd_only, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? NPD_OK : NPD_ERR_HIP;
+}
+
+npd_status npd_teacher_topk(int64_t n_tokens, int32_t vocab, int64_t teacher_stride, int32_t k, uint32_t flags,
+                            const void* teacher_logits, const uint8_t* loss_mask, int32_t* topk_idx,
+                            float* topk_val, void* stream) {
+  if (n_tokens <= 0 || vocab <= 0 || teacher_stride < vocab || k < 1 || k > vocab) return NPD_ERR_SHAPE;
+  if (flags & ~(uint32_t)NPD_TOPK_LOG_PROBS) return NPD_ERR_VALUE;
+  if (!teacher_logits || !topk_idx || !topk_val) return NPD_ERR_NULL;
+  if (k > npd::kTopkMax || n_tokens > 0x7fffffffLL) return NPD_ERR_UNSUPPORTED;
+  const hipError_t e = npd::launch_teacher_topk(n_tokens, vocab, teacher_stride, k, (flags & NPD_TOPK_LOG_PROBS) != 0,
+                                                static_cast<const uint16_t*>(teacher_logits), loss_mask, topk_idx,
+                                                topk_val, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? NPD_OK : NPD_ERR_HIP;
 }
 

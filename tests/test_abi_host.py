@@ -25,7 +25,7 @@ def test_exports_match_header(lib):
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None
-    assert lib.npd_version() >= 101
+    assert lib.npd_version() >= 102
     for st in range(8):
         assert len(lib.npd_status_string(st)) > 0
     assert lib.npd_status_string(0) == b"ok"
@@ -113,6 +113,20 @@ def test_segment_and_ifd_argument_validation(lib):
     assert lib.npd_delta_ifd_score(2, 4, *args, float("nan"), 0.5, 0, *outs, None) == E_VALUE
     assert lib.npd_delta_ifd_score(2, 4, *args, 0.0, 1.0, 8, *outs, None) == E_VALUE
     assert lib.npd_delta_ifd_score(2, 4, None, FAKE, FAKE, FAKE, FAKE, 0.0, 1.0, 0, *outs, None) == E_NULL
+
+
+def test_teacher_topk_argument_validation(lib):
+    ok = (16, 64, 64, 8, 0, FAKE, None, FAKE + 0x100000, FAKE + 0x200000, None)
+    def call(**kw):
+        names = ("T", "V", "stride", "k", "flags", "t", "mask", "idx", "val", "stream")
+        args = dict(zip(names, ok))
+        args.update(kw)
+        return lib.npd_teacher_topk(*[args[n] for n in names])
+    assert call(T=0) == E_SHAPE and call(V=0) == E_SHAPE and call(stride=63) == E_SHAPE
+    assert call(k=0) == E_SHAPE and call(k=65) == E_SHAPE
+    assert call(flags=2) == E_VALUE
+    assert call(t=None) == E_NULL and call(idx=None) == E_NULL and call(val=None) == E_NULL
+    assert call(V=8192, stride=8192, k=5000) == E_UNSUP
 
 
 def test_binding_refuses_host_tensors():

@@ -577,3 +577,67 @@ def test_policy_lag_monitor_is_the_same_entry_point_with_roles_swapped(oracle):
     compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle)
     rev = oracle.kd_dense(_bits(learner), _bits(gen), None, lay.loss_mask, want_grad=False)
     assert np.abs(rev["kd"] - ref["kd"]).max() > 1e-3      # the direction matters
+
+
+# --------------------------------------------------------------------------- teacher-side top-k record (Sec. 3.1)
+
+def _topk_gpu(t, k, mask=None, log_probs=True):
+    T = t.shape[0]
+    idx, val = Guarded(T * k, torch.int32), Guarded(T * k, torch.float32)
+    binding.npd_teacher_topk(t, k, topk_idx=idx.t.view(T, k), topk_val=val.t.view(T, k), loss_mask=mask,
+                             log_probs=log_probs)
+    torch.cuda.synchronize()
+    return idx.check().view(T, k), val.check().view(T, k)
+
+
+@pytest.mark.parametrize("V,stride,k,log_probs", [
+    (151936, 151936, 64, True),      # config 2's record
+    (151936, 151936, 10, False),     # the paper's default k, raw logits
+    (151936, 151936, 1, True),       # arg-max
+    (262144, 262144, 1024, True),    # as many entries as threads
+    (40000, 40000, 2000, False),     # k beyond the per-thread-maximum bound: exact slow path
+    (5003, 5003, 33, True),          # unaligned rows: element-wise path
+    (5003, 5008, 4096, False),       # the largest supported k on unaligned, strided rows
+    (300, 300, 300, True),           # k = V: a full ordering of the row
+])
+def test_teacher_topk_shapes(oracle, V, stride, k, log_probs):
+    T = 24 if V > 100000 else 40
+    w = synth.scaled(synth.config(1), n_rows=1, row_len=T, vocab=V, length_lo=4, length_hi=16)
+    _say(f"teacher top-k V={V} stride={stride} k={k} log_probs={log_probs}")
+    lay, _, t, mask, _ = _inputs(w, stride)
+    idx, val = _topk_gpu(t, k, mask, log_probs)
+    ref = oracle.teacher_topk(_bits(t.contiguous()), k, lay.loss_mask, log_probs)
+    np.testing.assert_array_equal(idx.cpu().numpy(), ref["idx"])                 # ids bit-exact, ties included
+    np.testing.assert_allclose(val.cpu().numpy(), ref["val"], rtol=0, atol=2e-5 if log_probs else 0)
+
+
+def test_teacher_topk_ties_and_degenerate_rows(oracle):
+    V, k = 151936, 64
+    t = (torch.randn((6, V), device=dev()) * 3).to(torch.bfloat16)
+    t[0, :] = 1.5                                    # constant row: ids 0..k-1 (slow path: every element ties)
+    t[1, 1000:9000] = 50.0                           # 8000 equal maxima: the 64 lowest ids among them
+    t[2, :] = 0.0
+    t[2, ::2] = -0.0                                 # +0 and -0 are equal values
+    t[3, 7] = 30.0
+    t[3, 100000:100063] = 30.0                       # exactly k tied maxima, one far from the others
+    t[4, -1] = 99.0                                  # the last element of the row
+    idx, val = _topk_gpu(t, k, None, False)
+    ref = oracle.teacher_topk(_bits(t), k, None, False)
+    np.testing.assert_array_equal(idx.cpu().numpy(), ref["idx"])
+    np.testing.assert_array_equal(val.cpu().numpy().astype(np.float64), ref["val"])
+    assert idx[0].tolist() == list(range(k)) and idx[1].tolist() == list(range(1000, 1000 + k))
+    assert idx[2].tolist() == list(range(k)) and idx[4, 0].item() == V - 1
+    assert idx[3].tolist() == [7] + list(range(100000, 100063))
+
+
+def test_teacher_topk_feeds_the_kd_loss(oracle):
+    """Phase 2 then Phase 3 on the device: extract the record, then distil against it."""
+    w = synth.scaled(synth.config(2), n_rows=1, row_len=64, vocab=151936, length_lo=8, length_hi=32)
+    lay, s, t, mask, labels = _inputs(w)
+    k = 64
+    idx, val = _topk_gpu(t, k, mask, True)
+    gpu = run_gpu_kd(s, mask, idx=idx.contiguous(), val=val.contiguous(), labels=labels, tau=2.0)
+    rec = oracle.teacher_topk(_bits(t), k, lay.loss_mask, True)
+    ref = oracle.kd_topk(_bits(s), rec["idx"], rec["val"], lay.labels, lay.loss_mask, tau=2.0)
+    assert gpu["status"] == 0
+    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle, tau=2.0)
