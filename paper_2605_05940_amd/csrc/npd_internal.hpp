@@ -39,6 +39,9 @@ hipError_t launch_kd(const KdArgs& a, int teacher_kind, bool want_grad, hipStrea
 bool cached_path_applies(const KdArgs& a, int teacher_kind, bool want_grad);
 hipError_t launch_kd_cached(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream);
 
+// compute units of the current device (cached per device)
+int compute_units();
+
 hipError_t launch_teacher_topk(int64_t T, int32_t V, int64_t stride, int32_t k, int log_probs, const uint16_t* t,
                                const uint8_t* mask, int32_t* idx, float* val, hipStream_t stream);
 

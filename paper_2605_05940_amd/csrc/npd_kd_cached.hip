@@ -420,7 +420,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
 }
 
 // compute units of the current device (queried once per device, no allocation)
-static int compute_units() {
+int compute_units() {
   static int cached[64] = {0};
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
