@@ -11,10 +11,10 @@
 // in id order with block-wide scans.
 //
 // teacher_topk_stream_kernel (16-byte aligned rows of at least 8192 elements) reads each row from HBM once: the
-// 16-byte groups of a row are visited in a strided order, so that the first few groups a thread loads sample the
-// whole vocabulary range; the bound comes from that sample alone (the k-th largest of a subset never exceeds the
-// k-th largest of the row), and the rest of the row streams through an 8-deep register window, compared as packed
-// 16-bit integers.  teacher_topk_kernel (any shape) takes the bound from the whole row and reads it twice.
+// 16-byte groups of a row are visited in a strided order, so that the first window of groups a thread loads (12 of
+// the 19 groups of a 151,936-entry row) samples the whole vocabulary range; the bound comes from that sample alone
+// (the k-th largest of a subset never exceeds the k-th largest of the row), and the rest of the row streams through
+// the same 12-deep register window, compared as packed 16-bit integers.  teacher_topk_kernel (any shape) takes the bound from the whole row and reads it twice.
 #include "npd_device.hpp"
 #include "npd_internal.hpp"
 
@@ -274,7 +274,10 @@ __device__ __forceinline__ void rank_sort(TopkShared& sh, const unsigned long lo
   __syncthreads();
 }
 
-constexpr int kDirectRankMax = 192;  // lists up to this length are rank-sorted as they are
+#ifndef NPD_TOPK_DIRECT
+#define NPD_TOPK_DIRECT 192
+#endif
+constexpr int kDirectRankMax = NPD_TOPK_DIRECT;  // lists up to this length are rank-sorted as they are
 
 // Orders the n >= k candidate words in sh.cand (all distinct: the ids differ) and writes the first k as the row's
 // record.  Called by all threads after a barrier that made the candidates visible; ends with a barrier.
@@ -579,7 +582,16 @@ hipError_t launch_teacher_topk(int64_t T, int32_t V, int64_t stride, int32_t k, 
   a.nvec = aligned ? V / 8 : 0;
   a.log_probs = log_probs;
   if (a.nvec >= kTB) {
-    constexpr int kWindow = 8, kSample = 4;
+    // Measured on MI355X, 32,768 x 151,936, k = 10 / 64 / 256: window 8 with a 4-group sample 1.72 / 2.04 / 2.77 ms,
+    // 8 with 8 1.62 / 1.80 / 2.48, 12 with 12 1.57 / 1.69 / 2.29 (a larger sample gives a tighter bound, hence fewer
+    // candidates to cut and order); 12 groups are what fits 64 VGPRs, i.e. two workgroups per CU.
+#ifndef NPD_TOPK_WINDOW
+#define NPD_TOPK_WINDOW 12
+#endif
+#ifndef NPD_TOPK_SAMPLE
+#define NPD_TOPK_SAMPLE 12
+#endif
+    constexpr int kWindow = NPD_TOPK_WINDOW, kSample = NPD_TOPK_SAMPLE;
     const int ngroups = (a.nvec + kTB - 1) / kTB;
     // visiting order: the first kSample groups spread over the row
     int step = ngroups > kSample ? (ngroups + kSample - 1) / kSample : 1;

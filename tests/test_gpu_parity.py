@@ -596,6 +596,9 @@ def _topk_gpu(t, k, mask=None, log_probs=True):
     (151936, 151936, 1, True),       # arg-max
     (262144, 262144, 1024, True),    # as many entries as threads
     (40000, 40000, 2000, False),     # k beyond the per-thread-maximum bound: exact slow path
+    (151936, 151936, 256, True),     # long candidate list: radix cut before the ordering
+    (50001, 50008, 40, False),       # aligned rows with a ragged last group and V mod 8 elements at the end
+    (9000, 9000, 7, True),           # two groups per thread only: shorter than the register window
     (5003, 5003, 33, True),          # unaligned rows: element-wise path
     (5003, 5008, 4096, False),       # the largest supported k on unaligned, strided rows
     (300, 300, 300, True),           # k = V: a full ordering of the row
@@ -628,6 +631,31 @@ def test_teacher_topk_ties_and_degenerate_rows(oracle):
     assert idx[0].tolist() == list(range(k)) and idx[1].tolist() == list(range(1000, 1000 + k))
     assert idx[2].tolist() == list(range(k)) and idx[4, 0].item() == V - 1
     assert idx[3].tolist() == [7] + list(range(100000, 100063))
+
+
+def test_teacher_topk_negative_rows_and_tie_runs(oracle):
+    """Rows of log-probabilities (all negative), rows whose bound is zero, and tie runs at the cut that are
+    longer than the short list but fit the candidate list."""
+    V, k = 151936, 64
+    g = torch.Generator(device="cpu").manual_seed(synth.SEED + 77)
+    base = torch.randn((8, V), generator=g) * 3
+    t = base.clone()
+    t[0] = torch.log_softmax(base[0], dim=-1)                    # all negative
+    t[1] = -torch.abs(base[1]) - 0.5                              # all negative, dense near the top
+    t[2] = torch.where(base[2] > 0, torch.zeros(()), base[2])    # half the row is +0: the bound is zero
+    t[2, 5::7] = -0.0
+    t[3, 20000:23000] = 40.0                                      # 3000 equal maxima: a tie run at the cut
+    t[4] = torch.where(base[4] > 6.0, base[4], torch.full((), -3.0e38))   # a handful of finite values
+    t[4, :200] = 1.0
+    t[5] = -base[5].abs()
+    t[5, 100] = 0.0                                               # a single +0 above negatives
+    t = t.to(torch.bfloat16).to(dev())
+    for log_probs in (False, True):
+        idx, val = _topk_gpu(t, k, None, log_probs)
+        ref = oracle.teacher_topk(_bits(t), k, None, log_probs)
+        np.testing.assert_array_equal(idx.cpu().numpy(), ref["idx"])
+        np.testing.assert_allclose(val.cpu().numpy(), ref["val"], rtol=0, atol=2e-5 if log_probs else 0)
+    assert idx[3].tolist() == list(range(20000, 20000 + k))
 
 
 def test_teacher_topk_feeds_the_kd_loss(oracle):
