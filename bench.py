@@ -6,6 +6,9 @@ KD loss and of the student / teacher NLLs over cu_seqlens, and the Delta-IFD sco
 NLLs.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--no-cpu-baseline]
+
+`--op teacher_topk [--topk K]` times the teacher-side top-k record of the same batch's teacher logits instead
+(Alg. 1 Phase 2: not part of the student step, so not part of the headline line).
 """
 import argparse
 import json
@@ -44,6 +47,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=1, help="workload index (1 = the 32,768 x 151,936 headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--op", choices=("kd", "teacher_topk"), default="kd")
+    ap.add_argument("--topk", type=int, default=64, help="k of --op teacher_topk")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run a plain 2 GiB device-to-device copy (untimed), so that a rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE run holds a kernel of known traffic to scale the counters by")
@@ -57,6 +62,8 @@ def main():
     binding.load()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.op == "teacher_topk":
+        return bench_teacher_topk(args, binding, synth, dev)
     w = synth.config(args.config)
     lay = synth.make_layout(w)
     T, V, S = w.n_tokens, w.vocab, lay.n_segments
@@ -168,6 +175,62 @@ def main():
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, lay, s if pristine is None else pristine, t, idx, val)
+    print(json.dumps(out))
+
+
+def bench_teacher_topk(args, binding, synth, dev):
+    """Top-k record (ids + log-softmax over the k) of every scored row of the workload's teacher logits."""
+    from dataclasses import replace
+    w = replace(synth.config(args.config), teacher="dense")
+    lay = synth.make_layout(w)
+    T, V, k = w.n_tokens, w.vocab, args.topk
+    s = torch.empty((T, V), dtype=torch.bfloat16, device=dev)
+    t = torch.empty((T, V), dtype=torch.bfloat16, device=dev)
+    synth.fill_logits(w, s, t)
+    del s
+    mask = torch.from_numpy(lay.loss_mask).to(dev)
+    idx = torch.empty((T, k), dtype=torch.int32, device=dev)
+    val = torch.empty((T, k), dtype=torch.float32, device=dev)
+    for _ in range(args.warmup):
+        binding.npd_teacher_topk(t, k, topk_idx=idx, topk_val=val, loss_mask=mask, log_probs=True)
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        binding.npd_teacher_topk(t, k, topk_idx=idx, topk_val=val, loss_mask=mask, log_probs=True)
+        e1.record()
+        events.append((e0, e1))
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kernel_ms = float(np.mean([a.elapsed_time(b) for a, b in events]))
+    n_scored = int(lay.loss_mask.sum())
+    alg_bytes = n_scored * (2 * V) + T * k * 8          # scored rows read once; every row's record written
+    achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
+    out = {
+        "metric": "teacher_topk_tokens_per_sec", "value": T * args.steps / elapsed, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: teacher logits {T} x {V} bf16, top-{k} ids + log-probs",
+                   "tokens": T, "scored_tokens": n_scored},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "npd::teacher_topk_stream_kernel", "kernel_ms": kernel_ms,
+                     "algorithmic_bytes_per_launch": alg_bytes},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import npd_oracle
+        rows, spent = 0, 0.0
+        while rows < T and spent < 10.0:
+            r1 = min(rows + 256, T)
+            tb = synth.bf16_bits(t[rows:r1])
+            c0 = time.perf_counter()
+            npd_oracle.teacher_topk(tb, k, lay.loss_mask[rows:r1], True)
+            spent += time.perf_counter() - c0
+            rows = r1
+        out["cpu_baseline"] = {"value": rows / spent, "unit": "tokens/s", "cores": npd_oracle.threads(),
+                               "kind": "oracle", "sample": f"first {rows} of {T} token rows, {spent:.1f} s"}
     print(json.dumps(out))
 
 
