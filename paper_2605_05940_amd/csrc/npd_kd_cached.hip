@@ -33,9 +33,25 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t row_rsrc(const uint16_t* row, int nvec) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(row), 0, nvec * 16, 0x00020000);
 }
-__device__ __forceinline__ uint4 ld_group(__amdgpu_buffer_rsrc_t r, int voff, int it, bool checked) {
-  const u32x4 v = checked ? __builtin_amdgcn_raw_buffer_load_b128(r, voff + it * kGroupBytes, 0, 0)
-                          : __builtin_amdgcn_raw_buffer_load_b128(r, voff, it * kGroupBytes, 0);
+#ifndef NPD_NT_RESIDENT
+#define NPD_NT_RESIDENT 2
+#endif
+#ifndef NPD_NT_REREAD
+#define NPD_NT_REREAD 2
+#endif
+// `once`: the group stays on chip after this load (registers or LDS) and is not read again
+__device__ __forceinline__ uint4 ld_group(__amdgpu_buffer_rsrc_t r, int voff, int it, bool checked,
+                                          bool once = false, bool last = false) {
+  u32x4 v;
+  if (once && NPD_NT_RESIDENT)
+    v = checked ? __builtin_amdgcn_raw_buffer_load_b128(r, voff + it * kGroupBytes, 0, NPD_NT_RESIDENT)
+                : __builtin_amdgcn_raw_buffer_load_b128(r, voff, it * kGroupBytes, NPD_NT_RESIDENT);
+  else if (last && NPD_NT_REREAD)
+    v = checked ? __builtin_amdgcn_raw_buffer_load_b128(r, voff + it * kGroupBytes, 0, NPD_NT_REREAD)
+                : __builtin_amdgcn_raw_buffer_load_b128(r, voff, it * kGroupBytes, NPD_NT_REREAD);
+  else
+    v = checked ? __builtin_amdgcn_raw_buffer_load_b128(r, voff + it * kGroupBytes, 0, 0)
+                : __builtin_amdgcn_raw_buffer_load_b128(r, voff, it * kGroupBytes, 0);
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 __device__ __forceinline__ void st_group_stream(__amdgpu_buffer_rsrc_t r, int voff, int it, bool checked,
@@ -193,7 +209,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
   uint4 sst[D], tst[D];           // student groups beyond CSR / teacher groups in flight
   auto request_student = [&](__amdgpu_buffer_rsrc_t rs) {
 #pragma unroll
-    for (int it = 0; it < CSR; ++it) sreg[it] = ld_group(rs, voff, it, (it) == CS - 1);
+    for (int it = 0; it < CSR; ++it) sreg[it] = ld_group(rs, voff, it, (it) == CS - 1, true);
   };
 
   int64_t row = next_scored(blockIdx.x);
@@ -230,8 +246,8 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
     if constexpr (!PERSIST) request_student(rs);
 #pragma unroll
     for (int d = 0; d < D; ++d) {
-      if constexpr (TEACHER == kDense) tst[d] = ld_group(rt, voff, d, (d) == CS - 1);
-      if (d >= CSR) sst[d] = ld_group(rs, voff, d, (d) == CS - 1);
+      if constexpr (TEACHER == kDense) tst[d] = ld_group(rt, voff, d, (d) == CS - 1, GRAD ? d < CT : true);
+      if (d >= CSR) sst[d] = ld_group(rs, voff, d, (d) == CS - 1, !GRAD);
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -239,8 +255,9 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
       const uint4 vs = it < CSR ? sreg[it < CSR ? it : 0] : sst[it % D];
       const uint4 vt = TEACHER == kDense ? tst[it % D] : make_uint4(0, 0, 0, 0);
       if (it + D < CS) {
-        if constexpr (TEACHER == kDense) tst[it % D] = ld_group(rt, voff, it + D, (it + D) == CS - 1);
-        if (it + D >= CSR) sst[it % D] = ld_group(rs, voff, it + D, (it + D) == CS - 1);
+        if constexpr (TEACHER == kDense)
+          tst[it % D] = ld_group(rt, voff, it + D, (it + D) == CS - 1, GRAD ? it + D < CT : true);
+        if (it + D >= CSR) sst[it % D] = ld_group(rs, voff, it + D, (it + D) == CS - 1, !GRAD);
       }
       if (it < CS - 1 || it * kCB + tid < nvec) accum8<TEACHER, LSE1>(vs, vt, c, lse1_t, acc);
       if constexpr (TEACHER == kDense)
@@ -280,8 +297,8 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
 #pragma unroll
       for (int d = 0; d < D; ++d) {
         const int it = CS - 1 - d;
-        if (TEACHER == kDense && it >= CT) tst[d] = ld_group(rt, voff, it, (it) == CS - 1);
-        if (it >= CSR) sst[d] = ld_group(rs, voff, it, (it) == CS - 1);
+        if (TEACHER == kDense && it >= CT) tst[d] = ld_group(rt, voff, it, (it) == CS - 1, false, true);
+        if (it >= CSR) sst[d] = ld_group(rs, voff, it, (it) == CS - 1, false, true);
       }
     }
 
@@ -372,14 +389,14 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
               vs = sreg[it < CSR ? it : 0];
             } else {
               vs = sst[q % D];  // requested D visits ago
-              if (it - D >= CSR) sst[q % D] = ld_group(rs, voff, it - D, (it - D) == CS - 1);
+              if (it - D >= CSR) sst[q % D] = ld_group(rs, voff, it - D, (it - D) == CS - 1, false, true);
             }
             if constexpr (TEACHER == kDense) {
               if (it < CT) {
                 vt = lds_t[tid * CT + it];
               } else {
                 vt = tst[q % D];
-                if (it - D >= CT) tst[q % D] = ld_group(rt, voff, it - D, (it - D) == CS - 1);
+                if (it - D >= CT) tst[q % D] = ld_group(rt, voff, it - D, (it - D) == CS - 1, false, true);
               }
             }
             {
