@@ -286,14 +286,19 @@ def test_delta_ifd_invalid_pair_index_and_empty():
     assert kc.item() == 0
 
 
-def test_cfg3_scoring_pass_reduced(oracle):
+@pytest.mark.parametrize("row_len,vocab,length_lo,length_hi,min_pairs", [
+    (1024, 32000, 16, 200, 6),        # a handful of pairs at a real vocabulary
+    (32768, 1024, 32, 400, 180),      # about 200 pairs (the sample count the blueprint names for this pass), small V
+])
+def test_cfg3_scoring_pass_reduced(oracle, row_len, vocab, length_lo, length_hi, min_pairs):
     """The Delta-IFD pass end to end on a reduced config 3: forward-only NLL of student and teacher logits,
     per-sample means, Delta-IFD, zones, and the middle-80 % filter."""
-    w = synth.scaled(synth.config(3), n_rows=2, row_len=1024, vocab=32000, length_lo=16, length_hi=200)
+    w = synth.scaled(synth.config(3), n_rows=2, row_len=row_len, vocab=vocab, length_lo=length_lo,
+                     length_hi=length_hi)
     w.prefix_lo, w.prefix_hi = 8, 64
     lay = synth.make_layout(w)
     P = len(lay.pair_cond)
-    assert P >= 6
+    assert P >= min_pairs
     _say(f"{w.name} reduced: T={w.n_tokens} V={w.vocab} pairs={P}")
     T, V = w.n_tokens, w.vocab
     bs, bt = synth.delta_ifd_boosts(w, lay)
@@ -344,6 +349,29 @@ def test_cfg3_scoring_pass_reduced(oracle):
             assert gpu["keep_count"][0] == ref["keep_count"]
     assert ref["keep_count"] == P - 2 * n_cut     # the middle 80 %
     assert len(set(ref0["zone"].tolist())) >= 2   # the synthetic IFDs do spread over more than one zone
+
+
+def test_cfg4_many_short_samples_inplace(oracle):
+    """About 1,500 samples of 16..71 tokens in 65,536 tokens (the sample count the blueprint names for the stress
+    configuration), heavy-tailed logits, gradient in place; small vocabulary so that every row is compared."""
+    w = synth.scaled(synth.config(4), vocab=2048, length_lo=16, length_hi=71)
+    lay, s, t, mask, labels = _inputs(w)
+    S = lay.n_segments
+    _say(f"{w.name} short samples: T={w.n_tokens} V={w.vocab} segments={S}")
+    assert w.n_tokens == 65536 and S >= 1400
+    sb = _bits(s)
+    ref = oracle.kd_dense(sb, _bits(t), lay.labels, lay.loss_mask)
+    gpu = run_gpu_kd(s, mask, t=t, labels=labels, inplace=True)
+    assert gpu["status"] == 0
+    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle)
+    cu = torch.from_numpy(lay.cu_seqlens).to(dev())
+    seg = _segment_gpu(torch.from_numpy(gpu["kd"].astype(np.float32)).to(dev()), mask, cu)
+    rseg = oracle.segment_reduce(ref["kd"], lay.loss_mask, lay.cu_seqlens)
+    np.testing.assert_array_equal(seg["count"], rseg["count"])
+    np.testing.assert_array_equal(seg["token_to_sample"], rseg["token_to_sample"])
+    nz = rseg["count"] > 0
+    assert (np.abs(seg["mean"][nz] - rseg["mean"][nz]) <= REL_PER_SAMPLE * np.abs(rseg["mean"][nz]) + 1e-5).all()
+    assert (seg["mean"][~nz] == 0).all()
 
 
 # --------------------------------------------------------------------------- full benchmark size, sampled rows
