@@ -22,6 +22,10 @@
  *   - gradient of the composite loss of Eq. 1, L_total = (1 - lambda) L_CE + lambda L_KD:
  *     the KD gradient times grad_scale plus ce_grad_scale * (Softmax(O_S)(c) - [c == label])
  *     (the caller sets grad_scale = lambda * w and ce_grad_scale = (1 - lambda) * w)
+ *   - the other token-level divergences that the Related Works section names next to the forward KL
+ *     of Eq. 2 (the paper defines none of them; the definitions are those of the works it cites):
+ *     reverse KL  KL(p_S || p_T), skew KL  KL(p_T || alpha p_T + (1 - alpha) p_S) and skew reverse KL
+ *     KL(p_S || (1 - alpha) p_T + alpha p_S), each with its gradient with respect to the student logits
  *   - per-sample reduction over cu_seqlens under the response mask
  *   - IFD (Eq. 3), Delta-IFD (Eq. 4) and the three curation zones of Sec. 3.2
  *
@@ -120,6 +124,57 @@ static void row_kd_dense(const double *s, const double *t, int64_t V, double tau
       const double p_t = exp(b[c] - lse_b);
       grad[c] = grad_scale * (1.0 / tau) * (p_s - p_t);
     }
+  }
+}
+
+/* divergences between the teacher and student distributions of one position */
+enum { DIV_FORWARD_KL = 0, DIV_REVERSE_KL = 1, DIV_SKEW_KL = 2, DIV_SKEW_REVERSE_KL = 3 };
+
+/*
+ * One position, dense teacher, any of the divergences above (Related Works: reverse KL, skew KL).
+ * With p_S = Softmax(s / tau), p_T = Softmax(t / tau):
+ *   forward       D = sum_c p_T log(p_T / p_S)                                   (Eq. 2)
+ *   reverse       D = sum_c p_S log(p_S / p_T)
+ *   skew          D = sum_c p_T log(p_T / m),  m = alpha p_T + (1 - alpha) p_S
+ *   skew reverse  D = sum_c p_S log(p_S / m),  m = (1 - alpha) p_T + alpha p_S
+ * The gradient follows from the chain rule through the softmax: with u_c = dD / d p_S(c),
+ *   dD / d s_j = (1 / tau) p_S(j) (u_j - sum_c p_S(c) u_c),
+ *   forward: u = -p_T / p_S;  reverse: u = log(p_S / p_T) + 1;
+ *   skew: u = -(1 - alpha) p_T / m;  skew reverse: u = log(p_S / m) + 1 - alpha p_S / m.
+ * a, b, u are caller-provided work rows of V doubles.
+ */
+static void row_div_dense(const double *s, const double *t, int64_t V, double tau, double grad_scale, int divergence,
+                          double alpha, double *a, double *b, double *u, double *kd, double *grad) {
+  if (divergence == DIV_FORWARD_KL) {
+    row_kd_dense(s, t, V, tau, grad_scale, a, b, kd, grad);
+    return;
+  }
+  for (int64_t c = 0; c < V; ++c) a[c] = s[c] / tau;
+  for (int64_t c = 0; c < V; ++c) b[c] = t[c] / tau;
+  const double lse_a = logsumexp(a, V);
+  const double lse_b = logsumexp(b, V);
+  double acc = 0.0;
+  for (int64_t c = 0; c < V; ++c) {
+    const double logp_s = a[c] - lse_a, logp_t = b[c] - lse_b;
+    const double p_s = exp(logp_s), p_t = exp(logp_t);
+    if (divergence == DIV_REVERSE_KL) {
+      if (p_s > 0.0) acc += p_s * (logp_s - logp_t);
+      u[c] = logp_s - logp_t + 1.0;
+    } else if (divergence == DIV_SKEW_KL) {
+      const double m = alpha * p_t + (1.0 - alpha) * p_s;
+      if (p_t > 0.0) acc += p_t * (logp_t - log(m));
+      u[c] = m > 0.0 ? -(1.0 - alpha) * p_t / m : 0.0;
+    } else {
+      const double m = (1.0 - alpha) * p_t + alpha * p_s;
+      if (p_s > 0.0) acc += p_s * (logp_s - log(m));
+      u[c] = p_s > 0.0 ? logp_s - log(m) + 1.0 - alpha * p_s / m : 0.0;
+    }
+  }
+  if (kd) *kd = acc;
+  if (grad) {
+    double ubar = 0.0;
+    for (int64_t c = 0; c < V; ++c) ubar += exp(a[c] - lse_a) * u[c];
+    for (int64_t c = 0; c < V; ++c) grad[c] = grad_scale * (1.0 / tau) * exp(a[c] - lse_a) * (u[c] - ubar);
   }
 }
 
@@ -294,6 +349,70 @@ void npd_oracle_kd_dense_bf16(int64_t T, int64_t V, const uint16_t *s, int64_t s
     free(tr);
     free(a);
     free(b);
+  }
+}
+
+/*
+ * Dense-teacher distillation with a selectable divergence (0 forward KL, 1 reverse KL, 2 skew KL, 3 skew reverse KL;
+ * alpha is the skew coefficient, ignored by 0 and 1).  Same conventions as npd_oracle_kd_dense_f64; outputs kd[T] and
+ * grad[T, V] (each may be NULL); labels are needed only when ce_grad_scale != 0.
+ */
+void npd_oracle_div_dense_f64(int64_t T, int64_t V, const double *s, const double *t, const int32_t *labels,
+                              const uint8_t *mask, double tau, double grad_scale, double ce_grad_scale,
+                              int32_t divergence, double alpha, double *kd, double *grad) {
+#pragma omp parallel
+  {
+    double *a = (double *)malloc(sizeof(double) * (size_t)V);
+    double *b = (double *)malloc(sizeof(double) * (size_t)V);
+    double *u = (double *)malloc(sizeof(double) * (size_t)V);
+#pragma omp for schedule(dynamic, 1)
+    for (int64_t r = 0; r < T; ++r) {
+      double *g = grad ? grad + r * V : NULL;
+      if (!mask[r]) {
+        if (kd) kd[r] = 0.0;
+        if (g)
+          for (int64_t c = 0; c < V; ++c) g[c] = 0.0;
+        continue;
+      }
+      row_div_dense(s + r * V, t + r * V, V, tau, grad_scale, divergence, alpha, a, b, u, kd ? kd + r : NULL, g);
+      if (g && ce_grad_scale != 0.0) row_add_ce_grad(s + r * V, V, labels[r], ce_grad_scale, g);
+    }
+    free(a);
+    free(b);
+    free(u);
+  }
+}
+
+void npd_oracle_div_dense_bf16(int64_t T, int64_t V, const uint16_t *s, int64_t s_stride, const uint16_t *t,
+                               int64_t t_stride, const int32_t *labels, const uint8_t *mask, double tau,
+                               double grad_scale, double ce_grad_scale, int32_t divergence, double alpha, double *kd,
+                               double *grad) {
+#pragma omp parallel
+  {
+    double *sr = (double *)malloc(sizeof(double) * (size_t)V);
+    double *tr = (double *)malloc(sizeof(double) * (size_t)V);
+    double *a = (double *)malloc(sizeof(double) * (size_t)V);
+    double *b = (double *)malloc(sizeof(double) * (size_t)V);
+    double *u = (double *)malloc(sizeof(double) * (size_t)V);
+#pragma omp for schedule(dynamic, 1)
+    for (int64_t r = 0; r < T; ++r) {
+      double *g = grad ? grad + r * V : NULL;
+      if (!mask[r]) {
+        if (kd) kd[r] = 0.0;
+        if (g)
+          for (int64_t c = 0; c < V; ++c) g[c] = 0.0;
+        continue;
+      }
+      for (int64_t c = 0; c < V; ++c) sr[c] = bf16_to_double(s[r * s_stride + c]);
+      for (int64_t c = 0; c < V; ++c) tr[c] = bf16_to_double(t[r * t_stride + c]);
+      row_div_dense(sr, tr, V, tau, grad_scale, divergence, alpha, a, b, u, kd ? kd + r : NULL, g);
+      if (g && ce_grad_scale != 0.0) row_add_ce_grad(sr, V, labels[r], ce_grad_scale, g);
+    }
+    free(sr);
+    free(tr);
+    free(a);
+    free(b);
+    free(u);
   }
 }
 

@@ -11,6 +11,7 @@ import numpy as np
 from . import build as _build
 
 ZONE_DEGENERATE, ZONE_PROXIMAL, ZONE_DISCONNECT, ZONE_INVALID = 0, 1, 2, 3
+DIVERGENCES = {"forward": 0, "reverse": 1, "skew": 2, "skew_reverse": 3}
 
 _lib = None
 
@@ -34,6 +35,11 @@ def lib():
         L.npd_oracle_kd_dense_bf16.restype = None
         L.npd_oracle_kd_dense_bf16.argtypes = [_i64, _i64, _p, _i64, _p, _i64, _p, _p, _f64, _f64, _f64,
                                                _p, _p, _p, _p, _p]
+        L.npd_oracle_div_dense_f64.restype = None
+        L.npd_oracle_div_dense_f64.argtypes = [_i64, _i64, _p, _p, _p, _p, _f64, _f64, _f64, _i32, _f64, _p, _p]
+        L.npd_oracle_div_dense_bf16.restype = None
+        L.npd_oracle_div_dense_bf16.argtypes = [_i64, _i64, _p, _i64, _p, _i64, _p, _p, _f64, _f64, _f64, _i32, _f64,
+                                                _p, _p]
         L.npd_oracle_kd_topk_bf16.restype = _i64
         L.npd_oracle_kd_topk_bf16.argtypes = [_i64, _i64, _i32, _p, _i64, _p, _p, _p, _p, _f64, _f64, _f64,
                                               _p, _p, _p, _p]
@@ -97,6 +103,30 @@ def kd_dense(s, t, labels=None, mask=None, tau=1.0, grad_scale=1.0, want_grad=Tr
         lib().npd_oracle_kd_dense_f64(T, V, _ptr(s), _ptr(t), _ptr(labels), _ptr(mask), tau, grad_scale, ce_grad_scale,
                                       _ptr(kd), _ptr(nll_s), _ptr(nll_t), _ptr(lse), _ptr(grad))
     return dict(kd=kd, nll_s=nll_s, nll_t=nll_t, lse_s=lse, grad=grad)
+
+
+def div_dense(s, t, divergence, alpha=0.1, labels=None, mask=None, tau=1.0, grad_scale=1.0, want_grad=True,
+              ce_grad_scale=0.0):
+    """Dense-teacher distillation under ``divergence`` in {"forward", "reverse", "skew", "skew_reverse"}
+    (``alpha``: skew coefficient).  Inputs as for ``kd_dense``; returns dict(kd, grad)."""
+    assert ce_grad_scale == 0.0 or labels is not None
+    T, V = s.shape
+    assert t.shape == (T, V)
+    labels, mask = _labels_mask(T, labels, mask)
+    kd = np.empty(T)
+    grad = np.empty((T, V)) if want_grad else None
+    code = DIVERGENCES[divergence]
+    if s.dtype == np.uint16:
+        assert t.dtype == np.uint16 and s.strides[1] == 2 and t.strides[1] == 2
+        lib().npd_oracle_div_dense_bf16(T, V, s.ctypes.data, s.strides[0] // 2, t.ctypes.data, t.strides[0] // 2,
+                                        _ptr(labels), _ptr(mask), tau, grad_scale, ce_grad_scale, code, alpha,
+                                        _ptr(kd), _ptr(grad))
+    else:
+        s = _c(s, np.float64)
+        t = _c(t, np.float64)
+        lib().npd_oracle_div_dense_f64(T, V, _ptr(s), _ptr(t), _ptr(labels), _ptr(mask), tau, grad_scale,
+                                       ce_grad_scale, code, alpha, _ptr(kd), _ptr(grad))
+    return dict(kd=kd, grad=grad)
 
 
 def kd_topk(s, idx, val, labels=None, mask=None, tau=1.0, grad_scale=1.0, want_grad=True, ce_grad_scale=0.0):

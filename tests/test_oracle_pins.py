@@ -505,3 +505,120 @@ def test_teacher_topk_log_probs_and_consistency_with_eq2(oracle):
     m = oracle.teacher_topk(tb, k, mask=np.array([1, 0, 1, 1], np.uint8))
     assert m["idx"][1].tolist() == list(range(k)) and (m["val"][1] == 0).all()
     np.testing.assert_array_equal(m["idx"][[0, 2, 3]], lp["idx"][[0, 2, 3]])
+
+
+# --------------------------------------------------------------------------- other divergences (Related Works)
+
+DIVS = ("reverse", "skew", "skew_reverse")
+
+
+def test_divergence_values_through_the_pinned_forward_kl(oracle):
+    """Each divergence is a forward KL between other distributions, and the forward KL is pinned above:
+    reverse = KL(p_S || p_T) = forward with the roles swapped; skew = KL(p_T || m) and skew reverse = KL(p_S || m),
+    i.e. the forward KL against a 'student' whose logits are log m."""
+    s, t = _rand(7, 90, 3.0), _rand(7, 90, 3.0)
+    for tau in (1.0, 2.0):
+        ps = torch.softmax(torch.from_numpy(s) / tau, 1).numpy()
+        pt = torch.softmax(torch.from_numpy(t) / tau, 1).numpy()
+        np.testing.assert_allclose(oracle.div_dense(s, t, "reverse", tau=tau, want_grad=False)["kd"],
+                                   oracle.kd_dense(t, s, tau=tau, want_grad=False)["kd"], rtol=1e-12)
+        for alpha in (0.1, 0.5):
+            m = alpha * pt + (1 - alpha) * ps
+            np.testing.assert_allclose(oracle.div_dense(s, t, "skew", alpha, tau=tau, want_grad=False)["kd"],
+                                       oracle.kd_dense(np.log(m), t / tau, want_grad=False)["kd"], rtol=1e-11)
+            m = (1 - alpha) * pt + alpha * ps
+            np.testing.assert_allclose(oracle.div_dense(s, t, "skew_reverse", alpha, tau=tau, want_grad=False)["kd"],
+                                       oracle.kd_dense(np.log(m), s / tau, want_grad=False)["kd"], rtol=1e-11)
+
+
+def test_divergence_library_values_and_two_level_closed_form(oracle):
+    s, t = _rand(5, 64, 2.5), _rand(5, 64, 2.5)
+    ls, lt = torch.log_softmax(torch.from_numpy(s), 1), torch.log_softmax(torch.from_numpy(t), 1)
+    # F.kl_div(input, target) = sum target * (log target - input)
+    ref = F.kl_div(lt, ls, reduction="none", log_target=True).sum(1)
+    np.testing.assert_allclose(oracle.div_dense(s, t, "reverse")["kd"], ref.numpy(), rtol=1e-11)
+    lm = torch.log(0.1 * lt.exp() + 0.9 * ls.exp())
+    ref = F.kl_div(lm, lt, reduction="none", log_target=True).sum(1)
+    np.testing.assert_allclose(oracle.div_dense(s, t, "skew", 0.1)["kd"], ref.numpy(), rtol=1e-11)
+    lm = torch.log(0.9 * lt.exp() + 0.1 * ls.exp())
+    ref = F.kl_div(lm, ls, reduction="none", log_target=True).sum(1)
+    np.testing.assert_allclose(oracle.div_dense(s, t, "skew_reverse", 0.1)["kd"], ref.numpy(), rtol=1e-11)
+    # two-level rows: reverse KL is the binary KL with the student in front
+    V, a, b = 500, 2.0, 0.5
+    s1 = np.zeros((1, V)); s1[0, 0] = b
+    t1 = np.zeros((1, V)); t1[0, 0] = a
+    pt = math.exp(a) / (math.exp(a) + V - 1)
+    ps = math.exp(b) / (math.exp(b) + V - 1)
+    want = ps * math.log(ps / pt) + (1 - ps) * math.log((1 - ps) / (1 - pt))
+    assert oracle.div_dense(s1, t1, "reverse")["kd"][0] == pytest.approx(want, rel=1e-12)
+
+
+def test_divergence_limits_and_zero_at_equality(oracle):
+    s, t = _rand(6, 50, 3.0), _rand(6, 50, 3.0)
+    fwd = oracle.kd_dense(s, t, tau=1.5)
+    rev = oracle.div_dense(s, t, "reverse", tau=1.5)
+    # alpha = 0 removes the skew
+    a0 = oracle.div_dense(s, t, "skew", 0.0, tau=1.5)
+    np.testing.assert_allclose(a0["kd"], fwd["kd"], rtol=1e-12)
+    np.testing.assert_allclose(a0["grad"], fwd["grad"], rtol=1e-9, atol=1e-15)
+    b0 = oracle.div_dense(s, t, "skew_reverse", 0.0, tau=1.5)
+    np.testing.assert_allclose(b0["kd"], rev["kd"], rtol=1e-12)
+    np.testing.assert_allclose(b0["grad"], rev["grad"], rtol=1e-9, atol=1e-15)
+    # "forward" is Eq. 2 itself
+    f = oracle.div_dense(s, t, "forward", tau=1.5)
+    assert (f["kd"] == fwd["kd"]).all() and (f["grad"] == fwd["grad"]).all()
+    for d in DIVS:
+        out = oracle.div_dense(s, t, d, 0.3)
+        assert (out["kd"] > 0).all()
+        np.testing.assert_allclose(out["grad"].sum(1), 0.0, atol=1e-13)      # softmax Jacobian: rows sum to zero
+        same = oracle.div_dense(s, s.copy(), d, 0.3)
+        np.testing.assert_allclose(same["kd"], 0.0, atol=1e-15)
+        np.testing.assert_allclose(same["grad"], 0.0, atol=1e-15)
+    # skewing towards the other distribution can only shrink the divergence (convexity of KL)
+    assert (oracle.div_dense(s, t, "skew", 0.3)["kd"] < oracle.kd_dense(s, t)["kd"]).all()
+    assert (oracle.div_dense(s, t, "skew_reverse", 0.3)["kd"] < oracle.div_dense(s, t, "reverse")["kd"]).all()
+
+
+@pytest.mark.parametrize("div", DIVS)
+@pytest.mark.parametrize("tau", [1.0, 2.0])
+def test_divergence_gradient_finite_differences(oracle, div, tau):
+    T, V, h, alpha = 2, 40, 1e-6, 0.2
+    s, t = _rand(T, V), _rand(T, V)
+    g = oracle.div_dense(s, t, div, alpha, tau=tau, grad_scale=1.0)["grad"]
+    for r in range(T):
+        for c in range(V):
+            sp, sm = s.copy(), s.copy()
+            sp[r, c] += h
+            sm[r, c] -= h
+            fd = (oracle.div_dense(sp, t, div, alpha, tau=tau, want_grad=False)["kd"][r]
+                  - oracle.div_dense(sm, t, div, alpha, tau=tau, want_grad=False)["kd"][r]) / (2 * h)
+            assert g[r, c] == pytest.approx(fd, rel=5e-6, abs=2e-9)
+
+
+def test_divergence_gradient_matches_autograd_with_composite_term_and_bf16_front_end(oracle):
+    T, V, tau, alpha, gs, cs = 4, 33, 2.0, 0.1, 0.9, 0.1
+    s, t = _rand(T, V), _rand(T, V)
+    labels = RNG.integers(0, V, T).astype(np.int32)
+    for div in DIVS:
+        st = torch.from_numpy(s).requires_grad_(True)
+        ps, pt = torch.softmax(st / tau, 1), torch.softmax(torch.from_numpy(t) / tau, 1)
+        if div == "reverse":
+            d = (ps * (ps.log() - pt.log())).sum(1)
+        elif div == "skew":
+            d = (pt * (pt.log() - (alpha * pt + (1 - alpha) * ps).log())).sum(1)
+        else:
+            d = (ps * (ps.log() - ((1 - alpha) * pt + alpha * ps).log())).sum(1)
+        loss = gs * d.sum() + cs * F.cross_entropy(st, torch.from_numpy(labels).long(), reduction="sum")
+        loss.backward()
+        out = oracle.div_dense(s, t, div, alpha, labels=labels, tau=tau, grad_scale=gs, ce_grad_scale=cs)
+        np.testing.assert_allclose(out["kd"], d.detach().numpy(), rtol=1e-11)
+        np.testing.assert_allclose(out["grad"], st.grad.numpy(), rtol=1e-9, atol=1e-13)
+    # the bf16 front-end converts exactly and masks rows
+    sb = torch.from_numpy(s).to(torch.bfloat16)
+    tb = torch.from_numpy(t).to(torch.bfloat16)
+    mask = np.array([1, 0, 1, 1], np.uint8)
+    a = oracle.div_dense(sb.view(torch.int16).numpy().view(np.uint16), tb.view(torch.int16).numpy().view(np.uint16),
+                         "skew_reverse", alpha, mask=mask)
+    b = oracle.div_dense(sb.double().numpy(), tb.double().numpy(), "skew_reverse", alpha, mask=mask)
+    assert (a["kd"] == b["kd"]).all() and (a["grad"] == b["grad"]).all()
+    assert a["kd"][1] == 0 and (a["grad"][1] == 0).all()
