@@ -52,6 +52,15 @@ enum {
   NPD_TEACHER_NONE = 2        /* no teacher: only nll_tok / lse_tok are produced (scoring pass)   */
 };
 
+/* npd_kd_desc.divergence: what kd_tok measures between p_T and p_S (Related Works names reverse KL and skew KL
+ * beside the forward KL of Eq. 2; alpha = npd_kd_desc.skew_alpha).  All but FORWARD need a dense teacher. */
+enum {
+  NPD_DIV_FORWARD_KL = 0,      /* sum p_T log(p_T / p_S)                                  (Eq. 2)      */
+  NPD_DIV_REVERSE_KL = 1,      /* sum p_S log(p_S / p_T)                                               */
+  NPD_DIV_SKEW_KL = 2,         /* sum p_T log(p_T / m),  m = alpha p_T + (1 - alpha) p_S               */
+  NPD_DIV_SKEW_REVERSE_KL = 3  /* sum p_S log(p_S / m),  m = (1 - alpha) p_T + alpha p_S               */
+};
+
 /* npd_kd_desc.flags */
 enum {
   NPD_FLAG_FWD_ONLY = 1u,      /* no gradient: grad_out must be NULL                               */
@@ -91,6 +100,8 @@ typedef struct {
   float ce_grad_scale;    /* finite; weight of the hard-label CE gradient of Eq. 1 (the caller sets
                              (1 - lambda) / N_tokens); 0 = KD gradient only.  Non-zero needs labels
                              and a gradient buffer                                                 */
+  int32_t divergence;     /* NPD_DIV_*; 0 = the forward KL of Eq. 2                                */
+  float skew_alpha;       /* skew coefficient in [0, 1) of NPD_DIV_SKEW_*; ignored otherwise       */
 } npd_kd_desc;
 
 /* Library version (major * 100 + minor). */
@@ -119,6 +130,10 @@ size_t npd_workspace_bytes(const npd_kd_desc* desc);
  *   nll_tok[p]         = logsumexp(student[p, :]) - student[p, labels[p]]   (tau = 1 always)
  *   teacher_nll_tok[p] = logsumexp(teacher[p, :]) - teacher[p, labels[p]]   (dense teacher only)
  *   lse_tok[p]         = logsumexp(student[p, :])                           (tau = 1)
+ *
+ * With desc->divergence != NPD_DIV_FORWARD_KL (dense teacher only, else NPD_ERR_UNSUPPORTED) kd_tok[p] is that
+ * divergence D of p_T and p_S and the first gradient term becomes grad_scale * dD / d student logit
+ *   = grad_scale / tau * p_S(c) * (u_c - sum_c' p_S(c') u_c'),  u = dD / d p_S.
  *
  * At positions with loss_mask[p] == 0 the scalar outputs are 0 and the gradient row is
  * zero-filled (its logits are not read).  No tau^2 factor is applied.

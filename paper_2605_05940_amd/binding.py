@@ -16,6 +16,7 @@ LIB_PATH = os.environ.get("NPD_LIB_PATH") or os.path.join(HERE, "libnpd.so")
 
 NPD_TEACHER_DENSE_BF16, NPD_TEACHER_TOPK, NPD_TEACHER_NONE = 0, 1, 2
 NPD_FLAG_FWD_ONLY, NPD_FLAG_INPLACE_GRAD = 1, 2
+NPD_DIV_FORWARD_KL, NPD_DIV_REVERSE_KL, NPD_DIV_SKEW_KL, NPD_DIV_SKEW_REVERSE_KL = 0, 1, 2, 3
 NPD_DEV_BAD_LABEL, NPD_DEV_BAD_TOPK_INDEX, NPD_DEV_BAD_CU_SEQLENS = 1, 2, 4
 NPD_ZONE_DEGENERATE, NPD_ZONE_PROXIMAL, NPD_ZONE_DISCONNECT, NPD_ZONE_INVALID = 0, 1, 2, 3
 NPD_IFD_REQUIRE_TEACHER_LE_1 = 1
@@ -36,7 +37,8 @@ class KdDesc(ctypes.Structure):
     _fields_ = [("n_tokens", ctypes.c_int64), ("vocab", ctypes.c_int32), ("teacher_kind", ctypes.c_int32),
                 ("student_stride", ctypes.c_int64), ("teacher_stride", ctypes.c_int64),
                 ("topk", ctypes.c_int32), ("flags", ctypes.c_uint32),
-                ("tau", ctypes.c_float), ("grad_scale", ctypes.c_float), ("ce_grad_scale", ctypes.c_float)]
+                ("tau", ctypes.c_float), ("grad_scale", ctypes.c_float), ("ce_grad_scale", ctypes.c_float),
+                ("divergence", ctypes.c_int32), ("skew_alpha", ctypes.c_float)]
 
 
 _lib = None
@@ -103,7 +105,8 @@ def npd_kd_loss_fwd_bwd(student_logits: torch.Tensor, loss_mask: torch.Tensor, *
                         teacher_dense: Optional[torch.Tensor] = None,
                         teacher_idx: Optional[torch.Tensor] = None, teacher_val: Optional[torch.Tensor] = None,
                         labels: Optional[torch.Tensor] = None, tau: float = 1.0, grad_scale: float = 1.0,
-                        ce_grad_scale: float = 0.0, grad_out: Optional[torch.Tensor] = None, kd_tok: Optional[torch.Tensor] = None,
+                        ce_grad_scale: float = 0.0, divergence: int = NPD_DIV_FORWARD_KL, skew_alpha: float = 0.0,
+                        grad_out: Optional[torch.Tensor] = None, kd_tok: Optional[torch.Tensor] = None,
                         nll_tok: Optional[torch.Tensor] = None, teacher_nll_tok: Optional[torch.Tensor] = None,
                         lse_tok: Optional[torch.Tensor] = None, dev_status: Optional[torch.Tensor] = None,
                         workspace: Optional[torch.Tensor] = None) -> None:
@@ -117,6 +120,7 @@ def npd_kd_loss_fwd_bwd(student_logits: torch.Tensor, loss_mask: torch.Tensor, *
     d.n_tokens, d.vocab = T, V
     d.student_stride = _row_stride(student_logits)
     d.tau, d.grad_scale, d.ce_grad_scale = tau, grad_scale, ce_grad_scale
+    d.divergence, d.skew_alpha = divergence, skew_alpha
     if teacher_dense is not None:
         d.teacher_kind, d.teacher_stride = NPD_TEACHER_DENSE_BF16, _row_stride(teacher_dense)
         if teacher_dense.shape != (T, V):

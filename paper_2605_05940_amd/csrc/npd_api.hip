@@ -40,6 +40,12 @@ npd_status check_desc(const npd_kd_desc* d) {
     return NPD_ERR_VALUE;  // a CE gradient needs a gradient buffer
   if (d->flags & ~(uint32_t)(NPD_FLAG_FWD_ONLY | NPD_FLAG_INPLACE_GRAD)) return NPD_ERR_VALUE;
   if ((d->flags & NPD_FLAG_FWD_ONLY) && (d->flags & NPD_FLAG_INPLACE_GRAD)) return NPD_ERR_VALUE;
+  if (d->divergence < NPD_DIV_FORWARD_KL || d->divergence > NPD_DIV_SKEW_REVERSE_KL) return NPD_ERR_VALUE;
+  if ((d->divergence == NPD_DIV_SKEW_KL || d->divergence == NPD_DIV_SKEW_REVERSE_KL) &&
+      !(d->skew_alpha >= 0.0f && d->skew_alpha < 1.0f))
+    return NPD_ERR_VALUE;
+  if (d->divergence != NPD_DIV_FORWARD_KL && d->teacher_kind != NPD_TEACHER_DENSE_BF16)
+    return NPD_ERR_UNSUPPORTED;  // off the top-k support p_T is 0: the other divergences need the full row
   if (d->n_tokens > 0x7fffffffLL) return NPD_ERR_UNSUPPORTED;  // one workgroup per position, 1-D grid
   if (d->teacher_kind == NPD_TEACHER_TOPK && d->topk > npd::kTopkMax) return NPD_ERR_UNSUPPORTED;
   return NPD_OK;
@@ -49,7 +55,7 @@ npd_status check_desc(const npd_kd_desc* d) {
 
 extern "C" {
 
-int npd_version(void) { return 102; }
+int npd_version(void) { return 103; }
 
 const char* npd_status_string(npd_status st) {
   switch (st) {
@@ -146,6 +152,8 @@ npd_status npd_kd_loss_fwd_bwd(const npd_kd_desc* desc, const void* student_logi
   a.inv_tau = 1.0f / d.tau;
   a.gscale = (float)((double)d.grad_scale / (double)d.tau);
   a.cscale = d.ce_grad_scale;
+  a.divergence = d.divergence;
+  a.alpha = d.skew_alpha;
   a.need_lse1 = (d.tau != 1.0f && (nll_tok || teacher_nll_tok || lse_tok || d.ce_grad_scale != 0.0f)) ? 1 : 0;
 
   const hipError_t e = npd::launch_kd(a, d.teacher_kind, !fwd_only, static_cast<hipStream_t>(stream));

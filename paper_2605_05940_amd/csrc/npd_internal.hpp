@@ -6,6 +6,7 @@
 namespace npd {
 
 enum TeacherKind { kDense = 0, kTopk = 1, kNone = 2 };
+enum Divergence { kForwardKl = 0, kReverseKl = 1, kSkewKl = 2, kSkewReverseKl = 3 };
 
 constexpr int kTopkMax = 4096;  // largest k the top-k kernels stage per row
 
@@ -31,9 +32,14 @@ struct KdArgs {
   float gscale;        // grad_scale / tau
   float cscale;        // ce_grad_scale (weight of the hard-label CE gradient; 0 = none)
   int32_t need_lse1;   // tau != 1 and a tau = 1 quantity (nll, teacher nll, lse) is wanted
+  int32_t divergence;  // Divergence
+  float alpha;         // skew coefficient
 };
 
 hipError_t launch_kd(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream);
+
+// divergences other than the forward KL, dense teacher (npd_div_kernels.hip)
+hipError_t launch_div(const KdArgs& a, bool want_grad, hipStream_t stream);
 
 // row-resident kernels for large vocabularies (npd_kd_cached.hip)
 bool cached_path_applies(const KdArgs& a, int teacher_kind, bool want_grad);

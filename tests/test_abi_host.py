@@ -25,7 +25,7 @@ def test_exports_match_header(lib):
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None
-    assert lib.npd_version() >= 102
+    assert lib.npd_version() >= 103
     for st in range(8):
         assert len(lib.npd_status_string(st)) > 0
     assert lib.npd_status_string(0) == b"ok"
@@ -33,8 +33,9 @@ def test_exports_match_header(lib):
 
 def test_desc_layout_matches_header():
     # n_tokens i64, vocab i32, teacher_kind i32, student_stride i64, teacher_stride i64, topk i32, flags u32,
-    # tau f32, grad_scale f32, ce_grad_scale f32 (+ tail padding)
-    assert ctypes.sizeof(binding.KdDesc) == 56 and binding.KdDesc.ce_grad_scale.offset == 48
+    # tau f32, grad_scale f32, ce_grad_scale f32, divergence i32, skew_alpha f32 (+ tail padding)
+    assert ctypes.sizeof(binding.KdDesc) == 64 and binding.KdDesc.ce_grad_scale.offset == 48
+    assert binding.KdDesc.divergence.offset == 52 and binding.KdDesc.skew_alpha.offset == 56
     assert binding.KdDesc.student_stride.offset == 16 and binding.KdDesc.tau.offset == 40
 
 
@@ -93,6 +94,15 @@ def test_kd_argument_validation(lib):
     assert _kd(lib, _desc(**tk), idx=FAKE + 0x500000, val=FAKE + 0x600000) == E_VALUE   # dense tensor given too
     big = _desc(teacher_kind=1, topk=5000, vocab=8192, student_stride=8192)
     assert _kd(lib, big, teacher=None, idx=FAKE + 0x500000, val=FAKE + 0x600000) == E_UNSUP
+    # divergences other than the forward KL
+    assert _kd(lib, _desc(divergence=4)) == E_VALUE
+    assert _kd(lib, _desc(divergence=-1)) == E_VALUE
+    assert _kd(lib, _desc(divergence=binding.NPD_DIV_SKEW_KL, skew_alpha=1.0)) == E_VALUE
+    assert _kd(lib, _desc(divergence=binding.NPD_DIV_SKEW_REVERSE_KL, skew_alpha=-0.1)) == E_VALUE
+    assert _kd(lib, _desc(divergence=binding.NPD_DIV_SKEW_KL, skew_alpha=float("nan"))) == E_VALUE
+    assert _kd(lib, _desc(divergence=binding.NPD_DIV_REVERSE_KL, **tk), teacher=None, idx=FAKE + 0x500000,
+               val=FAKE + 0x600000) == E_UNSUP                      # needs the full teacher row
+    assert _kd(lib, _desc(divergence=binding.NPD_DIV_REVERSE_KL, skew_alpha=7.0), grad=FAKE) == E_ALIAS  # alpha ignored
     # no teacher: forward-only scoring
     nt = dict(teacher_kind=binding.NPD_TEACHER_NONE)
     assert _kd(lib, _desc(**nt), teacher=None) == E_VALUE           # gradient without a teacher

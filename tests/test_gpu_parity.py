@@ -697,3 +697,72 @@ def test_teacher_topk_feeds_the_kd_loss(oracle):
     ref = oracle.kd_topk(_bits(s), rec["idx"], rec["val"], lay.labels, lay.loss_mask, tau=2.0)
     assert gpu["status"] == 0
     compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle, tau=2.0)
+
+
+# --------------------------------------------------------------------------- other divergences (Related Works)
+
+DIVS = {"reverse": binding.NPD_DIV_REVERSE_KL, "skew": binding.NPD_DIV_SKEW_KL,
+        "skew_reverse": binding.NPD_DIV_SKEW_REVERSE_KL}
+
+
+@pytest.mark.parametrize("div", sorted(DIVS))
+@pytest.mark.parametrize("V,stride,tau,alpha,scale,inplace", [
+    (1024, 1024, 1.0, 0.1, 1.0, False),        # one wave per row
+    (5003, 5003, 2.0, 0.5, 1.0, False),        # unaligned rows: element-wise path
+    (50264, 50272, 1.0, 0.1, 0.5, True),       # ragged last group, padded stride, in place
+    (151936, 151936, 1.0, 0.1, 1.0, False),    # the headline vocabulary
+    (151936, 151936, 3.0, 0.9, -2.0, True),
+])
+def test_divergence_shapes(oracle, div, V, stride, tau, alpha, scale, inplace):
+    T = 24 if V > 100000 else 64
+    w = synth.scaled(synth.config(1), n_rows=1, row_len=T, vocab=V, length_lo=4, length_hi=16)
+    _say(f"divergence {div} V={V} stride={stride} tau={tau} alpha={alpha} scale={scale} inplace={inplace}")
+    lay, s, t, mask, labels = _inputs(w, stride)
+    ref = oracle.div_dense(_bits(s), _bits(t), div, alpha, labels=lay.labels, mask=lay.loss_mask, tau=tau,
+                           grad_scale=scale)
+    nll = oracle.kd_dense(_bits(s), _bits(t), lay.labels, lay.loss_mask, want_grad=False)
+    ref.update(nll_s=nll["nll_s"], nll_t=nll["nll_t"], lse_s=nll["lse_s"])
+    gpu = run_gpu_kd(s, mask, t=t, labels=labels, tau=tau, grad_scale=scale, inplace=inplace, divergence=DIVS[div],
+                     skew_alpha=alpha)
+    assert gpu["status"] == 0
+    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle, grad_scale=scale, tau=tau, amp_from_ref=True)
+
+
+def test_divergence_forward_only_zero_at_equality_and_limits(oracle):
+    w = synth.scaled(synth.config(1), n_rows=1, row_len=32, vocab=40000, length_lo=4, length_hi=16)
+    lay, s, t, mask, labels = _inputs(w)
+    for div, code in DIVS.items():
+        ref = oracle.div_dense(_bits(s), _bits(t), div, 0.25, mask=lay.loss_mask, want_grad=False)
+        gpu = run_gpu_kd(s, mask, t=t, want_grad=False, divergence=code, skew_alpha=0.25)
+        compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle)
+        same = run_gpu_kd(s, mask, t=s.clone(), divergence=code, skew_alpha=0.25)
+        assert np.abs(same["kd"]).max() <= 1e-5 and np.abs(same["grad"]).max() <= 1e-5
+    # the reverse KL of a distribution with itself is exactly zero, and so is its gradient
+    same = run_gpu_kd(s, mask, t=s.clone(), divergence=binding.NPD_DIV_REVERSE_KL)
+    assert (same["kd"] == 0).all() and (same["grad_bits"] & 0x7fff == 0).all()
+    # alpha = 0 takes the skew out: skew KL = Eq. 2, skew reverse KL = reverse KL
+    fwd = oracle.kd_dense(_bits(s), _bits(t), mask=lay.loss_mask)
+    gpu = run_gpu_kd(s, mask, t=t, divergence=binding.NPD_DIV_SKEW_KL, skew_alpha=0.0)
+    compare_kd(gpu, dict(kd=fwd["kd"], grad=fwd["grad"]), lay.loss_mask, lay.cu_seqlens, oracle)
+
+
+@pytest.mark.parametrize("div", sorted(DIVS))
+@pytest.mark.parametrize("tau", [1.0, 2.0])
+def test_divergence_composite_gradient_and_bad_label(oracle, div, tau):
+    w = synth.scaled(synth.config(1), n_rows=1, row_len=24, vocab=32000, length_lo=4, length_hi=12)
+    lay, s, t, mask, labels = _inputs(w)
+    ref = oracle.div_dense(_bits(s), _bits(t), div, 0.1, labels=lay.labels, mask=lay.loss_mask, tau=tau,
+                           grad_scale=0.9, ce_grad_scale=0.1)
+    gpu = run_gpu_kd(s, mask, t=t, labels=labels, tau=tau, grad_scale=0.9, ce_grad_scale=0.1, divergence=DIVS[div],
+                     skew_alpha=0.1)
+    assert gpu["status"] == 0
+    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle, grad_scale=0.9, tau=tau, amp_from_ref=True)
+    bad = labels.clone()
+    r = int(np.flatnonzero(lay.loss_mask)[0])
+    bad[r] = w.vocab + 5
+    gpu = run_gpu_kd(s, mask, t=t, labels=bad, tau=tau, ce_grad_scale=0.1, divergence=DIVS[div], skew_alpha=0.1)
+    assert gpu["status"] == binding.NPD_DEV_BAD_LABEL
+    assert np.isnan(gpu["grad"][r]).all() and np.isnan(gpu["nll_s"][r])
+    others = lay.loss_mask.astype(bool).copy()
+    others[r] = False
+    assert np.isfinite(gpu["grad"][others]).all()
