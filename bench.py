@@ -47,6 +47,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=1, help="workload index (1 = the 32,768 x 151,936 headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--divergence", choices=("forward", "reverse", "skew", "skew_reverse"), default="forward",
+                    help="divergence of the dense-teacher configurations (forward = Eq. 2, the headline)")
+    ap.add_argument("--skew-alpha", type=float, default=0.1)
     ap.add_argument("--op", choices=("kd", "teacher_topk"), default="kd")
     ap.add_argument("--topk", type=int, default=64, help="k of --op teacher_topk")
     ap.add_argument("--traffic-calibration", action="store_true",
@@ -100,6 +103,10 @@ def main():
     status = torch.zeros(1, dtype=torch.int32, device=dev)
 
     kernel_events = []
+    div_code = ("forward", "reverse", "skew", "skew_reverse").index(args.divergence)
+    if div_code and not (dense and not w.paired):
+        print("bench.py: --divergence applies to the dense-teacher training configurations", file=sys.stderr)
+        sys.exit(2)
 
     def fused(record):
         if record:
@@ -110,6 +117,7 @@ def main():
             binding.npd_kd_loss_fwd_bwd(t, mask, labels=labels, nll_tok=tnll, dev_status=status)
         elif dense:
             binding.npd_kd_loss_fwd_bwd(s, mask, teacher_dense=t, labels=labels, tau=w.tau, grad_scale=1.0,
+                                        divergence=div_code, skew_alpha=args.skew_alpha,
                                         grad_out=g, kd_tok=kd, nll_tok=nll, teacher_nll_tok=tnll, dev_status=status)
         else:
             binding.npd_kd_loss_fwd_bwd(s, mask, teacher_idx=idx, teacher_val=val, labels=labels, tau=w.tau,
@@ -154,7 +162,7 @@ def main():
     alg_bytes = algorithmic_bytes(w, lay)
     achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
     n_scored = int(lay.loss_mask.sum())
-    traffic = MEASURED_TRAFFIC_BYTES.get(w.name)
+    traffic = MEASURED_TRAFFIC_BYTES.get(w.name) if div_code == 0 else None
     # v_exp_f32 per student logit: one per tensor in the loss sweep, one per tensor in the gradient sweep
     exps_per_logit = 2 if w.paired else (4 if dense else 2)
 
@@ -165,12 +173,15 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.n_rows}x{w.row_len} tokens x vocab {V}, teacher {w.teacher}"
                                f"{'' if dense else ' k=' + str(w.topk)}, tau {w.tau}, "
-                               f"{'in-place' if w.inplace else 'out-of-place'} bf16 grad",
+                               f"{'in-place' if w.inplace else 'out-of-place'} bf16 grad"
+                               f"{'' if div_code == 0 else ', divergence ' + args.divergence}",
                    "tokens": T, "scored_tokens": n_scored, "segments": S, "pairs": P,
                    "io_dtype": "bf16 logits and gradient, fp32 accumulation"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "npd::kd_cached_kernel (fused KD loss + gradient)", "kernel_ms": kernel_ms,
+                     "kernel": "npd::kd_cached_kernel (fused KD loss + gradient)" if div_code == 0 else
+                               f"npd::div_rows_kernel ({args.divergence} divergence + gradient)",
+                     "kernel_ms": kernel_ms,
                      "kernel_ms_median": float(np.median(kernel_all)), "kernel_ms_min": float(kernel_all.min()),
                      "algorithmic_bytes_per_launch": alg_bytes,
                      "counter_gbs": (traffic / (kernel_ms * 1e-3) / 1e9) if traffic else None,

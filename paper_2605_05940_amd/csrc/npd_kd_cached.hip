@@ -88,7 +88,14 @@ struct Sweep2Coef {
   float c, fs, ft;
   uint32_t sign;  // 0x80008000 when the weights are negative (folded form)
   bool folded;    // uniform
+  // reverse KL (and its CE term at tau = 1): grad = 2^(x_s c - r_S) ((x_s - x_t) ra + rb),
+  //   ra = grad_scale / (tau^2 z_S),  rb = (ce_grad_scale - grad_scale / tau (lse_S - lse_T + D)) / z_S
+  float ra, rb;
 };
+
+__device__ __forceinline__ float grad_reverse_elem(float xs, float xt, const Sweep2Coef& k) {
+  return exp2_fast(__builtin_fmaf(xs, k.c, -k.p.rs)) * __builtin_fmaf(xs - xt, k.ra, k.rb);
+}
 
 __device__ __forceinline__ Sweep2Coef sweep2_coef(const Lse& S, const Lse& Tt, float c, float gscale, float cscale,
                                                   bool has_teacher_stream, bool dense) {
@@ -104,15 +111,21 @@ __device__ __forceinline__ Sweep2Coef sweep2_coef(const Lse& S, const Lse& Tt, f
   const bool small_s = A == 0.0f || fabsf(k.fs) < 1024.0f;
   const bool small_t = !dense || B == 0.0f || fabsf(k.ft) < 1024.0f;
   k.folded = same_sign && small_s && small_t;
+  k.ra = k.rb = 0.0f;
   return k;
 }
 
 // gradient of 8 elements
-template <int TEACHER, bool FOLDED>
+template <int TEACHER, bool FOLDED, bool REV = false>
 __device__ __forceinline__ uint4 grad8(const uint4& vs, const uint4& vt, const Sweep2Coef& k) {
   float xs[8], gv[8];
   unpack8(vs, xs);
-  if constexpr (TEACHER == kDense) {
+  if constexpr (REV) {
+    float xt[8];
+    unpack8(vt, xt);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) gv[j] = grad_reverse_elem(xs[j], xt[j], k);
+  } else if constexpr (TEACHER == kDense) {
     float xt[8];
     unpack8(vt, xt);
     if constexpr (FOLDED) {
@@ -137,7 +150,7 @@ __device__ __forceinline__ uint4 grad8(const uint4& vs, const uint4& vt, const S
   o.y = pack_bf16(gv[2], gv[3]);
   o.z = pack_bf16(gv[4], gv[5]);
   o.w = pack_bf16(gv[6], gv[7]);
-  if constexpr (FOLDED) {
+  if constexpr (FOLDED && !REV) {
     o.x ^= k.sign;
     o.y ^= k.sign;
     o.z ^= k.sign;
@@ -147,7 +160,7 @@ __device__ __forceinline__ uint4 grad8(const uint4& vs, const uint4& vt, const S
 }
 
 // sweep-1 contribution of 8 elements
-template <int TEACHER, bool LSE1>
+template <int TEACHER, bool LSE1, bool REV = false>
 __device__ __forceinline__ void accum8(const uint4& vs, const uint4& vt, float c, bool lse1_t,
                                        Lse (&acc)[LSE1 ? 4 : 2]) {
   float xs[8];
@@ -155,16 +168,22 @@ __device__ __forceinline__ void accum8(const uint4& vs, const uint4& vt, float c
   if constexpr (TEACHER == kDense) {
     float xt[8];
     unpack8(vt, xt);
-    acc[1].add8_cross(xt, xs, c);
+    if constexpr (REV) {  // reverse KL: the cross term sum e_S (s - t) rides on the student stream
+      acc[1].add8(xt, c);
+      acc[0].add8_cross(xs, xt, c);
+    } else {
+      acc[1].add8_cross(xt, xs, c);
+    }
     if constexpr (LSE1)
       if (lse1_t) acc[3].add8(xt, kLog2e);
   }
-  acc[0].add8(xs, c);
+  if constexpr (!REV) acc[0].add8(xs, c);
   if constexpr (LSE1) acc[2].add8(xs, kLog2e);
 }
 
-template <int CS, int CSR, int CT, int D, int TEACHER, bool GRAD, bool LSE1, bool PERSIST>
+template <int CS, int CSR, int CT, int D, int TEACHER, bool GRAD, bool LSE1, bool PERSIST, bool REV = false>
 __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
+  static_assert(!REV || (TEACHER == kDense && GRAD), "the reverse KL needs the full teacher row");
   // teacher groups parked for sweep 2, [1024][CT]: a thread's CT groups are contiguous, so one base register
   // plus an immediate offset addresses them all; the 16 * CT byte lane stride (144 B) is conflict-free for
   // 128-bit LDS accesses
@@ -259,7 +278,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
           tst[it % D] = ld_group(rt, voff, it + D, (it + D) == CS - 1, GRAD ? it + D < CT : true);
         if (it + D >= CSR) sst[it % D] = ld_group(rs, voff, it + D, (it + D) == CS - 1, !GRAD);
       }
-      if (it < CS - 1 || it * kCB + tid < nvec) accum8<TEACHER, LSE1>(vs, vt, c, lse1_t, acc);
+      if (it < CS - 1 || it * kCB + tid < nvec) accum8<TEACHER, LSE1, REV>(vs, vt, c, lse1_t, acc);
       if constexpr (TEACHER == kDense)
         if (it < CT) lds_t[tid * CT + it] = vt;
       __builtin_amdgcn_sched_barrier(0);  // keep the instruction scheduler from piling all loads up front
@@ -268,17 +287,22 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
     for (int i = CS * kCB + tid; i < nvec; i += kCB) {
       const uint4 vs = ld16(srow, i);
       const uint4 vt = TEACHER == kDense ? ld16(trow, i) : make_uint4(0, 0, 0, 0);
-      accum8<TEACHER, LSE1>(vs, vt, c, lse1_t, acc);
+      accum8<TEACHER, LSE1, REV>(vs, vt, c, lse1_t, acc);
     }
     for (int e = nvec * 8 + tid; e < V; e += kCB) {
       const float xs = bf16_one(srow[e]);
       if constexpr (TEACHER == kDense) {
         const float xt = bf16_one(trow[e]);
-        acc[1].add1_cross(xt, xt - xs, c);
+        if constexpr (REV) {
+          acc[1].add1(xt, c);
+          acc[0].add1_cross(xs, xs - xt, c);
+        } else {
+          acc[1].add1_cross(xt, xt - xs, c);
+        }
         if constexpr (LSE1)
           if (lse1_t) acc[3].add1(xt, kLog2e);
       }
-      acc[0].add1(xs, c);
+      if constexpr (!REV) acc[0].add1(xs, c);
       if constexpr (LSE1) acc[2].add1(xs, kLog2e);
     }
     int bad_index = 0;
@@ -308,13 +332,21 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
     const float Lt = TEACHER == kNone ? 0.0f : acc[1].log2_sum();
     const float lse1_s = __fmul_rn(LSE1 ? acc[NS - 2].log2_sum() : Ls, kLn2);
     float kd = 0.0f;
+    float lse_diff = 0.0f;  // lse_S - lse_T at temperature tau
     if constexpr (TEACHER == kDense) {
-      kd = (acc[1].a / acc[1].z) * a.inv_tau + ((acc[0].r - acc[1].r) + (acc[0].log2_z() - acc[1].log2_z())) * kLn2;
+      lse_diff = ((acc[0].r - acc[1].r) + (acc[0].log2_z() - acc[1].log2_z())) * kLn2;
+      kd = REV ? (acc[0].a / acc[0].z) * a.inv_tau - lse_diff : (acc[1].a / acc[1].z) * a.inv_tau + lse_diff;
       kd = kd < 0.0f ? 0.0f : kd;
     }
     const bool ce = GRAD && a.cscale != 0.0f;                       // uniform (tau = 1 here whenever it is set)
     const bool bad_label = a.labels && (unsigned)y >= (unsigned)V;  // uniform
-    const Sweep2Coef k = sweep2_coef(acc[0], acc[1], c, a.gscale, a.cscale, TEACHER != kNone, TEACHER == kDense);
+    Sweep2Coef k = sweep2_coef(acc[0], acc[1], c, a.gscale, a.cscale, TEACHER != kNone, TEACHER == kDense);
+    if constexpr (REV) {
+      const float inv_z = 1.0f / acc[0].z;
+      k.ra = a.gscale * a.inv_tau * inv_z;
+      k.rb = (a.cscale - a.gscale * (lse_diff + kd)) * inv_z;
+      k.folded = true;  // one form for all rows: the exponent is taken against the row's reference as in sweep 1
+    }
     if constexpr (TEACHER == kTopk) {
       bad_index = __syncthreads_or(bad_index);
       if (tid == 0) y_in_support = 0;
@@ -368,14 +400,17 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
         // sub-group tail and streamed part first (read most recently), then the first CS groups backwards
         for (int e = nvec * 8 + tid; e < V; e += kCB) {
           const float xs = bf16_one(srow[e]);
-          grow[e] =
-              one_bf16(TEACHER == kDense ? grad_dense_elem(xs, bf16_one(trow[e]), k.p) : grad_student_elem(xs, k.p));
+          if constexpr (REV)
+            grow[e] = one_bf16(grad_reverse_elem(xs, bf16_one(trow[e]), k));
+          else
+            grow[e] = one_bf16(TEACHER == kDense ? grad_dense_elem(xs, bf16_one(trow[e]), k.p)
+                                                 : grad_student_elem(xs, k.p));
         }
         for (int i = (nit - 1) * kCB + tid; i >= CS * kCB; i -= kCB) {
           if (i < nvec) {
             const uint4 vs = ld16(srow, i);
             const uint4 vt = TEACHER == kDense ? ld16(trow, i) : make_uint4(0, 0, 0, 0);
-            st16_stream(grow, i, grad8<TEACHER, false>(vs, vt, k));
+            st16_stream(grow, i, grad8<TEACHER, false, REV>(vs, vt, k));
           }
         }
         if (k.folded) {  // uniform
@@ -400,7 +435,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
               }
             }
             {
-              const uint4 gq = grad8<TEACHER, true>(vs, vt, k);
+              const uint4 gq = grad8<TEACHER, true, REV>(vs, vt, k);
               if (it < CS - 1 || it * kCB + tid < nvec) st16_stream(grow, it * kCB + tid, gq);
             }
             if (PERSIST && it < CSR) sreg[it < CSR ? it : 0] = ld_group(rnext, voff, it, (it) == CS - 1);
@@ -412,7 +447,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
             if (i < nvec) {
               const uint4 vs = ld16(srow, i);
               const uint4 vt = TEACHER == kDense ? ld16(trow, i) : make_uint4(0, 0, 0, 0);
-              st16_stream(grow, i, grad8<TEACHER, false>(vs, vt, k));
+              st16_stream(grow, i, grad8<TEACHER, false, REV>(vs, vt, k));
             }
           }
           if constexpr (PERSIST) request_student(rnext);
@@ -426,7 +461,8 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
             for (int j = tid; j < a.k; j += kCB) grow[irow[j]] = patch[j];
           }
           if (ce && tid == 0 && !(TEACHER == kTopk && y_in_support)) {
-            const float gy = TEACHER == kDense ? grad_dense_elem(s_y, t_y, k.p) : grad_student_elem(s_y, k.p);
+            const float gy = REV ? grad_reverse_elem(s_y, t_y, k)
+                                 : (TEACHER == kDense ? grad_dense_elem(s_y, t_y, k.p) : grad_student_elem(s_y, k.p));
             grow[y] = one_bf16(gy - a.cscale);
           }
         }
@@ -449,7 +485,7 @@ int compute_units() {
   return cached[dev];
 }
 
-template <int CS, int CSR, int CT, int D, int TEACHER, bool GRAD, bool PERSIST>
+template <int CS, int CSR, int CT, int D, int TEACHER, bool GRAD, bool PERSIST, bool REV = false>
 static hipError_t launch_cached_lse1(const KdArgs& a, hipStream_t stream) {
   const size_t lds_bytes = (size_t)CT * kCB * sizeof(uint4);
   auto launch = [&](auto kernel) -> hipError_t {
@@ -464,8 +500,8 @@ static hipError_t launch_cached_lse1(const KdArgs& a, hipStream_t stream) {
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(kCB), lds_bytes, stream, a);
     return hipGetLastError();
   };
-  if (a.need_lse1) return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, true, PERSIST>);
-  return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, false, PERSIST>);
+  if (a.need_lse1) return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, true, PERSIST, REV>);
+  return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, false, PERSIST, REV>);
 }
 
 // Tuning knobs of the dense-teacher gradient kernel (measured on MI355X, 32,768 x 151,936): how many student
@@ -499,12 +535,15 @@ static int unrolled_groups(const KdArgs& a, bool want_grad) {
 // temperature; this path covers it at tau = 1, where it shares the student's exponentials.)
 bool cached_path_applies(const KdArgs& a, int teacher_kind, bool want_grad) {
   const bool grad = want_grad && teacher_kind != kNone;
+  if (a.divergence != kForwardKl && !(a.divergence == kReverseKl && grad)) return false;  // reverse KL: gradient runs
   return unrolled_groups(a, grad) > 0 && !(a.cscale != 0.0f && a.need_lse1);
 }
 
 template <int CS>
 static hipError_t launch_grad_variants(const KdArgs& a, int teacher_kind, hipStream_t stream) {
   constexpr int CSR = NPD_CSR < CS ? NPD_CSR : CS;
+  if (teacher_kind == kDense && a.divergence == kReverseKl)
+    return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, NPD_PERSIST, true>(a, stream);
   if (teacher_kind == kDense) return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, NPD_PERSIST>(a, stream);
   return launch_cached_lse1<CS, (CS < NPD_TOPK_CSR ? CS : NPD_TOPK_CSR), 0, 3, kTopk, true, false>(a, stream);
 }
