@@ -192,6 +192,11 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
   __shared__ uint16_t patch[TEACHER == kTopk && GRAD ? kTopkMax : 1];
   __shared__ int y_in_support;  // top-k teacher: the label is one of the k support positions of this row
   static_assert(CT <= CS && CSR <= CS && D >= 1 && D <= CS, "bad cache shape");
+  // a thread's parked groups are LS * 16 bytes apart from its neighbour's: an odd LS keeps 128-bit accesses
+  // conflict-free
+  constexpr int LS = CT | 1;
+  // without a dense teacher the LDS parks student groups instead: groups CSR .. CSR + SL - 1
+  constexpr int SL = TEACHER == kDense ? 0 : (CT < CS - CSR ? CT : CS - CSR);
   const int tid = threadIdx.x;
   const int voff = tid * 16;
   const int V = a.V, nvec = a.nvec_s;  // only launched with 16-byte aligned rows: nvec = V / 8
@@ -266,7 +271,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
 #pragma unroll
     for (int d = 0; d < D; ++d) {
       if constexpr (TEACHER == kDense) tst[d] = ld_group(rt, voff, d, (d) == CS - 1, GRAD ? d < CT : true);
-      if (d >= CSR) sst[d] = ld_group(rs, voff, d, (d) == CS - 1, !GRAD);
+      if (d >= CSR) sst[d] = ld_group(rs, voff, d, (d) == CS - 1, !GRAD || d < CSR + SL);
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -276,11 +281,13 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
       if (it + D < CS) {
         if constexpr (TEACHER == kDense)
           tst[it % D] = ld_group(rt, voff, it + D, (it + D) == CS - 1, GRAD ? it + D < CT : true);
-        if (it + D >= CSR) sst[it % D] = ld_group(rs, voff, it + D, (it + D) == CS - 1, !GRAD);
+        if (it + D >= CSR) sst[it % D] = ld_group(rs, voff, it + D, (it + D) == CS - 1, !GRAD || it + D < CSR + SL);
       }
       if (it < CS - 1 || it * kCB + tid < nvec) accum8<TEACHER, LSE1, REV>(vs, vt, c, lse1_t, acc);
       if constexpr (TEACHER == kDense)
-        if (it < CT) lds_t[tid * CT + it] = vt;
+        if (it < CT) lds_t[tid * LS + it] = vt;
+      if constexpr (SL > 0)
+        if (it >= CSR && it < CSR + SL) lds_t[tid * LS + (it - CSR)] = vs;
       __builtin_amdgcn_sched_barrier(0);  // keep the instruction scheduler from piling all loads up front
     }
     // ---- sweep 1, streamed part (rows longer than the cache) and the sub-group tail
@@ -322,7 +329,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
       for (int d = 0; d < D; ++d) {
         const int it = CS - 1 - d;
         if (TEACHER == kDense && it >= CT) tst[d] = ld_group(rt, voff, it, (it) == CS - 1, false, true);
-        if (it >= CSR) sst[d] = ld_group(rs, voff, it, (it) == CS - 1, false, true);
+        if (it >= CSR + SL) sst[d] = ld_group(rs, voff, it, (it) == CS - 1, false, true);
       }
     }
 
@@ -422,13 +429,15 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
             if (it < CSR) {
               opaque(sreg[it < CSR ? it : 0]);
               vs = sreg[it < CSR ? it : 0];
+            } else if (it < CSR + SL) {
+              vs = lds_t[tid * LS + (it - CSR)];
             } else {
               vs = sst[q % D];  // requested D visits ago
-              if (it - D >= CSR) sst[q % D] = ld_group(rs, voff, it - D, (it - D) == CS - 1, false, true);
+              if (it - D >= CSR + SL) sst[q % D] = ld_group(rs, voff, it - D, (it - D) == CS - 1, false, true);
             }
             if constexpr (TEACHER == kDense) {
               if (it < CT) {
-                vt = lds_t[tid * CT + it];
+                vt = lds_t[tid * LS + it];
               } else {
                 vt = tst[q % D];
                 if (it - D >= CT) tst[q % D] = ld_group(rt, voff, it - D, (it - D) == CS - 1, false, true);
@@ -487,7 +496,7 @@ int compute_units() {
 
 template <int CS, int CSR, int CT, int D, int TEACHER, bool GRAD, bool PERSIST, bool REV = false>
 static hipError_t launch_cached_lse1(const KdArgs& a, hipStream_t stream) {
-  const size_t lds_bytes = (size_t)CT * kCB * sizeof(uint4);
+  const size_t lds_bytes = CT > 0 ? (size_t)(CT | 1) * kCB * sizeof(uint4) : 0;
   auto launch = [&](auto kernel) -> hipError_t {
     if (lds_bytes > 0) {  // more than the default 64 KB of dynamic LDS has to be asked for (cheap, idempotent)
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
@@ -545,7 +554,11 @@ static hipError_t launch_grad_variants(const KdArgs& a, int teacher_kind, hipStr
   if (teacher_kind == kDense && a.divergence == kReverseKl)
     return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, NPD_PERSIST, true>(a, stream);
   if (teacher_kind == kDense) return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, NPD_PERSIST>(a, stream);
-  return launch_cached_lse1<CS, (CS < NPD_TOPK_CSR ? CS : NPD_TOPK_CSR), 0, 3, kTopk, true, false>(a, stream);
+  // top-k teacher: only the student row is dense; what does not fit the registers is parked in LDS, so the whole
+  // row is on chip for the gradient sweep
+  constexpr int TCSR = CS < NPD_TOPK_CSR ? CS : NPD_TOPK_CSR;
+  constexpr int TCL = CS - TCSR < 9 ? CS - TCSR : 9;
+  return launch_cached_lse1<CS, TCSR, TCL, 3, kTopk, true, false>(a, stream);
 }
 
 hipError_t launch_kd_cached(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream) {
