@@ -197,3 +197,12 @@ def test_cpu_logit_generation_is_reproducible():
     assert idx.shape == (300, 16) and all(len(set(r.tolist())) == 16 for r in idx)
     assert idx.min() >= 0 and idx.max() < 520
     assert torch.allclose(val.double().exp().sum(1), torch.ones(300, dtype=torch.float64), atol=1e-6)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=300)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
