@@ -66,6 +66,18 @@ __device__ __forceinline__ void st_group_stream(__amdgpu_buffer_rsrc_t r, int vo
 __device__ __forceinline__ uint4 ld16(const uint16_t* row, int group) {
   return reinterpret_cast<const uint4*>(row)[group];
 }
+#ifndef NPD_NT_STREAM2
+#define NPD_NT_STREAM2 1
+#endif
+// second (last) read of a group of the streamed part
+__device__ __forceinline__ uint4 ld16_last(const uint16_t* row, int group) {
+#if NPD_NT_STREAM2
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row) + group);
+  return make_uint4(v.x, v.y, v.z, v.w);
+#else
+  return ld16(row, group);
+#endif
+}
 __device__ __forceinline__ void st16_stream(uint16_t* row, int group, const uint4& v) {
   u32x4 w = {v.x, v.y, v.z, v.w};
   __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(row) + group);
@@ -415,8 +427,8 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
         }
         for (int i = (nit - 1) * kCB + tid; i >= CS * kCB; i -= kCB) {
           if (i < nvec) {
-            const uint4 vs = ld16(srow, i);
-            const uint4 vt = TEACHER == kDense ? ld16(trow, i) : make_uint4(0, 0, 0, 0);
+            const uint4 vs = ld16_last(srow, i);
+            const uint4 vt = TEACHER == kDense ? ld16_last(trow, i) : make_uint4(0, 0, 0, 0);
             st16_stream(grow, i, grad8<TEACHER, false, REV>(vs, vt, k));
           }
         }
