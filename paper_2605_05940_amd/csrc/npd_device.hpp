@@ -160,6 +160,57 @@ __device__ __forceinline__ float grad_dense_elem(float xs, float xt, const GradC
   return g;
 }
 
+// ---- divergences other than the forward KL (dense teacher): reverse KL, skew KL, skew reverse KL
+constexpr int kDivReverseKl = 1, kDivSkewKl = 2, kDivSkewReverseKl = 3;  // the values of npd::Divergence
+
+// per-element terms of the skew forms from log2-probabilities; returns u_c, adds this element's share of D
+// (in nats) to `dsum` and of ubar to `usum`
+// The mixture m is kept away from 0 (both probabilities underflowed), so that neither the logarithm nor the
+// reciprocal needs a guard: such an element contributes 0 * finite = 0 everywhere.
+template <int DIV>
+__device__ __forceinline__ float skew_elem(float lps, float lpt, float alpha, float& dsum, float& usum) {
+  const float ps = exp2_fast(lps), pt = exp2_fast(lpt);
+  constexpr float kTiny = 1.0e-37f;
+  float u;
+  if constexpr (DIV == kDivSkewKl) {
+    const float m = __builtin_fmaxf(__builtin_fmaf(alpha, pt, (1.0f - alpha) * ps), kTiny);
+    dsum = __builtin_fmaf(pt, (lpt - __log2f(m)) * kLn2, dsum);
+    u = (alpha - 1.0f) * pt * __builtin_amdgcn_rcpf(m);
+  } else {
+    const float m = __builtin_fmaxf(__builtin_fmaf(1.0f - alpha, pt, alpha * ps), kTiny);
+    const float l = (lps - __log2f(m)) * kLn2;
+    u = __builtin_fmaf(-alpha * ps, __builtin_amdgcn_rcpf(m), l + 1.0f);
+    dsum = __builtin_fmaf(ps, l, dsum);
+  }
+  usum = __builtin_fmaf(ps, u, usum);
+  return u;
+}
+
+struct DivCoef {
+  float c, Ls, Lt;      // log2 normalisers at temperature tau
+  float inv_tau, K;     // reverse: u - ubar = (s - t) inv_tau - K
+  float alpha, ubar;    // skew forms
+  float gscale, cscale;
+  float L1;             // log2 normaliser of the student at tau = 1 (CE term when tau != 1)
+  bool ce, ce_shared;
+};
+
+template <int DIV>
+__device__ __forceinline__ float div_grad_elem(float xs, float xt, const DivCoef& k) {
+  const float lps = __builtin_fmaf(xs, k.c, -k.Ls);
+  const float ps = exp2_fast(lps);
+  float w;
+  if constexpr (DIV == kDivReverseKl) {
+    w = __builtin_fmaf(xs - xt, k.inv_tau, -k.K);
+  } else {
+    float d = 0.0f, us = 0.0f;
+    w = skew_elem<DIV>(lps, __builtin_fmaf(xt, k.c, -k.Lt), k.alpha, d, us) - k.ubar;
+  }
+  float g = ps * (w * k.gscale);
+  if (k.ce) g = __builtin_fmaf(k.ce_shared ? ps : exp2_fast(__builtin_fmaf(xs, kLog2e, -k.L1)), k.cscale, g);
+  return g;
+}
+
 __device__ __forceinline__ void wave_merge(Lse& v) {
 #pragma unroll
   for (int off = kWave / 2; off > 0; off >>= 1) {

@@ -18,55 +18,7 @@
 
 namespace npd {
 
-// per-element terms of the skew forms from log2-probabilities; returns u_c, adds this element's share of D
-// (in nats) to `dsum` and of ubar to `usum`
-template <int DIV>
-__device__ __forceinline__ float skew_elem(float lps, float lpt, float alpha, float& dsum, float& usum) {
-  const float ps = exp2_fast(lps), pt = exp2_fast(lpt);
-  float u;
-  if constexpr (DIV == kSkewKl) {
-    const float m = __builtin_fmaf(alpha, pt, (1.0f - alpha) * ps);
-    // p_T = 0 (underflow) contributes nothing; m > 0 wherever p_T > 0
-    if (pt > 0.0f) dsum = __builtin_fmaf(pt, (lpt - __log2f(m)) * kLn2, dsum);
-    u = m > 0.0f ? -(1.0f - alpha) * pt * __builtin_amdgcn_rcpf(m) : 0.0f;
-  } else {
-    const float m = __builtin_fmaf(1.0f - alpha, pt, alpha * ps);
-    float l = 0.0f;
-    u = 0.0f;
-    if (ps > 0.0f) {
-      l = (lps - __log2f(m)) * kLn2;
-      u = __builtin_fmaf(-alpha * ps, __builtin_amdgcn_rcpf(m), l + 1.0f);
-    }
-    dsum = __builtin_fmaf(ps, l, dsum);
-  }
-  usum = __builtin_fmaf(ps, u, usum);
-  return u;
-}
-
-struct DivCoef {
-  float c, Ls, Lt;      // log2 normalisers at temperature tau
-  float inv_tau, K;     // reverse: u - ubar = (s - t) inv_tau - K
-  float alpha, ubar;    // skew forms
-  float gscale, cscale;
-  float L1;             // log2 normaliser of the student at tau = 1 (CE term when tau != 1)
-  bool ce, ce_shared;
-};
-
-template <int DIV>
-__device__ __forceinline__ float div_grad_elem(float xs, float xt, const DivCoef& k) {
-  const float lps = __builtin_fmaf(xs, k.c, -k.Ls);
-  const float ps = exp2_fast(lps);
-  float w;
-  if constexpr (DIV == kReverseKl) {
-    w = __builtin_fmaf(xs - xt, k.inv_tau, -k.K);
-  } else {
-    float d = 0.0f, us = 0.0f;
-    w = skew_elem<DIV>(lps, __builtin_fmaf(xt, k.c, -k.Lt), k.alpha, d, us) - k.ubar;
-  }
-  float g = ps * (w * k.gscale);
-  if (k.ce) g = __builtin_fmaf(k.ce_shared ? ps : exp2_fast(__builtin_fmaf(xs, kLog2e, -k.L1)), k.cscale, g);
-  return g;
-}
+static_assert(kDivReverseKl == kReverseKl && kDivSkewKl == kSkewKl && kDivSkewReverseKl == kSkewReverseKl, "");
 
 template <int BLOCK, int DIV, bool GRAD>
 __global__ __launch_bounds__(BLOCK) void div_rows_kernel(const KdArgs a) {

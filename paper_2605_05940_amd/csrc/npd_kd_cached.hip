@@ -103,6 +103,7 @@ struct Sweep2Coef {
   // reverse KL (and its CE term at tau = 1): grad = 2^(x_s c - r_S) ((x_s - x_t) ra + rb),
   //   ra = grad_scale / (tau^2 z_S),  rb = (ce_grad_scale - grad_scale / tau (lse_S - lse_T + D)) / z_S
   float ra, rb;
+  DivCoef dv;  // skew forms
 };
 
 __device__ __forceinline__ float grad_reverse_elem(float xs, float xt, const Sweep2Coef& k) {
@@ -128,15 +129,20 @@ __device__ __forceinline__ Sweep2Coef sweep2_coef(const Lse& S, const Lse& Tt, f
 }
 
 // gradient of 8 elements
-template <int TEACHER, bool FOLDED, bool REV = false>
+template <int TEACHER, bool FOLDED, int DIVK = kForwardKl>
 __device__ __forceinline__ uint4 grad8(const uint4& vs, const uint4& vt, const Sweep2Coef& k) {
   float xs[8], gv[8];
   unpack8(vs, xs);
-  if constexpr (REV) {
+  if constexpr (DIVK == kReverseKl) {
     float xt[8];
     unpack8(vt, xt);
 #pragma unroll
     for (int j = 0; j < 8; ++j) gv[j] = grad_reverse_elem(xs[j], xt[j], k);
+  } else if constexpr (DIVK != kForwardKl) {
+    float xt[8];
+    unpack8(vt, xt);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) gv[j] = div_grad_elem<DIVK>(xs[j], xt[j], k.dv);
   } else if constexpr (TEACHER == kDense) {
     float xt[8];
     unpack8(vt, xt);
@@ -162,7 +168,7 @@ __device__ __forceinline__ uint4 grad8(const uint4& vs, const uint4& vt, const S
   o.y = pack_bf16(gv[2], gv[3]);
   o.z = pack_bf16(gv[4], gv[5]);
   o.w = pack_bf16(gv[6], gv[7]);
-  if constexpr (FOLDED && !REV) {
+  if constexpr (FOLDED && DIVK == kForwardKl) {
     o.x ^= k.sign;
     o.y ^= k.sign;
     o.z ^= k.sign;
@@ -193,9 +199,12 @@ __device__ __forceinline__ void accum8(const uint4& vs, const uint4& vt, float c
   if constexpr (LSE1) acc[2].add8(xs, kLog2e);
 }
 
-template <int CS, int CSR, int CT, int D, int TEACHER, bool GRAD, bool LSE1, bool PERSIST, bool REV = false>
+template <int CS, int CSR, int CT, int D, int TEACHER, bool GRAD, bool LSE1, bool PERSIST, int DIVK = kForwardKl>
 __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
-  static_assert(!REV || (TEACHER == kDense && GRAD), "the reverse KL needs the full teacher row");
+  static_assert(DIVK == kForwardKl || (TEACHER == kDense && GRAD), "the other divergences need the full teacher row");
+  constexpr bool REV = DIVK == kReverseKl;
+  constexpr bool SKEW = DIVK == kSkewKl || DIVK == kSkewReverseKl;  // three sweeps: normalisers, D and ubar, gradient
+  static_assert(!SKEW || !PERSIST, "the three-sweep forms are not persistent");
   // teacher groups parked for sweep 2, [1024][CT]: a thread's CT groups are contiguous, so one base register
   // plus an immediate offset addresses them all; the 16 * CT byte lane stride (144 B) is conflict-free for
   // 128-bit LDS accesses
@@ -336,14 +345,46 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
 
     // groups that are neither in registers nor in LDS are requested a second time, newest first (they are
     // still in cache); the first D of them travel while the partial sums are merged
-    if constexpr (GRAD) {
+    auto request_again = [&](bool last) {
 #pragma unroll
       for (int d = 0; d < D; ++d) {
         const int it = CS - 1 - d;
-        if (TEACHER == kDense && it >= CT) tst[d] = ld_group(rt, voff, it, (it) == CS - 1, false, true);
-        if (it >= CSR + SL) sst[d] = ld_group(rs, voff, it, (it) == CS - 1, false, true);
+        if (TEACHER == kDense && it >= CT) tst[d] = ld_group(rt, voff, it, (it) == CS - 1, false, last);
+        if (it >= CSR + SL) sst[d] = ld_group(rs, voff, it, (it) == CS - 1, false, last);
       }
-    }
+    };
+    // one backward walk over the first CS groups per thread: on-chip groups from where they are, the others from
+    // the D-deep ring that request_again() primed; f(it, vs, vt) consumes a group
+    auto walk_back = [&](auto&& f, bool last) {
+      // a second walk must fetch the parked groups from LDS again rather than keep the first walk's copies (and
+      // everything derived from them) alive in registers
+      if constexpr (SKEW) asm volatile("" ::: "memory");
+#pragma unroll
+      for (int q = 0; q < CS; ++q) {
+        const int it = CS - 1 - q;
+        uint4 vs, vt = make_uint4(0, 0, 0, 0);
+        if (it < CSR) {
+          opaque(sreg[it < CSR ? it : 0]);
+          vs = sreg[it < CSR ? it : 0];
+        } else if (it < CSR + SL) {
+          vs = lds_t[tid * LS + (it - CSR)];
+        } else {
+          vs = sst[q % D];  // requested D visits ago
+          if (it - D >= CSR + SL) sst[q % D] = ld_group(rs, voff, it - D, (it - D) == CS - 1, false, last);
+        }
+        if constexpr (TEACHER == kDense) {
+          if (it < CT) {
+            vt = lds_t[tid * LS + it];
+          } else {
+            vt = tst[q % D];
+            if (it - D >= CT) tst[q % D] = ld_group(rt, voff, it - D, (it - D) == CS - 1, false, last);
+          }
+        }
+        f(it, vs, vt);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    if constexpr (GRAD) request_again(!SKEW);
 
     block_merge<kCB, NS>(acc, red);
 
@@ -355,7 +396,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
     if constexpr (TEACHER == kDense) {
       lse_diff = ((acc[0].r - acc[1].r) + (acc[0].log2_z() - acc[1].log2_z())) * kLn2;
       kd = REV ? (acc[0].a / acc[0].z) * a.inv_tau - lse_diff : (acc[1].a / acc[1].z) * a.inv_tau + lse_diff;
-      kd = kd < 0.0f ? 0.0f : kd;
+      kd = kd < 0.0f ? 0.0f : kd;  // (the skew forms replace it below)
     }
     const bool ce = GRAD && a.cscale != 0.0f;                       // uniform (tau = 1 here whenever it is set)
     const bool bad_label = a.labels && (unsigned)y >= (unsigned)V;  // uniform
@@ -365,6 +406,45 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
       k.ra = a.gscale * a.inv_tau * inv_z;
       k.rb = (a.cscale - a.gscale * (lse_diff + kd)) * inv_z;
       k.folded = true;  // one form for all rows: the exponent is taken against the row's reference as in sweep 1
+    }
+    if constexpr (SKEW) {
+      k.dv.c = c;
+      k.dv.Ls = Ls;
+      k.dv.Lt = Lt;
+      k.dv.inv_tau = a.inv_tau;
+      k.dv.K = 0.0f;
+      k.dv.alpha = a.alpha;
+      k.dv.gscale = a.gscale;
+      k.dv.cscale = a.cscale;
+      k.dv.L1 = Ls;
+      k.dv.ce = ce;
+      k.dv.ce_shared = true;  // tau = 1 whenever the CE term is present on this path
+      k.folded = true;
+      // ---- sweep 2 of the skew forms: D and ubar over normalised probabilities; same walk as the gradient sweep
+      float dsum = 0.0f, usum = 0.0f;
+      auto accum = [&](const uint4& vs, const uint4& vt) {
+        float xs[8], xt[8];
+        unpack8(vs, xs);
+        unpack8(vt, xt);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          skew_elem<DIVK>(__builtin_fmaf(xs[j], c, -Ls), __builtin_fmaf(xt[j], c, -Lt), a.alpha, dsum, usum);
+        // both running sums are due here: otherwise the compiler sinks one chain below the whole walk and keeps
+        // every element's probabilities alive for it (in scratch memory)
+        asm volatile("" : "+v"(dsum), "+v"(usum));
+      };
+      for (int e = nvec * 8 + tid; e < V; e += kCB)
+        skew_elem<DIVK>(__builtin_fmaf(bf16_one(srow[e]), c, -Ls), __builtin_fmaf(bf16_one(trow[e]), c, -Lt), a.alpha,
+                        dsum, usum);
+      for (int i = (nit - 1) * kCB + tid; i >= CS * kCB; i -= kCB)
+        if (i < nvec) accum(ld16(srow, i), ld16(trow, i));
+      walk_back([&](int it, const uint4& vs, const uint4& vt) {
+        if (it < CS - 1 || it * kCB + tid < nvec) accum(vs, vt);
+      }, false);
+      request_again(true);  // travels while the two sums are merged
+      kd = block_sum<kCB>(dsum, red);
+      kd = kd < 0.0f ? 0.0f : kd;
+      k.dv.ubar = block_sum<kCB>(usum, red);
     }
     if constexpr (TEACHER == kTopk) {
       bad_index = __syncthreads_or(bad_index);
@@ -421,6 +501,8 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
           const float xs = bf16_one(srow[e]);
           if constexpr (REV)
             grow[e] = one_bf16(grad_reverse_elem(xs, bf16_one(trow[e]), k));
+          else if constexpr (SKEW)
+            grow[e] = one_bf16(div_grad_elem<DIVK>(xs, bf16_one(trow[e]), k.dv));
           else
             grow[e] = one_bf16(TEACHER == kDense ? grad_dense_elem(xs, bf16_one(trow[e]), k.p)
                                                  : grad_student_elem(xs, k.p));
@@ -429,13 +511,14 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
           if (i < nvec) {
             const uint4 vs = ld16_last(srow, i);
             const uint4 vt = TEACHER == kDense ? ld16_last(trow, i) : make_uint4(0, 0, 0, 0);
-            st16_stream(grow, i, grad8<TEACHER, false, REV>(vs, vt, k));
+            st16_stream(grow, i, grad8<TEACHER, false, DIVK>(vs, vt, k));
           }
         }
         if (k.folded) {  // uniform
           // a register-resident student group makes room, once used, for the same group of the next row
+          if constexpr (SKEW) asm volatile("" ::: "memory");  // see walk_back
 #pragma unroll
-          for (int q = 0; q < CS; ++q) {
+          for (int q = 0; q < CS; ++q) {  // the same walk as walk_back, spelled out (register allocation differs)
             const int it = CS - 1 - q;
             uint4 vs, vt = make_uint4(0, 0, 0, 0);
             if (it < CSR) {
@@ -456,7 +539,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
               }
             }
             {
-              const uint4 gq = grad8<TEACHER, true, REV>(vs, vt, k);
+              const uint4 gq = grad8<TEACHER, true, DIVK>(vs, vt, k);
               if (it < CS - 1 || it * kCB + tid < nvec) st16_stream(grow, it * kCB + tid, gq);
             }
             if (PERSIST && it < CSR) sreg[it < CSR ? it : 0] = ld_group(rnext, voff, it, (it) == CS - 1);
@@ -468,7 +551,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
             if (i < nvec) {
               const uint4 vs = ld16(srow, i);
               const uint4 vt = TEACHER == kDense ? ld16(trow, i) : make_uint4(0, 0, 0, 0);
-              st16_stream(grow, i, grad8<TEACHER, false, REV>(vs, vt, k));
+              st16_stream(grow, i, grad8<TEACHER, false, DIVK>(vs, vt, k));
             }
           }
           if constexpr (PERSIST) request_student(rnext);
@@ -482,8 +565,13 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
             for (int j = tid; j < a.k; j += kCB) grow[irow[j]] = patch[j];
           }
           if (ce && tid == 0 && !(TEACHER == kTopk && y_in_support)) {
-            const float gy = REV ? grad_reverse_elem(s_y, t_y, k)
-                                 : (TEACHER == kDense ? grad_dense_elem(s_y, t_y, k.p) : grad_student_elem(s_y, k.p));
+            float gy;
+            if constexpr (REV)
+              gy = grad_reverse_elem(s_y, t_y, k);
+            else if constexpr (SKEW)
+              gy = div_grad_elem<DIVK>(s_y, t_y, k.dv);
+            else
+              gy = TEACHER == kDense ? grad_dense_elem(s_y, t_y, k.p) : grad_student_elem(s_y, k.p);
             grow[y] = one_bf16(gy - a.cscale);
           }
         }
@@ -506,7 +594,7 @@ int compute_units() {
   return cached[dev];
 }
 
-template <int CS, int CSR, int CT, int D, int TEACHER, bool GRAD, bool PERSIST, bool REV = false>
+template <int CS, int CSR, int CT, int D, int TEACHER, bool GRAD, bool PERSIST, int DIVK = kForwardKl>
 static hipError_t launch_cached_lse1(const KdArgs& a, hipStream_t stream) {
   const size_t lds_bytes = CT > 0 ? (size_t)(CT | 1) * kCB * sizeof(uint4) : 0;
   auto launch = [&](auto kernel) -> hipError_t {
@@ -521,8 +609,8 @@ static hipError_t launch_cached_lse1(const KdArgs& a, hipStream_t stream) {
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(kCB), lds_bytes, stream, a);
     return hipGetLastError();
   };
-  if (a.need_lse1) return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, true, PERSIST, REV>);
-  return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, false, PERSIST, REV>);
+  if (a.need_lse1) return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, true, PERSIST, DIVK>);
+  return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, false, PERSIST, DIVK>);
 }
 
 // Tuning knobs of the dense-teacher gradient kernel (measured on MI355X, 32,768 x 151,936): how many student
@@ -556,7 +644,7 @@ static int unrolled_groups(const KdArgs& a, bool want_grad) {
 // temperature; this path covers it at tau = 1, where it shares the student's exponentials.)
 bool cached_path_applies(const KdArgs& a, int teacher_kind, bool want_grad) {
   const bool grad = want_grad && teacher_kind != kNone;
-  if (a.divergence != kForwardKl && !(a.divergence == kReverseKl && grad)) return false;  // reverse KL: gradient runs
+  if (a.divergence != kForwardKl && !grad) return false;  // the other divergences: gradient runs only
   return unrolled_groups(a, grad) > 0 && !(a.cscale != 0.0f && a.need_lse1);
 }
 
@@ -564,7 +652,11 @@ template <int CS>
 static hipError_t launch_grad_variants(const KdArgs& a, int teacher_kind, hipStream_t stream) {
   constexpr int CSR = NPD_CSR < CS ? NPD_CSR : CS;
   if (teacher_kind == kDense && a.divergence == kReverseKl)
-    return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, NPD_PERSIST, true>(a, stream);
+    return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, NPD_PERSIST, kReverseKl>(a, stream);
+  if (teacher_kind == kDense && a.divergence == kSkewKl)
+    return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, false, kSkewKl>(a, stream);
+  if (teacher_kind == kDense && a.divergence == kSkewReverseKl)
+    return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, false, kSkewReverseKl>(a, stream);
   if (teacher_kind == kDense) return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, NPD_PERSIST>(a, stream);
   // top-k teacher: only the student row is dense; what does not fit the registers is parked in LDS, so the whole
   // row is on chip for the gradient sweep

@@ -627,6 +627,7 @@ def _topk_gpu(t, k, mask=None, log_probs=True):
     (151936, 151936, 64, True),      # config 2's record
     (151936, 151936, 10, False),     # the paper's default k, raw logits
     (151936, 151936, 1, True),       # arg-max
+    (262144, 262144, 64, False),     # 32 groups per thread: the window is refilled twice
     (262144, 262144, 1024, True),    # as many entries as threads
     (40000, 40000, 2000, False),     # k beyond the per-thread-maximum bound: exact slow path
     (151936, 151936, 256, True),     # long candidate list: radix cut before the ordering
