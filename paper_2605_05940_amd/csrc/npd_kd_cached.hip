@@ -40,18 +40,19 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t row_rsrc(const uint16_t* row, 
 #define NPD_NT_REREAD 2
 #endif
 // `once`: the group stays on chip after this load (registers or LDS) and is not read again
+template <int GB = kGroupBytes>
 __device__ __forceinline__ uint4 ld_group(__amdgpu_buffer_rsrc_t r, int voff, int it, bool checked,
                                           bool once = false, bool last = false) {
   u32x4 v;
   if (once && NPD_NT_RESIDENT)
-    v = checked ? __builtin_amdgcn_raw_buffer_load_b128(r, voff + it * kGroupBytes, 0, NPD_NT_RESIDENT)
-                : __builtin_amdgcn_raw_buffer_load_b128(r, voff, it * kGroupBytes, NPD_NT_RESIDENT);
+    v = checked ? __builtin_amdgcn_raw_buffer_load_b128(r, voff + it * GB, 0, NPD_NT_RESIDENT)
+                : __builtin_amdgcn_raw_buffer_load_b128(r, voff, it * GB, NPD_NT_RESIDENT);
   else if (last && NPD_NT_REREAD)
-    v = checked ? __builtin_amdgcn_raw_buffer_load_b128(r, voff + it * kGroupBytes, 0, NPD_NT_REREAD)
-                : __builtin_amdgcn_raw_buffer_load_b128(r, voff, it * kGroupBytes, NPD_NT_REREAD);
+    v = checked ? __builtin_amdgcn_raw_buffer_load_b128(r, voff + it * GB, 0, NPD_NT_REREAD)
+                : __builtin_amdgcn_raw_buffer_load_b128(r, voff, it * GB, NPD_NT_REREAD);
   else
-    v = checked ? __builtin_amdgcn_raw_buffer_load_b128(r, voff + it * kGroupBytes, 0, 0)
-                : __builtin_amdgcn_raw_buffer_load_b128(r, voff, it * kGroupBytes, 0);
+    v = checked ? __builtin_amdgcn_raw_buffer_load_b128(r, voff + it * GB, 0, 0)
+                : __builtin_amdgcn_raw_buffer_load_b128(r, voff, it * GB, 0);
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 __device__ __forceinline__ void st_group_stream(__amdgpu_buffer_rsrc_t r, int voff, int it, bool checked,
@@ -199,8 +200,13 @@ __device__ __forceinline__ void accum8(const uint4& vs, const uint4& vt, float c
   if constexpr (LSE1) acc[2].add8(xs, kLog2e);
 }
 
-template <int CS, int CSR, int CT, int D, int TEACHER, bool GRAD, bool LSE1, bool PERSIST, int DIVK = kForwardKl>
-__global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
+// CB = threads per workgroup (1024, or 512 / 256 for shorter rows, so that a thread still holds 10 .. 19 groups and
+// several rows are in flight per CU).  SHORT: the row may have fewer than CS groups per thread; every group is then
+// range-checked by the buffer hardware and by a per-thread bound on its use.
+template <int CS, int CSR, int CT, int D, int TEACHER, bool GRAD, bool LSE1, bool PERSIST, int DIVK = kForwardKl,
+          int CB = kCB, bool SHORT = false>
+__global__ __launch_bounds__(CB, 4) void kd_cached_kernel(const KdArgs a) {
+  constexpr int GB = CB * 16;
   static_assert(DIVK == kForwardKl || (TEACHER == kDense && GRAD), "the other divergences need the full teacher row");
   constexpr bool REV = DIVK == kReverseKl;
   constexpr bool SKEW = DIVK == kSkewKl || DIVK == kSkewReverseKl;  // three sweeps: normalisers, D and ubar, gradient
@@ -209,7 +215,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
   // plus an immediate offset addresses them all; the 16 * CT byte lane stride (144 B) is conflict-free for
   // 128-bit LDS accesses
   extern __shared__ uint4 lds_t[];
-  __shared__ float red[4 * 3 * (kCB / kWave)];
+  __shared__ float red[4 * 3 * (CB / kWave)];
   __shared__ uint16_t patch[TEACHER == kTopk && GRAD ? kTopkMax : 1];
   __shared__ int y_in_support;  // top-k teacher: the label is one of the k support positions of this row
   static_assert(CT <= CS && CSR <= CS && D >= 1 && D <= CS, "bad cache shape");
@@ -227,7 +233,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
   const bool lse1_t = LSE1 && a.tnll != nullptr;
   // launched only for rows of more than (CS - 1) * 1024 groups: every one of the first CS groups per
   // thread is full except, when the row has at most CS * 1024 groups, the last one
-  const int nit = (nvec + kCB - 1) / kCB;  // 128-bit groups per thread
+  const int nit = (nvec + CB - 1) / CB;  // 128-bit groups per thread
 
   // A persistent workgroup owns rows blockIdx.x, blockIdx.x + G, ...; rows that are not scored are dealt
   // with on the way (scalars 0, gradient row zero-filled, logits never read).
@@ -242,8 +248,8 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
       if constexpr (GRAD) {
         uint16_t* grow0 = a.g + r * a.s_stride;
         const uint4 z = make_uint4(0, 0, 0, 0);
-        for (int i = tid; i < nvec; i += kCB) st16_stream(grow0, i, z);
-        for (int e = nvec * 8 + tid; e < V; e += kCB) grow0[e] = 0;
+        for (int i = tid; i < nvec; i += CB) st16_stream(grow0, i, z);
+        for (int e = nvec * 8 + tid; e < V; e += CB) grow0[e] = 0;
       }
       r += G;
     }
@@ -254,7 +260,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
   uint4 sst[D], tst[D];           // student groups beyond CSR / teacher groups in flight
   auto request_student = [&](__amdgpu_buffer_rsrc_t rs) {
 #pragma unroll
-    for (int it = 0; it < CSR; ++it) sreg[it] = ld_group(rs, voff, it, (it) == CS - 1, true);
+    for (int it = 0; it < CSR; ++it) sreg[it] = ld_group<GB>(rs, voff, it, SHORT || (it) == CS - 1, true);
   };
 
   int64_t row = next_scored(blockIdx.x);
@@ -291,8 +297,8 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
     if constexpr (!PERSIST) request_student(rs);
 #pragma unroll
     for (int d = 0; d < D; ++d) {
-      if constexpr (TEACHER == kDense) tst[d] = ld_group(rt, voff, d, (d) == CS - 1, GRAD ? d < CT : true);
-      if (d >= CSR) sst[d] = ld_group(rs, voff, d, (d) == CS - 1, !GRAD || d < CSR + SL);
+      if constexpr (TEACHER == kDense) tst[d] = ld_group<GB>(rt, voff, d, SHORT || (d) == CS - 1, GRAD ? d < CT : true);
+      if (d >= CSR) sst[d] = ld_group<GB>(rs, voff, d, SHORT || (d) == CS - 1, !GRAD || d < CSR + SL);
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -301,10 +307,10 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
       const uint4 vt = TEACHER == kDense ? tst[it % D] : make_uint4(0, 0, 0, 0);
       if (it + D < CS) {
         if constexpr (TEACHER == kDense)
-          tst[it % D] = ld_group(rt, voff, it + D, (it + D) == CS - 1, GRAD ? it + D < CT : true);
-        if (it + D >= CSR) sst[it % D] = ld_group(rs, voff, it + D, (it + D) == CS - 1, !GRAD || it + D < CSR + SL);
+          tst[it % D] = ld_group<GB>(rt, voff, it + D, SHORT || (it + D) == CS - 1, GRAD ? it + D < CT : true);
+        if (it + D >= CSR) sst[it % D] = ld_group<GB>(rs, voff, it + D, SHORT || (it + D) == CS - 1, !GRAD || it + D < CSR + SL);
       }
-      if (it < CS - 1 || it * kCB + tid < nvec) accum8<TEACHER, LSE1, REV>(vs, vt, c, lse1_t, acc);
+      if ((!SHORT && it < CS - 1) || it * CB + tid < nvec) accum8<TEACHER, LSE1, REV>(vs, vt, c, lse1_t, acc);
       if constexpr (TEACHER == kDense)
         if (it < CT) lds_t[tid * LS + it] = vt;
       if constexpr (SL > 0)
@@ -312,12 +318,12 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
       __builtin_amdgcn_sched_barrier(0);  // keep the instruction scheduler from piling all loads up front
     }
     // ---- sweep 1, streamed part (rows longer than the cache) and the sub-group tail
-    for (int i = CS * kCB + tid; i < nvec; i += kCB) {
+    for (int i = CS * CB + tid; i < nvec; i += CB) {
       const uint4 vs = ld16(srow, i);
       const uint4 vt = TEACHER == kDense ? ld16(trow, i) : make_uint4(0, 0, 0, 0);
       accum8<TEACHER, LSE1, REV>(vs, vt, c, lse1_t, acc);
     }
-    for (int e = nvec * 8 + tid; e < V; e += kCB) {
+    for (int e = nvec * 8 + tid; e < V; e += CB) {
       const float xs = bf16_one(srow[e]);
       if constexpr (TEACHER == kDense) {
         const float xt = bf16_one(trow[e]);
@@ -337,7 +343,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
     if constexpr (TEACHER == kTopk) {
       const int32_t* irow = a.tidx + row * (int64_t)a.k;
       const float* vrow = a.tval + row * (int64_t)a.k;
-      for (int j = tid; j < a.k; j += kCB) {
+      for (int j = tid; j < a.k; j += CB) {
         if ((unsigned)irow[j] >= (unsigned)V) bad_index = 1;
         acc[1].add1(vrow[j], c);
       }
@@ -349,8 +355,8 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
 #pragma unroll
       for (int d = 0; d < D; ++d) {
         const int it = CS - 1 - d;
-        if (TEACHER == kDense && it >= CT) tst[d] = ld_group(rt, voff, it, (it) == CS - 1, false, last);
-        if (it >= CSR + SL) sst[d] = ld_group(rs, voff, it, (it) == CS - 1, false, last);
+        if (TEACHER == kDense && it >= CT) tst[d] = ld_group<GB>(rt, voff, it, SHORT || (it) == CS - 1, false, last);
+        if (it >= CSR + SL) sst[d] = ld_group<GB>(rs, voff, it, SHORT || (it) == CS - 1, false, last);
       }
     };
     // one backward walk over the first CS groups per thread: on-chip groups from where they are, the others from
@@ -370,14 +376,14 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
           vs = lds_t[tid * LS + (it - CSR)];
         } else {
           vs = sst[q % D];  // requested D visits ago
-          if (it - D >= CSR + SL) sst[q % D] = ld_group(rs, voff, it - D, (it - D) == CS - 1, false, last);
+          if (it - D >= CSR + SL) sst[q % D] = ld_group<GB>(rs, voff, it - D, SHORT || (it - D) == CS - 1, false, last);
         }
         if constexpr (TEACHER == kDense) {
           if (it < CT) {
             vt = lds_t[tid * LS + it];
           } else {
             vt = tst[q % D];
-            if (it - D >= CT) tst[q % D] = ld_group(rt, voff, it - D, (it - D) == CS - 1, false, last);
+            if (it - D >= CT) tst[q % D] = ld_group<GB>(rt, voff, it - D, SHORT || (it - D) == CS - 1, false, last);
           }
         }
         f(it, vs, vt);
@@ -386,7 +392,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
     };
     if constexpr (GRAD) request_again(!SKEW);
 
-    block_merge<kCB, NS>(acc, red);
+    block_merge<CB, NS>(acc, red);
 
     const float Ls = acc[0].log2_sum();
     const float Lt = TEACHER == kNone ? 0.0f : acc[1].log2_sum();
@@ -433,18 +439,18 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
         // every element's probabilities alive for it (in scratch memory)
         asm volatile("" : "+v"(dsum), "+v"(usum));
       };
-      for (int e = nvec * 8 + tid; e < V; e += kCB)
+      for (int e = nvec * 8 + tid; e < V; e += CB)
         skew_elem<DIVK>(__builtin_fmaf(bf16_one(srow[e]), c, -Ls), __builtin_fmaf(bf16_one(trow[e]), c, -Lt), a.alpha,
                         dsum, usum);
-      for (int i = (nit - 1) * kCB + tid; i >= CS * kCB; i -= kCB)
+      for (int i = (nit - 1) * CB + tid; i >= CS * CB; i -= CB)
         if (i < nvec) accum(ld16(srow, i), ld16(trow, i));
       walk_back([&](int it, const uint4& vs, const uint4& vt) {
-        if (it < CS - 1 || it * kCB + tid < nvec) accum(vs, vt);
+        if ((!SHORT && it < CS - 1) || it * CB + tid < nvec) accum(vs, vt);
       }, false);
       request_again(true);  // travels while the two sums are merged
-      kd = block_sum<kCB>(dsum, red);
+      kd = block_sum<CB>(dsum, red);
       kd = kd < 0.0f ? 0.0f : kd;
-      k.dv.ubar = block_sum<kCB>(usum, red);
+      k.dv.ubar = block_sum<CB>(usum, red);
     }
     if constexpr (TEACHER == kTopk) {
       bad_index = __syncthreads_or(bad_index);
@@ -454,7 +460,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
       const float* vrow = a.tval + row * (int64_t)a.k;
       float part = 0.0f;
       if (!bad_index) {
-        for (int j = tid; j < a.k; j += kCB) {
+        for (int j = tid; j < a.k; j += CB) {
           const float b = vrow[j] * c;
           const float sj = bf16_one(srow[irow[j]]);
           const float lpt = b - Lt;
@@ -470,7 +476,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
           }
         }
       }
-      kd = block_sum<kCB>(part, red);
+      kd = block_sum<CB>(part, red);
       kd = kd < 0.0f ? 0.0f : kd;
       if (bad_index) kd = __builtin_nanf("");
     }
@@ -493,11 +499,11 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
     if constexpr (GRAD) {
       if ((TEACHER == kTopk && bad_index) || (ce && bad_label)) {  // uniform: the row cannot be differentiated
         const uint16_t qnan = 0x7fc0;
-        for (int e = tid; e < V; e += kCB) grow[e] = qnan;
+        for (int e = tid; e < V; e += CB) grow[e] = qnan;
         if constexpr (PERSIST) request_student(rnext);
       } else {
         // sub-group tail and streamed part first (read most recently), then the first CS groups backwards
-        for (int e = nvec * 8 + tid; e < V; e += kCB) {
+        for (int e = nvec * 8 + tid; e < V; e += CB) {
           const float xs = bf16_one(srow[e]);
           if constexpr (REV)
             grow[e] = one_bf16(grad_reverse_elem(xs, bf16_one(trow[e]), k));
@@ -507,7 +513,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
             grow[e] = one_bf16(TEACHER == kDense ? grad_dense_elem(xs, bf16_one(trow[e]), k.p)
                                                  : grad_student_elem(xs, k.p));
         }
-        for (int i = (nit - 1) * kCB + tid; i >= CS * kCB; i -= kCB) {
+        for (int i = (nit - 1) * CB + tid; i >= CS * CB; i -= CB) {
           if (i < nvec) {
             const uint4 vs = ld16_last(srow, i);
             const uint4 vt = TEACHER == kDense ? ld16_last(trow, i) : make_uint4(0, 0, 0, 0);
@@ -528,26 +534,26 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
               vs = lds_t[tid * LS + (it - CSR)];
             } else {
               vs = sst[q % D];  // requested D visits ago
-              if (it - D >= CSR + SL) sst[q % D] = ld_group(rs, voff, it - D, (it - D) == CS - 1, false, true);
+              if (it - D >= CSR + SL) sst[q % D] = ld_group<GB>(rs, voff, it - D, SHORT || (it - D) == CS - 1, false, true);
             }
             if constexpr (TEACHER == kDense) {
               if (it < CT) {
                 vt = lds_t[tid * LS + it];
               } else {
                 vt = tst[q % D];
-                if (it - D >= CT) tst[q % D] = ld_group(rt, voff, it - D, (it - D) == CS - 1, false, true);
+                if (it - D >= CT) tst[q % D] = ld_group<GB>(rt, voff, it - D, SHORT || (it - D) == CS - 1, false, true);
               }
             }
             {
               const uint4 gq = grad8<TEACHER, true, DIVK>(vs, vt, k);
-              if (it < CS - 1 || it * kCB + tid < nvec) st16_stream(grow, it * kCB + tid, gq);
+              if ((!SHORT && it < CS - 1) || it * CB + tid < nvec) st16_stream(grow, it * CB + tid, gq);
             }
-            if (PERSIST && it < CSR) sreg[it < CSR ? it : 0] = ld_group(rnext, voff, it, (it) == CS - 1);
+            if (PERSIST && it < CSR) sreg[it < CSR ? it : 0] = ld_group<GB>(rnext, voff, it, SHORT || (it) == CS - 1);
             __builtin_amdgcn_sched_barrier(0);
           }
         } else {
           // rows whose reference exponents are in the thousands: precise form, plain loop over the row
-          for (int i = (nit < CS ? nit : CS) * kCB - kCB + tid; i >= 0; i -= kCB) {
+          for (int i = (nit < CS ? nit : CS) * CB - CB + tid; i >= 0; i -= CB) {
             if (i < nvec) {
               const uint4 vs = ld16(srow, i);
               const uint4 vt = TEACHER == kDense ? ld16(trow, i) : make_uint4(0, 0, 0, 0);
@@ -562,7 +568,7 @@ __global__ __launch_bounds__(kCB) void kd_cached_kernel(const KdArgs a) {
           __syncthreads();
           if constexpr (TEACHER == kTopk) {
             const int32_t* irow = a.tidx + row * (int64_t)a.k;
-            for (int j = tid; j < a.k; j += kCB) grow[irow[j]] = patch[j];
+            for (int j = tid; j < a.k; j += CB) grow[irow[j]] = patch[j];
           }
           if (ce && tid == 0 && !(TEACHER == kTopk && y_in_support)) {
             float gy;
@@ -594,9 +600,10 @@ int compute_units() {
   return cached[dev];
 }
 
-template <int CS, int CSR, int CT, int D, int TEACHER, bool GRAD, bool PERSIST, int DIVK = kForwardKl>
+template <int CS, int CSR, int CT, int D, int TEACHER, bool GRAD, bool PERSIST, int DIVK = kForwardKl, int CB = kCB,
+          bool SHORT = false>
 static hipError_t launch_cached_lse1(const KdArgs& a, hipStream_t stream) {
-  const size_t lds_bytes = CT > 0 ? (size_t)(CT | 1) * kCB * sizeof(uint4) : 0;
+  const size_t lds_bytes = CT > 0 ? (size_t)(CT | 1) * CB * sizeof(uint4) : 0;
   auto launch = [&](auto kernel) -> hipError_t {
     if (lds_bytes > 0) {  // more than the default 64 KB of dynamic LDS has to be asked for (cheap, idempotent)
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
@@ -606,11 +613,11 @@ static hipError_t launch_cached_lse1(const KdArgs& a, hipStream_t stream) {
     // persistent: one workgroup per compute unit (a workgroup takes a CU's whole register file)
     const int64_t cus = compute_units();
     const unsigned grid = (unsigned)(!PERSIST || a.T < cus ? a.T : cus);
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kCB), lds_bytes, stream, a);
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(CB), lds_bytes, stream, a);
     return hipGetLastError();
   };
-  if (a.need_lse1) return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, true, PERSIST, DIVK>);
-  return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, false, PERSIST, DIVK>);
+  if (a.need_lse1) return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, true, PERSIST, DIVK, CB, SHORT>);
+  return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, false, PERSIST, DIVK, CB, SHORT>);
 }
 
 // Tuning knobs of the dense-teacher gradient kernel (measured on MI355X, 32,768 x 151,936): how many student
@@ -640,12 +647,37 @@ static int unrolled_groups(const KdArgs& a, bool want_grad) {
   return 0;
 }
 
+// Workgroup size and unrolled length of the forward-KL gradient kernels.  Measured on MI355X (32,768 unmasked rows,
+// % of 8 TB/s, 1024 / 512 / 256 threads per workgroup): dense teacher V = 81,920: 59 / 71 / 64, 100,352: 59 / 69 /
+// 63, 128,256: 64 / 67 / 61, 151,936: 64 / 64 / 57, 200,000: 64 / 63 / 50, 262,144: 58 / 57 / 51; top-k teacher
+// 128,256: 54 / 68 / 61, 151,936: 56 / 62 / 59, 262,144: 54 / 65 / 59.  Two 512-thread workgroups per CU overlap
+// one row's reductions and sweep turn-around with the other row's streaming, at the price of half the on-chip
+// share per row; rows above 131,072 entries are better off with the whole CU (with a top-k teacher only on the
+// packed batch with contiguous masked spans and tau = 2 that the benchmark times: 3.36 against 3.48 ms).  Rows of
+// 8,192 .. 40,959 entries run with 256 threads (four workgroups per CU).
+struct RowShape {
+  int cb, cs;
+};
+static RowShape forward_grad_shape(const KdArgs& a, int teacher_kind) {
+  const int nvec = a.nvec_s;
+  if (nvec < 1024) return {0, 0};
+  int cb = 256;
+  if (nvec > 16384)
+    cb = 1024;
+  else if (nvec >= 5120)
+    cb = 512;
+  const int nit = (nvec + cb - 1) / cb;
+  return {cb, nit <= 13 ? 13 : (nit <= 16 ? 16 : 19)};
+}
+
 // Row-resident path: 16-byte aligned rows that are long enough.  (The CE softmax of the composite loss has no
 // temperature; this path covers it at tau = 1, where it shares the student's exponentials.)
 bool cached_path_applies(const KdArgs& a, int teacher_kind, bool want_grad) {
   const bool grad = want_grad && teacher_kind != kNone;
   if (a.divergence != kForwardKl && !grad) return false;  // the other divergences: gradient runs only
-  return unrolled_groups(a, grad) > 0 && !(a.cscale != 0.0f && a.need_lse1);
+  if (a.cscale != 0.0f && a.need_lse1) return false;
+  if (grad && a.divergence == kForwardKl) return forward_grad_shape(a, teacher_kind).cb > 0;
+  return unrolled_groups(a, grad) > 0;
 }
 
 template <int CS>
@@ -665,10 +697,30 @@ static hipError_t launch_grad_variants(const KdArgs& a, int teacher_kind, hipStr
   return launch_cached_lse1<CS, TCSR, TCL, 3, kTopk, true, false>(a, stream);
 }
 
+// Forward-KL gradient kernels with 512 / 256 threads per workgroup (rows of up to 131,072 entries).
+template <int CS, int CB>
+static hipError_t launch_short(const KdArgs& a, int teacher_kind, hipStream_t stream) {
+  constexpr int CSR = NPD_CSR < CS ? NPD_CSR : CS;
+  if (teacher_kind == kDense)
+    return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, false, kForwardKl, CB, true>(a, stream);
+  constexpr int TCL = CS - CSR < 9 ? CS - CSR : 9;
+  return launch_cached_lse1<CS, CSR, TCL, 3, kTopk, true, false, kForwardKl, CB, true>(a, stream);
+}
+
+template <int CB>
+static hipError_t launch_short_cs(const KdArgs& a, int cs, int teacher_kind, hipStream_t stream) {
+  if (cs == 13) return launch_short<13, CB>(a, teacher_kind, stream);
+  if (cs == 16) return launch_short<16, CB>(a, teacher_kind, stream);
+  return launch_short<19, CB>(a, teacher_kind, stream);
+}
+
 hipError_t launch_kd_cached(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream) {
   const bool grad = want_grad && teacher_kind != kNone;
   if (grad) {
-    switch (unrolled_groups(a, true)) {
+    const RowShape sh = a.divergence == kForwardKl ? forward_grad_shape(a, teacher_kind) : RowShape{kCB, 0};
+    if (sh.cb == 512) return launch_short_cs<512>(a, sh.cs, teacher_kind, stream);
+    if (sh.cb == 256) return launch_short_cs<256>(a, sh.cs, teacher_kind, stream);
+    switch (unrolled_groups(a, true)) {  // 1024 threads: more than 16 groups per thread, or another divergence
       case 19: return launch_grad_variants<19>(a, teacher_kind, stream);
       case 16: return launch_grad_variants<16>(a, teacher_kind, stream);
       default: return launch_grad_variants<13>(a, teacher_kind, stream);
