@@ -1,17 +1,22 @@
-// Row-resident variant of the fused KD loss + gradient kernel for large vocabularies (gfx950).
+// Row-resident variant of the fused KD loss + gradient kernel (gfx950): rows of 8,192 entries and more, 16-byte
+// aligned.
 //
-// One persistent workgroup per compute unit walks over token rows.  A token row of ~150k bf16 logits (student + teacher = 608 KB) does not fit one CU, but most of it
-// does: 1024 threads x CS 128-bit groups of the student row stay in VGPRs (packed bf16, as loaded),
-// the first CT groups-per-thread of the teacher row are parked in LDS, and only the remaining teacher
-// groups are read a second time -- last-read-first, so they come from the XCD's L2, not from HBM.
-// HBM then sees each logit once and each gradient element once.  The gradient goes out with
-// non-temporal 128-bit stores after all of the row's loads: reads and writes reach HBM in separate
-// bursts, which it serves faster than an interleaved mix.
+// One workgroup per token row.  A row of ~150k bf16 logits (student + teacher = 608 KB) does not fit one CU, but most
+// of it does: CB threads x CSR 128-bit groups of the student row stay in VGPRs (packed bf16, as loaded), CT groups
+// per thread of the teacher row are parked in LDS, and only the remaining groups are read a second time --
+// last-read-first, so that many of them still sit in the XCD's L2.  The gradient goes out with non-temporal 128-bit
+// stores; loads of groups that stay on chip, and every second read, carry the non-temporal hint so that they do not
+// displace what is still to be read again.
 //
-// Loads are software-pipelined by hand: group it + D is requested before group it is consumed.  The
-// cached part is straight-line code (CS is a template parameter and every cached group but the last is
-// full), so the compiler can keep several loads in flight.  Groups beyond the cached CS (vocabularies
-// above CS * 8192 tokens) are streamed in sweep 1 and read again in sweep 2.  The arithmetic is the one of npd_kd_kernels.hip (same helpers, same merge tree).
+// Rows of more than 131,072 entries take a CU's whole register file (1024 threads, 128 VGPRs each); shorter rows run
+// with 512 or 256 threads, so that a thread still owns 10 .. 19 groups while two or four rows are in flight per CU
+// and one row's reductions overlap another row's streaming.
+//
+// Loads are software-pipelined by hand: group it + D is requested before group it is consumed.  The first CS groups
+// per thread are straight-line code (CS is a template parameter), so the compiler can keep several loads in flight;
+// groups beyond CS (longer rows) are streamed in sweep 1 and read again in sweep 2.  The arithmetic is the one of
+// npd_kd_kernels.hip (same helpers, same merge tree).  The same kernel carries the reverse KL (two sweeps) and the
+// skew forms (three sweeps) of the dense-teacher divergences.
 #include "npd_device.hpp"
 #include "npd_internal.hpp"
 
