@@ -253,14 +253,23 @@ __device__ __forceinline__ void block_merge(Lse (&v)[N], float* smem) {
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      // every wave folds the NW partials in the same order: identical totals everywhere
+      // every wave folds the NW partials in the same tree: lane l starts from partial l mod NW, a butterfly over
+      // log2(NW) steps merges them, and lane 0's result (one fixed order of operations) is what every lane keeps --
+      // identical totals everywhere, three LDS reads per lane instead of 3 NW
       Lse t;
-      t.r = smem[(i * 3 + 0) * NW];
-      t.z = smem[(i * 3 + 1) * NW];
-      t.a = smem[(i * 3 + 2) * NW];
+      t.r = smem[(i * 3 + 0) * NW + (lane & (NW - 1))];
+      t.z = smem[(i * 3 + 1) * NW + (lane & (NW - 1))];
+      t.a = smem[(i * 3 + 2) * NW + (lane & (NW - 1))];
 #pragma unroll
-      for (int w = 1; w < NW; ++w) t.merge(smem[(i * 3 + 0) * NW + w], smem[(i * 3 + 1) * NW + w], smem[(i * 3 + 2) * NW + w]);
-      v[i] = t;
+      for (int off = NW / 2; off > 0; off >>= 1) {
+        const float r2 = __shfl_xor(t.r, off, kWave);
+        const float z2 = __shfl_xor(t.z, off, kWave);
+        const float a2 = __shfl_xor(t.a, off, kWave);
+        t.merge(r2, z2, a2);
+      }
+      v[i].r = __shfl(t.r, 0, kWave);
+      v[i].z = __shfl(t.z, 0, kWave);
+      v[i].a = __shfl(t.a, 0, kWave);
     }
     __syncthreads();
   } else {
