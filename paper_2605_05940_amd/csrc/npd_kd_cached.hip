@@ -632,6 +632,9 @@ static hipError_t launch_cached_lse1(const KdArgs& a, hipStream_t stream) {
 #ifndef NPD_CSR
 #define NPD_CSR 12
 #endif
+#ifndef NPD_CSR_FWD
+#define NPD_CSR_FWD 16  // forward KL with 1024 threads: 4.53 ms with 12 resident groups, 4.48 ms with 16 (config 1)
+#endif
 #ifndef NPD_TOPK_CSR
 #define NPD_TOPK_CSR 12
 #endif
@@ -694,7 +697,8 @@ static hipError_t launch_grad_variants(const KdArgs& a, int teacher_kind, hipStr
     return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, false, kSkewKl>(a, stream);
   if (teacher_kind == kDense && a.divergence == kSkewReverseKl)
     return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, false, kSkewReverseKl>(a, stream);
-  if (teacher_kind == kDense) return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, NPD_PERSIST>(a, stream);
+  constexpr int CSRF = NPD_CSR_FWD < CS ? NPD_CSR_FWD : CS;
+  if (teacher_kind == kDense) return launch_cached_lse1<CS, CSRF, 9, NPD_TD, kDense, true, NPD_PERSIST>(a, stream);
   // top-k teacher: only the student row is dense; what does not fit the registers is parked in LDS, so the whole
   // row is on chip for the gradient sweep
   constexpr int TCSR = CS < NPD_TOPK_CSR ? CS : NPD_TOPK_CSR;
