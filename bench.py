@@ -22,7 +22,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 
 # HBM-side bytes per launch of the fused kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
 # counters read for a plain copy of known size (x2.000 and x1.000); summary in profiles/kd_cached_kernel_cfg1_hbm_traffic.md
-MEASURED_TRAFFIC_BYTES = {"cfg1_1b_dense": (16_401_164 + 9_731_131) * 1024}
+MEASURED_TRAFFIC_BYTES = {"cfg1_1b_dense": (14_854_249 + 9_732_739) * 1024}
 
 
 def algorithmic_bytes(w, lay):
