@@ -678,6 +678,24 @@ static RowShape forward_grad_shape(const KdArgs& a, int teacher_kind) {
   return {cb, nit <= 13 ? 13 : (nit <= 16 ? 16 : 19)};
 }
 
+// Forward-only calls (scoring passes, monitors) stream a row once through the same software pipeline, nothing is
+// kept: threads per workgroup by row length.  Measured (32,768 rows, dense forward-only, % of 8 TB/s, 1024 / 512 /
+// 256 threads): V = 32,000: 50 / 75 / 84, 65,536: 79 / 88 / 85, 100,352: 87 / 87 / 85, 128,256: 88 / 87 / 85,
+// 151,936: 87 / 87 / 84, 262,144: 84 / 86 / 81.
+#ifndef NPD_FWD_CB_A
+#define NPD_FWD_CB_A 5120   // up to this many 128-bit groups per row: 256 threads
+#endif
+#ifndef NPD_FWD_CB_B
+#define NPD_FWD_CB_B 13000  // up to this many: 512 threads; beyond: 1024
+#endif
+static int forward_only_threads(const KdArgs& a) {
+  const int nvec = a.nvec_s;
+  if (nvec < 1024) return 0;
+  if (nvec <= NPD_FWD_CB_A) return 256;
+  if (nvec <= NPD_FWD_CB_B) return 512;
+  return 1024;
+}
+
 // Row-resident path: 16-byte aligned rows that are long enough.  (The CE softmax of the composite loss has no
 // temperature; this path covers it at tau = 1, where it shares the student's exponentials.)
 bool cached_path_applies(const KdArgs& a, int teacher_kind, bool want_grad) {
@@ -685,6 +703,7 @@ bool cached_path_applies(const KdArgs& a, int teacher_kind, bool want_grad) {
   if (a.divergence != kForwardKl && !grad) return false;  // the other divergences: gradient runs only
   if (a.cscale != 0.0f && a.need_lse1) return false;
   if (grad && a.divergence == kForwardKl) return forward_grad_shape(a, teacher_kind).cb > 0;
+  if (!grad) return forward_only_threads(a) > 0;
   return unrolled_groups(a, grad) > 0;
 }
 
@@ -723,6 +742,15 @@ static hipError_t launch_short_cs(const KdArgs& a, int cs, int teacher_kind, hip
   return launch_short<19, CB>(a, teacher_kind, stream);
 }
 
+template <int CB>
+static hipError_t launch_forward_only(const KdArgs& a, int teacher_kind, hipStream_t stream) {
+  switch (teacher_kind) {
+    case kDense: return launch_cached_lse1<19, 0, 0, 4, kDense, false, false, kForwardKl, CB, true>(a, stream);
+    case kTopk: return launch_cached_lse1<19, 0, 0, 4, kTopk, false, false, kForwardKl, CB, true>(a, stream);
+    default: return launch_cached_lse1<19, 0, 0, 4, kNone, false, false, kForwardKl, CB, true>(a, stream);
+  }
+}
+
 hipError_t launch_kd_cached(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream) {
   const bool grad = want_grad && teacher_kind != kNone;
   if (grad) {
@@ -735,10 +763,10 @@ hipError_t launch_kd_cached(const KdArgs& a, int teacher_kind, bool want_grad, h
       default: return launch_grad_variants<13>(a, teacher_kind, stream);
     }
   }
-  switch (teacher_kind) {
-    case kDense: return launch_cached_lse1<19, 0, 0, 4, kDense, false, false>(a, stream);
-    case kTopk: return launch_cached_lse1<19, 0, 0, 4, kTopk, false, false>(a, stream);
-    default: return launch_cached_lse1<19, 0, 0, 4, kNone, false, false>(a, stream);
+  switch (forward_only_threads(a)) {
+    case 256: return launch_forward_only<256>(a, teacher_kind, stream);
+    case 512: return launch_forward_only<512>(a, teacher_kind, stream);
+    default: return launch_forward_only<1024>(a, teacher_kind, stream);
   }
 }
 
