@@ -156,8 +156,12 @@ size_t npd_workspace_bytes(const npd_kd_desc* desc);
  *   workspace        device, >= npd_workspace_bytes(desc) bytes, 256-byte aligned (NULL if 0)
  *
  * Each gradient element is rounded to bf16 once (round to nearest even) from an fp32
- * value; all sums are accumulated in fp32.  Results are bitwise reproducible from run
- * to run (no floating-point atomics).
+ * value; all sums are accumulated in fp32.  A call's results are bitwise reproducible from
+ * run to run (no floating-point atomics).  Two different calls on the same data (forward only
+ * vs with gradient, other strides or alignment) may sum a row in another order: their scalar
+ * outputs then agree to fp32 rounding, not bit for bit.  Rows that are 16-byte aligned with
+ * strides that are multiples of 8 elements take the fast kernels; anything else is handled
+ * element-wise, with the same results to rounding.
  */
 npd_status npd_kd_loss_fwd_bwd(const npd_kd_desc* desc, const void* student_logits, const void* teacher_dense,
                                const int32_t* teacher_idx, const float* teacher_val, const int32_t* labels,
