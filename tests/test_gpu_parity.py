@@ -176,7 +176,9 @@ def test_bad_label_sets_status_and_nan(oracle):
     (40000, 1, 1.0, 1.0, False),     # k = 1; 512-thread row-resident shape
     (32000, 64, 2.0, 1.0, True),     # 256-thread workgroups, in place, tau != 1
     (65536, 16, 1.0, 1.0, False),    # 512 threads, 16 groups
-    (90000, 64, 1.0, 1.0, False),    # 1024 threads, 11 groups
+    (90000, 64, 1.0, 1.0, False),    # 512 threads, 22 groups: the last ones streamed twice
+    (151936, 4096, 1.0, 1.0, False), # the largest supported k
+    (20000, 4096, 2.0, 1.0, True),   # the largest k on a 256-thread shape, in place
 ])
 def test_topk_shapes(oracle, V, k, tau, scale, inplace):
     n_rows, row_len = (2, 96) if V > 100000 else (2, 128)
