@@ -43,7 +43,7 @@ def algorithmic_bytes(w, lay):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=1, help="workload index (1 = the 32,768 x 151,936 headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
