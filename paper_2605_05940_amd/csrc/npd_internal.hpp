@@ -48,6 +48,13 @@ hipError_t launch_kd_cached(const KdArgs& a, int teacher_kind, bool want_grad, h
 // compute units of the current device (cached per device)
 int compute_units();
 
+// the instantiations of the row-resident kernel, one translation unit each (npd_kd_cached_*.hip)
+hipError_t launch_cached_forward_1024(const KdArgs& a, int cs, int teacher_kind, hipStream_t stream);
+hipError_t launch_cached_divergence_1024(const KdArgs& a, int cs, hipStream_t stream);
+hipError_t launch_cached_short_512(const KdArgs& a, int cs, int teacher_kind, hipStream_t stream);
+hipError_t launch_cached_short_256(const KdArgs& a, int cs, int teacher_kind, hipStream_t stream);
+hipError_t launch_cached_forward_only(const KdArgs& a, int threads, int teacher_kind, hipStream_t stream);
+
 hipError_t launch_teacher_topk(int64_t T, int32_t V, int64_t stride, int32_t k, int log_probs, const uint16_t* t,
                                const uint8_t* mask, int32_t* idx, float* val, hipStream_t stream);
 
