@@ -51,6 +51,8 @@ int compute_units();
 // the instantiations of the row-resident kernel, one translation unit each (npd_kd_cached_*.hip)
 hipError_t launch_cached_forward_1024(const KdArgs& a, int cs, int teacher_kind, hipStream_t stream);
 hipError_t launch_cached_divergence_1024(const KdArgs& a, int cs, hipStream_t stream);
+hipError_t launch_cached_divergence_512(const KdArgs& a, int cs, hipStream_t stream);
+hipError_t launch_cached_divergence_256(const KdArgs& a, int cs, hipStream_t stream);
 hipError_t launch_cached_short_512(const KdArgs& a, int cs, int teacher_kind, hipStream_t stream);
 hipError_t launch_cached_short_256(const KdArgs& a, int cs, int teacher_kind, hipStream_t stream);
 hipError_t launch_cached_forward_only(const KdArgs& a, int threads, int teacher_kind, hipStream_t stream);

@@ -28,7 +28,7 @@ static int unrolled_groups(const KdArgs& a, bool want_grad) {
   return 0;
 }
 
-// Workgroup size and unrolled length of the forward-KL gradient kernels.  Measured on MI355X (32,768 unmasked rows,
+// Workgroup size and unrolled length of the gradient kernels (measured with the forward KL).  Measured on MI355X (32,768 unmasked rows,
 // % of 8 TB/s, 1024 / 512 / 256 threads per workgroup): dense teacher V = 81,920: 59 / 71 / 64, 100,352: 59 / 69 /
 // 63, 128,256: 64 / 67 / 61, 151,936: 64 / 64 / 57, 200,000: 64 / 63 / 50, 262,144: 58 / 57 / 51; top-k teacher
 // 128,256: 54 / 68 / 61, 151,936: 56 / 62 / 59, 262,144: 54 / 65 / 59.  Two 512-thread workgroups per CU overlap
@@ -75,19 +75,21 @@ bool cached_path_applies(const KdArgs& a, int teacher_kind, bool want_grad) {
   const bool grad = want_grad && teacher_kind != kNone;
   if (a.divergence != kForwardKl && !grad) return false;  // the other divergences: gradient runs only
   if (a.cscale != 0.0f && a.need_lse1) return false;
-  if (grad && a.divergence == kForwardKl) return forward_grad_shape(a, teacher_kind).cb > 0;
-  if (!grad) return forward_only_threads(a) > 0;
-  return unrolled_groups(a, grad) > 0;
+  if (grad) return forward_grad_shape(a, teacher_kind).cb > 0;
+  return forward_only_threads(a) > 0;
 }
 
 hipError_t launch_kd_cached(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream) {
   const bool grad = want_grad && teacher_kind != kNone;
   if (grad) {
-    const RowShape sh = a.divergence == kForwardKl ? forward_grad_shape(a, teacher_kind) : RowShape{kCB, 0};
-    if (sh.cb == 512) return launch_cached_short_512(a, sh.cs, teacher_kind, stream);
-    if (sh.cb == 256) return launch_cached_short_256(a, sh.cs, teacher_kind, stream);
-    // 1024 threads: more than 16 groups per thread, or another divergence
-    if (a.divergence == kForwardKl) return launch_cached_forward_1024(a, unrolled_groups(a, true), teacher_kind, stream);
+    const RowShape sh = forward_grad_shape(a, teacher_kind);  // the same shapes for every divergence
+    if (a.divergence == kForwardKl) {
+      if (sh.cb == 512) return launch_cached_short_512(a, sh.cs, teacher_kind, stream);
+      if (sh.cb == 256) return launch_cached_short_256(a, sh.cs, teacher_kind, stream);
+      return launch_cached_forward_1024(a, unrolled_groups(a, true), teacher_kind, stream);  // 17 or more groups
+    }
+    if (sh.cb == 512) return launch_cached_divergence_512(a, sh.cs, stream);
+    if (sh.cb == 256) return launch_cached_divergence_256(a, sh.cs, stream);
     return launch_cached_divergence_1024(a, unrolled_groups(a, true), stream);
   }
   return launch_cached_forward_only(a, forward_only_threads(a), teacher_kind, stream);

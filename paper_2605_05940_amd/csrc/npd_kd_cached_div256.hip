@@ -1,0 +1,23 @@
+// Row-resident KD kernels for the reverse KL and the skew forms (dense teacher, gradient), 256 threads per workgroup.
+#include "npd_kd_cached.hpp"
+
+namespace npd {
+
+template <int CS>
+static hipError_t launch_divergence(const KdArgs& a, hipStream_t stream) {
+  constexpr int CB = 256;
+  constexpr int CSR = NPD_CSR < CS ? NPD_CSR : CS;
+  if (a.divergence == kReverseKl)
+    return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, false, kReverseKl, CB, true>(a, stream);
+  if (a.divergence == kSkewKl)
+    return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, false, kSkewKl, CB, true>(a, stream);
+  return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, false, kSkewReverseKl, CB, true>(a, stream);
+}
+
+hipError_t launch_cached_divergence_256(const KdArgs& a, int cs, hipStream_t stream) {
+  if (cs == 13) return launch_divergence<13>(a, stream);
+  if (cs == 16) return launch_divergence<16>(a, stream);
+  return launch_divergence<19>(a, stream);
+}
+
+}  // namespace npd
