@@ -220,9 +220,8 @@ __global__ __launch_bounds__(CB, 4) void kd_cached_kernel(const KdArgs a) {
   constexpr bool REV = DIVK == kReverseKl;
   constexpr bool SKEW = DIVK == kSkewKl || DIVK == kSkewReverseKl;  // three sweeps: normalisers, D and ubar, gradient
   static_assert(!SKEW || !PERSIST, "the three-sweep forms are not persistent");
-  // teacher groups parked for sweep 2, [1024][CT]: a thread's CT groups are contiguous, so one base register
-  // plus an immediate offset addresses them all; the 16 * CT byte lane stride (144 B) is conflict-free for
-  // 128-bit LDS accesses
+  // groups parked for sweep 2, [CB][LS]: a thread's groups are contiguous, so one base register plus an immediate
+  // offset addresses them all
   extern __shared__ uint4 lds_t[];
   __shared__ float red[4 * 3 * (CB / kWave)];
   __shared__ uint16_t patch[TEACHER == kTopk && GRAD ? kTopkMax : 1];
@@ -240,12 +239,12 @@ __global__ __launch_bounds__(CB, 4) void kd_cached_kernel(const KdArgs a) {
   const int64_t G = gridDim.x;
   const float c = a.c;
   const bool lse1_t = LSE1 && a.tnll != nullptr;
-  // launched only for rows of more than (CS - 1) * 1024 groups: every one of the first CS groups per
-  // thread is full except, when the row has at most CS * 1024 groups, the last one
+  // without SHORT: launched only for rows of more than (CS - 1) * CB groups, so every one of the first CS groups
+  // per thread is full except, when the row has at most CS * CB groups, the last one
   const int nit = (nvec + CB - 1) / CB;  // 128-bit groups per thread
 
-  // A persistent workgroup owns rows blockIdx.x, blockIdx.x + G, ...; rows that are not scored are dealt
-  // with on the way (scalars 0, gradient row zero-filled, logits never read).
+  // A workgroup owns rows blockIdx.x, blockIdx.x + G, ... (one row each unless PERSIST); rows that are not scored
+  // are dealt with on the way (scalars 0, gradient row zero-filled, logits never read).
   auto next_scored = [&](int64_t r) -> int64_t {
     while (r < T && !a.mask[r]) {
       if (tid == 0) {
