@@ -786,3 +786,68 @@ def test_divergence_composite_gradient_and_bad_label(oracle, div, tau):
     others = lay.loss_mask.astype(bool).copy()
     others[r] = False
     assert np.isfinite(gpu["grad"][others]).all()
+
+
+# --------------------------------------------------------------------------- stream capture
+
+def test_whole_step_replays_from_a_hip_graph(oracle):
+    """The library allocates nothing and never synchronises, so a whole step (fused loss + gradient, top-k record,
+    the per-sample reductions, Delta-IFD) can be captured once and replayed: every replay, on new logits in the same
+    buffers, must reproduce the eager results bit for bit."""
+    w = synth.scaled(synth.config(1), n_rows=2, row_len=96, vocab=50264, length_lo=8, length_hi=48)
+    lay, s, t, mask, labels = _inputs(w)
+    T, V, S, k = w.n_tokens, w.vocab, lay.n_segments, 16
+    cu = torch.from_numpy(lay.cu_seqlens).to(dev())
+    real = np.flatnonzero(~lay.is_pad_segment).astype(np.int32)
+    pc = torch.from_numpy(real[0::2][:len(real) // 2]).to(dev())
+    pu = torch.from_numpy(real[1::2][:len(real) // 2]).to(dev())
+    P = pc.numel()
+
+    def buffers():
+        return dict(g=torch.zeros_like(s), kd=torch.zeros(T, device=dev()), nll=torch.zeros(T, device=dev()),
+                    tnll=torch.zeros(T, device=dev()), idx=torch.zeros((T, k), dtype=torch.int32, device=dev()),
+                    val=torch.zeros((T, k), device=dev()), seg=torch.zeros(S, device=dev()),
+                    cnt=torch.zeros(S, dtype=torch.int32, device=dev()), ms=torch.zeros(S, device=dev()),
+                    mt=torch.zeros(S, device=dev()), delta=torch.zeros(P, device=dev()),
+                    zone=torch.zeros(P, dtype=torch.uint8, device=dev()),
+                    keep_count=torch.zeros(1, dtype=torch.int32, device=dev()),
+                    status=torch.zeros(1, dtype=torch.int32, device=dev()))
+
+    def step(b):
+        binding.npd_kd_loss_fwd_bwd(s, mask, teacher_dense=t, labels=labels, grad_scale=0.9, ce_grad_scale=0.1,
+                                    grad_out=b["g"], kd_tok=b["kd"], nll_tok=b["nll"], teacher_nll_tok=b["tnll"],
+                                    dev_status=b["status"])
+        binding.npd_teacher_topk(t, k, topk_idx=b["idx"], topk_val=b["val"], loss_mask=mask, log_probs=True)
+        binding.npd_segment_reduce(b["kd"], mask, cu, seg_sum=b["seg"], seg_count=b["cnt"])
+        binding.npd_segment_reduce(b["nll"], mask, cu, seg_mean=b["ms"])
+        binding.npd_segment_reduce(b["tnll"], mask, cu, seg_mean=b["mt"])
+        binding.npd_delta_ifd_score(b["ms"], b["mt"], b["cnt"], pc, pu, 0.0, 0.8, delta=b["delta"], zone=b["zone"],
+                                    keep_count=b["keep_count"])
+
+    captured = buffers()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(captured)                                   # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(captured)
+    for trial in range(3):
+        synth.fill_logits(w, s, t, synth.SEED + 100 + trial)   # new logits in the same buffers, eager work in between
+        eager = buffers()
+        step(eager)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name in eager:
+            a, b = eager[name], captured[name]
+            assert torch.equal(a.view(torch.uint8) if a.dtype != torch.bfloat16 else a.view(torch.int16),
+                               b.view(torch.uint8) if b.dtype != torch.bfloat16 else b.view(torch.int16)), \
+                f"replay {trial}: {name} differs from the eager run"
+        assert int(captured["status"].item()) == 0
+    ref = oracle.kd_dense(_bits(s), _bits(t), lay.labels, lay.loss_mask, grad_scale=0.9, ce_grad_scale=0.1)
+    gpu = dict(kd=captured["kd"].cpu().numpy().astype(np.float64), nll_s=captured["nll"].cpu().numpy().astype(np.float64),
+               grad=captured["g"].float().cpu().numpy().astype(np.float64))
+    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle)
