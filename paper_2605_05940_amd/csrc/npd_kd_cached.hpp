@@ -42,6 +42,10 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t row_rsrc(const uint16_t* row, int nvec) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(row), 0, nvec * 16, 0x00020000);
 }
+// persistent workgroups (NPD_PERSIST) also request the next row's resident student groups during the gradient sweep
+#ifndef NPD_PERSIST_PREFETCH
+#define NPD_PERSIST_PREFETCH true
+#endif
 #ifndef NPD_NT_RESIDENT
 #define NPD_NT_RESIDENT 2
 #endif
@@ -272,7 +276,7 @@ __global__ __launch_bounds__(CB, 4) void kd_cached_kernel(const KdArgs a) {
   };
 
   int64_t row = next_scored(blockIdx.x);
-  if (PERSIST && row < T) request_student(row_rsrc(a.s + row * a.s_stride, nvec));
+  if (PERSIST && NPD_PERSIST_PREFETCH && row < T) request_student(row_rsrc(a.s + row * a.s_stride, nvec));
 
   while (row < T) {
     const int64_t nrow = PERSIST ? next_scored(row + G) : T;
@@ -302,7 +306,7 @@ __global__ __launch_bounds__(CB, 4) void kd_cached_kernel(const KdArgs a) {
     // ---- sweep 1, first CS groups per thread: the register-resident student groups are requested first
     // (or already were, during the previous row); the other student groups and the teacher groups are
     // requested D ahead of their use
-    if constexpr (!PERSIST) request_student(rs);
+    if constexpr (!(PERSIST && NPD_PERSIST_PREFETCH)) request_student(rs);
 #pragma unroll
     for (int d = 0; d < D; ++d) {
       if constexpr (TEACHER == kDense) tst[d] = ld_group<GB>(rt, voff, d, SHORT || (d) == CS - 1, GRAD ? d < CT : true);
@@ -508,7 +512,7 @@ __global__ __launch_bounds__(CB, 4) void kd_cached_kernel(const KdArgs a) {
       if ((TEACHER == kTopk && bad_index) || (ce && bad_label)) {  // uniform: the row cannot be differentiated
         const uint16_t qnan = 0x7fc0;
         for (int e = tid; e < V; e += CB) grow[e] = qnan;
-        if constexpr (PERSIST) request_student(rnext);
+        if constexpr (PERSIST && NPD_PERSIST_PREFETCH) request_student(rnext);
       } else {
         // sub-group tail and streamed part first (read most recently), then the first CS groups backwards
         for (int e = nvec * 8 + tid; e < V; e += CB) {
@@ -556,7 +560,7 @@ __global__ __launch_bounds__(CB, 4) void kd_cached_kernel(const KdArgs a) {
               const uint4 gq = grad8<TEACHER, true, DIVK>(vs, vt, k);
               if ((!SHORT && it < CS - 1) || it * CB + tid < nvec) st16_stream(grow, it * CB + tid, gq);
             }
-            if (PERSIST && it < CSR) sreg[it < CSR ? it : 0] = ld_group<GB>(rnext, voff, it, SHORT || (it) == CS - 1);
+            if (PERSIST && NPD_PERSIST_PREFETCH && it < CSR) sreg[it < CSR ? it : 0] = ld_group<GB>(rnext, voff, it, SHORT || (it) == CS - 1);
             __builtin_amdgcn_sched_barrier(0);
           }
         } else {
@@ -568,7 +572,7 @@ __global__ __launch_bounds__(CB, 4) void kd_cached_kernel(const KdArgs a) {
               st16_stream(grow, i, grad8<TEACHER, false, DIVK>(vs, vt, k));
             }
           }
-          if constexpr (PERSIST) request_student(rnext);
+          if constexpr (PERSIST && NPD_PERSIST_PREFETCH) request_student(rnext);
         }
         if (TEACHER == kTopk || ce) {  // uniform
           // the k support positions and the label position get their final values once the dense stores of the
