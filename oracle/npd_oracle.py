@@ -23,7 +23,8 @@ def lib():
     """Load (building first if missing or stale) the oracle library."""
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        # NPD_ORACLE_LIB: a differently built oracle (the pin tests run against copies with planted mistakes)
+        path = os.environ.get("NPD_ORACLE_LIB") or _build.build(force=False)
         L = ctypes.CDLL(path)
         L.npd_oracle_threads.restype = ctypes.c_int
         L.npd_oracle_kd_dense_f64.restype = None
