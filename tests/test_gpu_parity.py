@@ -851,3 +851,35 @@ def test_whole_step_replays_from_a_hip_graph(oracle):
     gpu = dict(kd=captured["kd"].cpu().numpy().astype(np.float64), nll_s=captured["nll"].cpu().numpy().astype(np.float64),
                grad=captured["g"].float().cpu().numpy().astype(np.float64))
     compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle)
+
+
+# --------------------------------------------------------------------------- shape-selection boundaries
+
+@pytest.mark.parametrize("V", [
+    8 * 1024, 8 * 1025,                 # first row-resident shape (256 threads, 4 groups) and one vector more
+    8 * 13 * 256, 8 * 13 * 256 + 8,     # 13 full groups at 256 threads | a 14th group with one vector
+    8 * 16 * 256 + 16, 8 * 19 * 256,    # 16 -> 19 unrolled groups | exactly 19
+    8 * 5119, 8 * 5120, 8 * 5121,       # 256 -> 512 threads
+    8 * 19 * 512, 8 * 19 * 512 + 8,     # exactly 19 groups at 512 threads | one streamed vector beyond
+    8 * 13000, 8 * 13001,               # forward-only: 512 -> 1024 threads
+    8 * 16384 + 8,                      # 512 -> 1024 threads with gradient (17 groups: 16 unrolled + streamed)
+    8 * 18 * 1024 + 24,                 # 19 unrolled groups of 1024 threads, the last one nearly empty
+    8 * 19 * 1024 + 8 + 3,              # one streamed vector and a 3-element tail beyond 19 groups
+])
+def test_shape_selection_boundaries(oracle, V):
+    w = synth.scaled(synth.config(1), n_rows=1, row_len=20, vocab=V, length_lo=4, length_hi=10)
+    _say(f"boundary V={V}")
+    lay, s, t, mask, labels = _inputs(w, V + (8 - V % 8) % 8)
+    ref = oracle.kd_dense(_bits(s.contiguous()), _bits(t.contiguous()), lay.labels, lay.loss_mask)
+    gpu = run_gpu_kd(s, mask, t=t, labels=labels)
+    assert gpu["status"] == 0
+    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle)
+    fwd = run_gpu_kd(s, mask, t=t, labels=labels, want_grad=False)
+    compare_kd(fwd, dict(kd=ref["kd"], nll_s=ref["nll_s"], nll_t=ref["nll_t"], lse_s=ref["lse_s"]), lay.loss_mask,
+               lay.cu_seqlens, oracle)
+    idx, val = _topk_gpu(t, 8, mask, True)
+    rk = oracle.teacher_topk(_bits(t.contiguous()), 8, lay.loss_mask, True)
+    np.testing.assert_array_equal(idx.cpu().numpy(), rk["idx"])
+    tk = run_gpu_kd(s, mask, idx=idx.contiguous(), val=val.contiguous(), labels=labels, tau=2.0)
+    rt = oracle.kd_topk(_bits(s.contiguous()), rk["idx"], rk["val"], lay.labels, lay.loss_mask, tau=2.0)
+    compare_kd(tk, rt, lay.loss_mask, lay.cu_seqlens, oracle, tau=2.0)
