@@ -883,3 +883,28 @@ def test_shape_selection_boundaries(oracle, V):
     tk = run_gpu_kd(s, mask, idx=idx.contiguous(), val=val.contiguous(), labels=labels, tau=2.0)
     rt = oracle.kd_topk(_bits(s.contiguous()), rk["idx"], rk["val"], lay.labels, lay.loss_mask, tau=2.0)
     compare_kd(tk, rt, lay.loss_mask, lay.cu_seqlens, oracle, tau=2.0)
+
+
+# --------------------------------------------------------------------------- non-finite inputs stay in their row
+
+@pytest.mark.parametrize("V", [5003, 50264, 151936])
+def test_non_finite_logits_poison_only_their_own_row(V):
+    """Inputs are required to be finite; if they are not, the damage must stay in the offending position: every
+    other row's outputs are bit-identical to a run on clean inputs."""
+    w = synth.scaled(synth.config(1), n_rows=1, row_len=24, vocab=V, length_lo=4, length_hi=12)
+    lay, s, t, mask, labels = _inputs(w)
+    clean = run_gpu_kd(s, mask, t=t, labels=labels)
+    scored = np.flatnonzero(lay.loss_mask)
+    r_nan, r_inf = int(scored[1]), int(scored[3])
+    s2, t2 = s.clone(), t.clone()
+    s2[r_nan, V // 2] = float("nan")
+    t2[r_inf, 17] = float("inf")
+    dirty = run_gpu_kd(s2, mask, t=t2, labels=labels)
+    others = np.ones(w.n_tokens, bool)
+    others[[r_nan, r_inf]] = False
+    for key in ("kd", "nll_s", "nll_t", "lse_s"):
+        np.testing.assert_array_equal(dirty[key][others], clean[key][others])
+    np.testing.assert_array_equal(dirty["grad_bits"][others], clean["grad_bits"][others])
+    assert np.isnan(dirty["kd"][r_nan]) and np.isnan(dirty["nll_s"][r_nan]) and np.isnan(dirty["grad"][r_nan]).all()
+    assert not np.isfinite(dirty["kd"][r_inf])
+    assert dirty["status"] == 0          # not a bookkeeping error: nothing is flagged
