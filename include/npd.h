@@ -138,6 +138,12 @@ size_t npd_workspace_bytes(const npd_kd_desc* desc);
  * At positions with loss_mask[p] == 0 the scalar outputs are 0 and the gradient row is
  * zero-filled (its logits are not read).  No tau^2 factor is applied.
  *
+ * Logits are expected to be finite, with one exception: -inf marks a vocabulary entry of probability 0
+ * (vocabulary padding, a banned token).  In the teacher (dense logits or a top-k value) such an entry
+ * contributes nothing to kd_tok and the gradient there is the student term alone; in the student its
+ * gradient is 0 where the teacher agrees, and kd_tok is +inf where the teacher does not.  NaN or +inf
+ * make the outputs of their own position non-finite and touch no other position.
+ *
  *   student_logits   bf16 [T, student_stride], required
  *   teacher_dense    bf16 [T, teacher_stride]; required iff teacher_kind == DENSE, else NULL
  *   teacher_idx      int32 [T, k], unique per row, in [0, V); required iff TOPK, else NULL

@@ -57,15 +57,17 @@ __device__ __forceinline__ float max8(const float x[8]) {
 // Partial log-sum-exp with an optional cross term.
 struct Lse {
   float r, z, a;
-  __device__ __forceinline__ void init() { r = -INFINITY; z = 0.0f; a = 0.0f; }
-  // raise the reference to `u` if it lags by more than the slack (also the first touch: r = -inf).
+  // the reference starts far below every finite logit but finite, so that a first element of -inf (a masked
+  // vocabulary entry) gives 2^(-inf - r) = 0 rather than 2^(-inf + inf)
+  __device__ __forceinline__ void init() { r = -1.0e30f; z = 0.0f; a = 0.0f; }
+  // raise the reference to `u` if it lags by more than the slack (also the first touch).
   // The outer test is wave-uniform, so the common case is one compare and a scalar branch not taken.
   __device__ __forceinline__ void raise(float u) {
     const bool lag = u > r + kRefSlack;
     if (__builtin_amdgcn_ballot_w64(lag) != 0) {
       asm volatile("");  // not speculatable: keeps this rare path behind a real branch
       if (lag) {
-        const float f = exp2_fast(r - u);  // r = -inf gives 0
+        const float f = exp2_fast(r - u);  // the initial reference gives 0
         z *= f;
         a *= f;
         r = u;
@@ -77,14 +79,15 @@ struct Lse {
 #pragma unroll
     for (int i = 0; i < 8; ++i) z += exp2_fast(__builtin_fmaf(x[i], c, -r));
   }
-  // also accumulates a += 2^(x*c - r) * (x - y)
+  // also accumulates a += 2^(x*c - r) * (x - y).  The difference is kept above -FLT_MAX: a logit of -inf on the
+  // x side (a masked vocabulary entry: probability 0) then contributes 0 * finite = 0 rather than 0 * -inf.
   __device__ __forceinline__ void add8_cross(const float x[8], const float y[8], float c) {
     raise(max8(x) * c);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const float e = exp2_fast(__builtin_fmaf(x[i], c, -r));
       z += e;
-      a = __builtin_fmaf(e, x[i] - y[i], a);
+      a = __builtin_fmaf(e, __builtin_fmaxf(x[i] - y[i], -3.4028234663852886e38f), a);
     }
   }
   __device__ __forceinline__ void add1(float x, float c) {
@@ -95,7 +98,7 @@ struct Lse {
     raise(x * c);
     const float e = exp2_fast(__builtin_fmaf(x, c, -r));
     z += e;
-    a = __builtin_fmaf(e, d, a);
+    a = __builtin_fmaf(e, __builtin_fmaxf(d, -3.4028234663852886e38f), a);
   }
   // merge another partial into this one (same code for every stream, so that two streams fed
   // identical data stay bitwise identical)

@@ -477,7 +477,7 @@ __global__ __launch_bounds__(CB, 4) void kd_cached_kernel(const KdArgs a) {
           const float sj = bf16_one(srow[irow[j]]);
           const float lpt = b - Lt;
           const float lps = __builtin_fmaf(sj, c, -Ls);
-          part = __builtin_fmaf(exp2_fast(lpt), (lpt - lps) * kLn2, part);
+          part = __builtin_fmaf(exp2_fast(lpt), __builtin_fmaxf(lpt - lps, -3.4028234663852886e38f) * kLn2, part);  // a -inf entry: 0
           if constexpr (GRAD) {
             float gj = grad_pair_elem(sj, b, k.p);
             if (ce && irow[j] == y) {

@@ -130,7 +130,7 @@ __global__ __launch_bounds__(BLOCK) void kd_rows_kernel(const KdArgs a) {
         const float sj = bf16_one(srow[irow[j]]);
         const float lpt = b - Lt;                         // log2 p_T
         const float lps = __builtin_fmaf(sj, c, -Ls);     // log2 p_S
-        part = __builtin_fmaf(exp2_fast(lpt), (lpt - lps) * kLn2, part);
+        part = __builtin_fmaf(exp2_fast(lpt), __builtin_fmaxf(lpt - lps, -3.4028234663852886e38f) * kLn2, part);  // a -inf entry: 0
         if constexpr (GRAD) {
           // the value this position finally holds, from fp32, rounded once
           float gj = grad_pair_elem(sj, b, gk);

@@ -908,3 +908,37 @@ def test_non_finite_logits_poison_only_their_own_row(V):
     assert np.isnan(dirty["kd"][r_nan]) and np.isnan(dirty["nll_s"][r_nan]) and np.isnan(dirty["grad"][r_nan]).all()
     assert not np.isfinite(dirty["kd"][r_inf])
     assert dirty["status"] == 0          # not a bookkeeping error: nothing is flagged
+
+
+@pytest.mark.parametrize("V", [5003, 50264, 151936])
+def test_minus_infinity_marks_a_masked_vocabulary_entry(oracle, V):
+    """A logit of -inf is a vocabulary entry of probability 0 (vocabulary padding, banned tokens).  In the teacher it
+    contributes nothing to Eq. 2 and the gradient there is p_S; where the student is -inf too, the gradient is 0."""
+    w = synth.scaled(synth.config(1), n_rows=1, row_len=24, vocab=V, length_lo=4, length_hi=12)
+    lay, s, t, mask, labels = _inputs(w)
+    t[:, V - 70:] = float("-inf")                 # padded tail of the teacher's vocabulary
+    t[3, 100:200] = float("-inf")
+    s[:, V - 6:] = float("-inf")                  # the last entries are masked in both
+    labels = torch.clamp(labels, max=V - 100)     # labels stay on real entries
+    lab = labels.cpu().numpy()
+    ref = oracle.kd_dense(_bits(s), _bits(t), lab, lay.loss_mask)
+    assert np.isfinite(ref["kd"]).all() and np.isfinite(ref["grad"]).all()
+    gpu = run_gpu_kd(s, mask, t=t, labels=labels)
+    assert gpu["status"] == 0
+    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle)
+    m = lay.loss_mask.astype(bool)
+    assert (gpu["grad"][m][:, V - 6:] == 0).all()
+    # top-k record of such a teacher, then the top-k loss against it
+    idx, val = _topk_gpu(t, 16, mask, True)
+    rk = oracle.teacher_topk(_bits(t), 16, lay.loss_mask, True)
+    np.testing.assert_array_equal(idx.cpu().numpy(), rk["idx"])
+    tk = run_gpu_kd(s, mask, idx=idx.contiguous(), val=val.contiguous(), labels=labels)
+    rt = oracle.kd_topk(_bits(s), rk["idx"], rk["val"], lab, lay.loss_mask)
+    compare_kd(tk, rt, lay.loss_mask, lay.cu_seqlens, oracle)
+    # a stored top-k value of -inf is an entry of probability 0 as well
+    val2 = val.clone()
+    val2[:, -1] = float("-inf")
+    tk2 = run_gpu_kd(s, mask, idx=idx.contiguous(), val=val2.contiguous(), labels=labels)
+    rt2 = oracle.kd_topk(_bits(s), rk["idx"], val2.cpu().numpy(), lab, lay.loss_mask)
+    assert np.isfinite(rt2["kd"]).all()
+    compare_kd(tk2, rt2, lay.loss_mask, lay.cu_seqlens, oracle)
