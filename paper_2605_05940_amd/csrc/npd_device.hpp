@@ -177,11 +177,11 @@ __device__ __forceinline__ float skew_elem(float lps, float lpt, float alpha, fl
   float u;
   if constexpr (DIV == kDivSkewKl) {
     const float m = __builtin_fmaxf(__builtin_fmaf(alpha, pt, (1.0f - alpha) * ps), kTiny);
-    dsum = __builtin_fmaf(pt, (lpt - __log2f(m)) * kLn2, dsum);
+    dsum = __builtin_fmaf(pt, __builtin_fmaxf(lpt - __log2f(m), -3.0e38f) * kLn2, dsum);  // p_T = 0: no term
     u = (alpha - 1.0f) * pt * __builtin_amdgcn_rcpf(m);
   } else {
     const float m = __builtin_fmaxf(__builtin_fmaf(1.0f - alpha, pt, alpha * ps), kTiny);
-    const float l = (lps - __log2f(m)) * kLn2;
+    const float l = __builtin_fmaxf(lps - __log2f(m), -3.0e38f) * kLn2;  // p_S = 0: no term, no gradient
     u = __builtin_fmaf(-alpha * ps, __builtin_amdgcn_rcpf(m), l + 1.0f);
     dsum = __builtin_fmaf(ps, l, dsum);
   }

@@ -935,6 +935,12 @@ def test_minus_infinity_marks_a_masked_vocabulary_entry(oracle, V):
     tk = run_gpu_kd(s, mask, idx=idx.contiguous(), val=val.contiguous(), labels=labels)
     rt = oracle.kd_topk(_bits(s), rk["idx"], rk["val"], lab, lay.loss_mask)
     compare_kd(tk, rt, lay.loss_mask, lay.cu_seqlens, oracle)
+    # the skew forms: p_T = 0 terms vanish there too (the reverse forms are +inf by definition where p_T = 0 < p_S)
+    for div in ("skew", "skew_reverse"):
+        rd = oracle.div_dense(_bits(s), _bits(t), div, 0.1, mask=lay.loss_mask)
+        assert np.isfinite(rd["kd"]).all() and np.isfinite(rd["grad"]).all()
+        gd = run_gpu_kd(s, mask, t=t, divergence=DIVS[div], skew_alpha=0.1)
+        compare_kd(gd, rd, lay.loss_mask, lay.cu_seqlens, oracle, amp_from_ref=True)
     # a stored top-k value of -inf is an entry of probability 0 as well
     val2 = val.clone()
     val2[:, -1] = float("-inf")
