@@ -1,20 +1,22 @@
 // Row-resident KD kernels: which shape runs a call (threads per workgroup, unrolled length), and the dispatch to the
 // translation units that hold the instantiations.
+#include <atomic>
+
 #include "npd_kd_cached.hpp"
 
 namespace npd {
 
 // compute units of the current device (queried once per device, no allocation)
 int compute_units() {
-  static int cached[64] = {0};
+  static std::atomic<int> cached[64];  // zero-initialised; callers on several host threads may race to fill a slot
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-  if (cached[dev] == 0) {
-    int n = 0;
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
     if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-    cached[dev] = n;
+    cached[dev].store(n, std::memory_order_relaxed);
   }
-  return cached[dev];
+  return n;
 }
 
 // Groups per thread that the unrolled part of the kernel covers.  19 fits vocabularies of 147,464 .. 155,648
