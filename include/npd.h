@@ -16,7 +16,8 @@
  *   - The return value is an npd_status.  On any status other than NPD_OK nothing has
  *     been enqueued and no output was touched.  Argument checks run before any HIP
  *     call, so they work on a machine without a GPU.
- *   - bf16 = upper 16 bits of an IEEE binary32.  Logits must be finite.
+ *   - bf16 = upper 16 bits of an IEEE binary32.  Logits must be finite (-inf is allowed as the
+ *     mark of a vocabulary entry of probability 0: see npd_kd_loss_fwd_bwd).
  *   - Packed layout: the batch is flattened to T positions.  Position p is scored iff
  *     loss_mask[p] != 0.  labels[p] is the token position p predicts (already
  *     shifted).  Sample i owns positions [cu_seqlens[i], cu_seqlens[i+1]).
@@ -85,9 +86,13 @@ enum {
 /* npd_delta_ifd_score flags */
 enum { NPD_IFD_REQUIRE_TEACHER_LE_1 = 1u };
 
+/* Largest vocabulary and number of positions one call takes (beyond: NPD_ERR_UNSUPPORTED). */
+#define NPD_MAX_VOCAB (1 << 26)
+#define NPD_MAX_TOKENS 0x7fffffffLL
+
 typedef struct {
-  int64_t n_tokens;       /* T > 0: flattened positions of the packed batch                        */
-  int32_t vocab;          /* V > 0                                                                 */
+  int64_t n_tokens;       /* T in [1, NPD_MAX_TOKENS]: flattened positions of the packed batch     */
+  int32_t vocab;          /* V in [1, NPD_MAX_VOCAB]                                               */
   int32_t teacher_kind;   /* NPD_TEACHER_*                                                         */
   int64_t student_stride; /* elements between consecutive rows of student_logits (>= V); grad_out
                              uses the same stride                                                  */
@@ -189,7 +194,8 @@ enum { NPD_TOPK_LOG_PROBS = 1u /* values = log-softmax of the k selected logits 
  *   positions with loss_mask[p] == 0 get ids 0..k-1 and values 0 (their logits are not read)
  *
  *   teacher_logits bf16 [T, teacher_stride] (finite), loss_mask uint8 [T] or NULL (all scored),
- *   topk_idx int32 [T, k], topk_val fp32 [T, k].  1 <= k <= min(V, 4096) (larger k: NPD_ERR_UNSUPPORTED).
+ *   topk_idx int32 [T, k], topk_val fp32 [T, k].  1 <= k <= min(V, 4096) (larger k: NPD_ERR_UNSUPPORTED);
+ *   T and V within NPD_MAX_TOKENS and NPD_MAX_VOCAB.
  */
 npd_status npd_teacher_topk(int64_t n_tokens, int32_t vocab, int64_t teacher_stride, int32_t k, uint32_t flags,
                             const void* teacher_logits, const uint8_t* loss_mask, int32_t* topk_idx,

@@ -23,6 +23,9 @@ size_t rows_bytes(int64_t T, int64_t stride, int64_t width, size_t elem) {
   return (size_t)(((T - 1) * stride + width) * (int64_t)elem);
 }
 
+// a row stride the byte extent of [T, stride] bf16 / fp32 arrays can be computed with in 64 bits
+bool stride_fits(int64_t T, int64_t stride) { return stride <= (INT64_MAX / 8) / T; }
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 npd_status check_desc(const npd_kd_desc* d) {
@@ -33,6 +36,10 @@ npd_status check_desc(const npd_kd_desc* d) {
     return NPD_ERR_VALUE;
   if (d->student_stride < d->vocab) return NPD_ERR_SHAPE;
   if (d->teacher_kind == NPD_TEACHER_DENSE_BF16 && d->teacher_stride < d->vocab) return NPD_ERR_SHAPE;
+  if (d->n_tokens > NPD_MAX_TOKENS) return NPD_ERR_UNSUPPORTED;  // one workgroup per position, 1-D grid
+  if (d->vocab > NPD_MAX_VOCAB) return NPD_ERR_UNSUPPORTED;    // in-row offsets are 32-bit
+  if (!stride_fits(d->n_tokens, d->student_stride)) return NPD_ERR_SHAPE;
+  if (d->teacher_kind == NPD_TEACHER_DENSE_BF16 && !stride_fits(d->n_tokens, d->teacher_stride)) return NPD_ERR_SHAPE;
   if (d->teacher_kind == NPD_TEACHER_TOPK && (d->topk < 1 || d->topk > d->vocab)) return NPD_ERR_SHAPE;
   if (!(d->tau > 0.0f) || !isfinite(d->tau)) return NPD_ERR_VALUE;
   if (!isfinite(d->grad_scale) || !isfinite(d->ce_grad_scale)) return NPD_ERR_VALUE;
@@ -46,7 +53,6 @@ npd_status check_desc(const npd_kd_desc* d) {
     return NPD_ERR_VALUE;
   if (d->divergence != NPD_DIV_FORWARD_KL && d->teacher_kind != NPD_TEACHER_DENSE_BF16)
     return NPD_ERR_UNSUPPORTED;  // off the top-k support p_T is 0: the other divergences need the full row
-  if (d->n_tokens > 0x7fffffffLL) return NPD_ERR_UNSUPPORTED;  // one workgroup per position, 1-D grid
   if (d->teacher_kind == NPD_TEACHER_TOPK && d->topk > npd::kTopkMax) return NPD_ERR_UNSUPPORTED;
   return NPD_OK;
 }
@@ -166,7 +172,8 @@ npd_status npd_teacher_topk(int64_t n_tokens, int32_t vocab, int64_t teacher_str
   if (n_tokens <= 0 || vocab <= 0 || teacher_stride < vocab || k < 1 || k > vocab) return NPD_ERR_SHAPE;
   if (flags & ~(uint32_t)NPD_TOPK_LOG_PROBS) return NPD_ERR_VALUE;
   if (!teacher_logits || !topk_idx || !topk_val) return NPD_ERR_NULL;
-  if (k > npd::kTopkMax || n_tokens > 0x7fffffffLL) return NPD_ERR_UNSUPPORTED;
+  if (k > npd::kTopkMax || n_tokens > NPD_MAX_TOKENS || vocab > NPD_MAX_VOCAB) return NPD_ERR_UNSUPPORTED;
+  if (!stride_fits(n_tokens, teacher_stride)) return NPD_ERR_SHAPE;
   const hipError_t e = npd::launch_teacher_topk(n_tokens, vocab, teacher_stride, k, (flags & NPD_TOPK_LOG_PROBS) != 0,
                                                 static_cast<const uint16_t*>(teacher_logits), loss_mask, topk_idx,
                                                 topk_val, static_cast<hipStream_t>(stream));

@@ -31,6 +31,21 @@ def test_exports_match_header(lib):
     assert lib.npd_status_string(0) == b"ok"
 
 
+def test_header_is_plain_c_and_its_layout_is_what_the_binding_assumes(tmp_path):
+    """include/npd.h compiles as C99 and as C++ without warnings; struct size and limits as the binding has them."""
+    import subprocess
+    src = tmp_path / "use_npd.c"
+    src.write_text('#include "npd.h"\n'
+                   "typedef char desc_is_64_bytes[sizeof(npd_kd_desc) == 64 ? 1 : -1];\n"
+                   "typedef char limits[(NPD_MAX_VOCAB == 67108864 && NPD_MAX_TOKENS == 2147483647LL) ? 1 : -1];\n"
+                   "int use(void) { return (int)NPD_DIV_SKEW_REVERSE_KL + (int)NPD_ZONE_INVALID + npd_version(); }\n")
+    inc = os.path.join(ROOT, "include")
+    for cc, std in (("gcc", "-std=c99"), ("g++", "-std=c++11")):
+        lang = ["-x", "c++"] if cc == "g++" else []
+        subprocess.run([cc, std, "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc, *lang,
+                        str(src)], check=True)
+
+
 def test_desc_layout_matches_header():
     # n_tokens i64, vocab i32, teacher_kind i32, student_stride i64, teacher_stride i64, topk i32, flags u32,
     # tau f32, grad_scale f32, ce_grad_scale f32, divergence i32, skew_alpha f32 (+ tail padding)
@@ -108,6 +123,12 @@ def test_kd_argument_validation(lib):
     assert _kd(lib, _desc(**nt), teacher=None) == E_VALUE           # gradient without a teacher
     assert _kd(lib, _desc(flags=1, **nt), teacher=None, grad=None, kd=FAKE + 0x700000) == E_VALUE
     assert lib.npd_workspace_bytes(ctypes.byref(_desc())) == 0
+    # limits of one call: positions, vocabulary, and strides whose byte extents would not fit 64 bits
+    assert _kd(lib, _desc(n_tokens=2**31)) == E_UNSUP
+    huge = (1 << 26) + 8
+    assert _kd(lib, _desc(vocab=huge, student_stride=huge, teacher_stride=huge)) == E_UNSUP
+    assert _kd(lib, _desc(student_stride=2**61)) == E_SHAPE
+    assert _kd(lib, _desc(teacher_stride=2**61)) == E_SHAPE
 
 
 def test_segment_and_ifd_argument_validation(lib):
@@ -133,6 +154,8 @@ def test_teacher_topk_argument_validation(lib):
         args.update(kw)
         return lib.npd_teacher_topk(*[args[n] for n in names])
     assert call(T=0) == E_SHAPE and call(V=0) == E_SHAPE and call(stride=63) == E_SHAPE
+    assert call(T=2**31) == E_UNSUP and call(V=(1 << 26) + 8, stride=(1 << 26) + 8) == E_UNSUP
+    assert call(stride=2**61) == E_SHAPE
     assert call(k=0) == E_SHAPE and call(k=65) == E_SHAPE
     assert call(flags=2) == E_VALUE
     assert call(t=None) == E_NULL and call(idx=None) == E_NULL and call(val=None) == E_NULL
