@@ -732,9 +732,10 @@ DIVS = {"reverse": binding.NPD_DIV_REVERSE_KL, "skew": binding.NPD_DIV_SKEW_KL,
     (50264, 50272, 1.0, 0.1, 0.5, True),       # ragged last group, padded stride, in place
     (151936, 151936, 1.0, 0.1, 1.0, False),    # the headline vocabulary
     (151936, 151936, 3.0, 0.9, -2.0, True),
+    (600000, 600000, 1.0, 0.3, 1.0, False),    # 74 groups per thread: most of the row streamed in every sweep
 ])
 def test_divergence_shapes(oracle, div, V, stride, tau, alpha, scale, inplace):
-    T = 24 if V > 100000 else 64
+    T = (12 if V > 500000 else 24) if V > 100000 else 64
     w = synth.scaled(synth.config(1), n_rows=1, row_len=T, vocab=V, length_lo=4, length_hi=16)
     _say(f"divergence {div} V={V} stride={stride} tau={tau} alpha={alpha} scale={scale} inplace={inplace}")
     lay, s, t, mask, labels = _inputs(w, stride)
@@ -865,6 +866,7 @@ def test_whole_step_replays_from_a_hip_graph(oracle):
     8 * 16384 + 8,                      # 512 -> 1024 threads with gradient (17 groups: 16 unrolled + streamed)
     8 * 18 * 1024 + 24,                 # 19 unrolled groups of 1024 threads, the last one nearly empty
     8 * 19 * 1024 + 8 + 3,              # one streamed vector and a 3-element tail beyond 19 groups
+    1 << 20, 1000003,                   # rows of a million entries: 109 of 128 groups per thread streamed twice
 ])
 def test_shape_selection_boundaries(oracle, V):
     w = synth.scaled(synth.config(1), n_rows=1, row_len=20, vocab=V, length_lo=4, length_hi=10)
