@@ -50,7 +50,9 @@ def main():
     ap.add_argument("--divergence", choices=("forward", "reverse", "skew", "skew_reverse"), default="forward",
                     help="divergence of the dense-teacher configurations (forward = Eq. 2, the headline)")
     ap.add_argument("--skew-alpha", type=float, default=0.1)
-    ap.add_argument("--op", choices=("kd", "teacher_topk"), default="kd")
+    ap.add_argument("--op", choices=("kd", "teacher_topk", "membench"), default="kd",
+                    help="kd: the fused loss step (default); teacher_topk: the teacher-side top-k record; membench: "
+                         "arithmetic-free streaming kernels over arrays of the workload's size (practical ceilings)")
     ap.add_argument("--topk", type=int, default=64, help="k of --op teacher_topk")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run a plain 2 GiB device-to-device copy (untimed), so that a rocprofv3 --pmc "
@@ -67,6 +69,8 @@ def main():
     torch.cuda.set_device(dev)
     if args.op == "teacher_topk":
         return bench_teacher_topk(args, binding, synth, dev)
+    if args.op == "membench":
+        return bench_memory_system(args, synth, dev)
     w = synth.config(args.config)
     lay = synth.make_layout(w)
     T, V, S = w.n_tokens, w.vocab, lay.n_segments
@@ -180,7 +184,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": "npd::kd_cached_kernel (fused KD loss + gradient)" if div_code == 0 else
-                               f"npd::div_rows_kernel ({args.divergence} divergence + gradient)",
+                               f"npd::kd_cached_kernel ({args.divergence} divergence + gradient)",
                      "kernel_ms": kernel_ms,
                      "kernel_ms_median": float(np.median(kernel_all)), "kernel_ms_min": float(kernel_all.min()),
                      "algorithmic_bytes_per_launch": alg_bytes,
@@ -194,6 +198,65 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, lay, s if pristine is None else pristine, t, idx, val)
     print(json.dumps(out))
+
+
+def bench_memory_system(args, synth, dev):
+    """What the memory system gives each access mix of the KD kernels: arithmetic-free row-streaming kernels
+    (``paper_2605_05940_amd/membench``) over three arrays the size of the workload's logits, every workgroup size
+    with and without the non-temporal hint, plus the runtime's own fill and copy.  Context for `roofline.frac`."""
+    from paper_2605_05940_amd import membench
+    membench.load()
+    w = synth.config(args.config)
+    rows, groups = w.n_tokens, w.vocab // 8
+    nbytes = rows * groups * 16
+    a, b, o = (torch.empty(nbytes, dtype=torch.uint8, device=dev) for _ in range(3))
+    a.fill_(1), b.fill_(2), o.zero_()
+
+    def rate(fn, moved):
+        for _ in range(max(1, min(args.warmup, 3))):
+            fn()
+        times = []
+        for _ in range(args.steps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            times.append((e0, e1))
+        torch.cuda.synchronize()
+        ms = float(np.mean([x.elapsed_time(y) for x, y in times]))
+        return moved * nbytes / (ms * 1e-3) / 1e9
+
+    patterns = {}
+    for order in membench.ORDERS:
+        for name in membench.PATTERNS:
+            if name == "row_read_2_then_write_1" and order != "rows":
+                continue
+            moved = sum(membench.MOVES[name])
+            variants = {}
+            for threads in (256, 512, 1024):
+                if name == "row_read_2_then_write_1" and groups > membench.ROW_GROUPS_PER_THREAD * threads:
+                    continue           # the row does not fit this workgroup's registers
+                for nt in (False, True):
+                    key = f"{threads}{'_nt' if nt else ''}"
+                    variants[key] = rate(lambda: membench.run(name, threads, nt, a, b, o, rows, groups, order=order),
+                                         moved)
+            if not variants:
+                continue
+            best = max(variants, key=variants.get)
+            patterns[f"{name}/{order}"] = {"best_gbs": variants[best], "best_variant": best,
+                                           "frac_of_peak": variants[best] / HBM_PEAK_GBS, "variants_gbs": variants}
+    runtime = {"fill_gbs": rate(lambda: o.zero_(), 1), "copy_gbs": rate(lambda: o.copy_(a), 2)}
+    print(json.dumps({
+        "metric": "memory_system_stream_rate_2_reads_1_write",
+        "value": max(patterns[p]["best_gbs"] for p in ("read_2_write_1/rows", "row_read_2_then_write_1/rows")
+                     if p in patterns),
+        "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True,
+        "data": "synthetic", "dtype": "u8",
+        "config": {"workload": f"three arrays of {rows} rows x {groups * 16} bytes ({w.name}'s logit tensors), 128-bit "
+                               f"accesses; order rows = one workgroup per row (4 requests in flight per thread), "
+                               f"address = one short-lived workgroup per consecutive run of groups; value = best "
+                               f"2-reads-1-write rate in row order (the order a row-reduction kernel can produce)"},
+        "peak_gbs": HBM_PEAK_GBS, "patterns": patterns, "runtime": runtime}))
 
 
 def bench_teacher_topk(args, binding, synth, dev):

@@ -1,0 +1,57 @@
+"""The arithmetic-free streaming kernels behind ``bench.py --op membench`` (a measurement aid, not the loss path):
+the library loads and rejects bad arguments on the host; on the GPU every pattern moves exactly what it says."""
+import ctypes
+
+import pytest
+import torch
+
+from paper_2605_05940_amd import membench
+
+HIP_INVALID_VALUE = 1
+FAKE = 0x10000
+
+
+def test_membench_library_loads_and_validates_on_the_host():
+    lib = membench.load()
+    assert lib.npd_membench_patterns() == len(membench.PATTERNS) == len(membench.MOVES)
+    ok = dict(pattern=4, order=0, threads=1024, nt=1, a=FAKE, b=FAKE + 0x1000, o=FAKE + 0x2000, rows=4, groups=8)
+
+    def call(**kw):
+        p = dict(ok, **kw)
+        return lib.npd_membench_run(p["pattern"], p["order"], p["threads"], p["nt"], p["a"], p["b"], p["o"], p["rows"],
+                                    p["groups"], None)
+    # every call below is refused before anything is enqueued (the addresses are never touched)
+    assert call(a=None) == HIP_INVALID_VALUE and call(o=None) == HIP_INVALID_VALUE
+    assert call(rows=0) == HIP_INVALID_VALUE and call(groups=0) == HIP_INVALID_VALUE
+    assert call(rows=2**31) == HIP_INVALID_VALUE
+    assert call(a=FAKE + 4) == HIP_INVALID_VALUE               # not 16-byte aligned
+    assert call(threads=128) == HIP_INVALID_VALUE and call(pattern=6) == HIP_INVALID_VALUE
+    assert call(pattern=5, threads=256, groups=19 * 256 + 1) == HIP_INVALID_VALUE   # row larger than the registers
+    assert call(order=2) == HIP_INVALID_VALUE and call(pattern=5, order=1) == HIP_INVALID_VALUE
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("threads", [256, 512, 1024])
+@pytest.mark.parametrize("nt", [False, True])
+def test_membench_patterns_move_what_they_say(threads, nt):
+    dev = torch.device("cuda:0")
+    rows, groups = 7, 4 * threads + 37          # a ragged tail after one full round of 4 requests per thread
+    n = rows * groups * 16
+    gen = torch.Generator(device="cpu").manual_seed(5)
+    a = torch.randint(0, 256, (n,), dtype=torch.uint8, generator=gen).to(dev)
+    b = torch.randint(0, 256, (n,), dtype=torch.uint8, generator=gen).to(dev)
+    guard = 4096
+    full = torch.full((n + 2 * guard,), 0xA5, dtype=torch.uint8, device=dev)
+    o = full[guard:guard + n]
+    assert o.data_ptr() % 16 == 0
+    expect = {"read_1": torch.full_like(a, 0xA5), "read_2": torch.full_like(a, 0xA5), "write_1": torch.zeros_like(a),
+              "copy_1r_1w": a, "read_2_write_1": a ^ b, "row_read_2_then_write_1": a ^ b}
+    for name in membench.PATTERNS:
+        for order in membench.ORDERS:
+            if order == "address" and name == "row_read_2_then_write_1":
+                continue
+            full.fill_(0xA5)
+            membench.run(name, threads, nt, a, b, o, rows, groups, order=order)
+            torch.cuda.synchronize()
+            assert torch.equal(o, expect[name]), (name, order)
+            assert (full[:guard] == 0xA5).all() and (full[guard + n:] == 0xA5).all(), (name, order)
