@@ -390,11 +390,11 @@ def test_cfg4_many_short_samples_inplace(oracle):
 
 # --------------------------------------------------------------------------- full benchmark size, sampled rows
 
-@pytest.mark.parametrize("div", ["forward", "reverse"])
+@pytest.mark.parametrize("div", ["forward", "reverse", "skew", "skew_reverse"])
 def test_cfg1_full_size_sampled_rows(oracle, div):
     """Config 1 at its real size (32,768 x 151,936, the launch bench.py times): a sample of rows is checked
-    element by element, every row through properties that hold at any size.  Also with the reverse KL, which
-    runs in the same row-resident kernel."""
+    element by element, every row through properties that hold at any size.  Also with the other divergences, which
+    run in the same row-resident kernel."""
     w = synth.config(1)
     lay, s, t, mask, labels = _inputs(w)
     T, V = w.n_tokens, w.vocab
@@ -406,7 +406,7 @@ def test_cfg1_full_size_sampled_rows(oracle, div):
     status = torch.zeros(1, dtype=torch.int32, device=dev())
     binding.npd_kd_loss_fwd_bwd(s, mask, teacher_dense=t, labels=labels, grad_out=g, kd_tok=kd, nll_tok=nll,
                                 teacher_nll_tok=tnll, dev_status=status,
-                                divergence=binding.NPD_DIV_REVERSE_KL if div == "reverse" else 0)
+                                divergence=0 if div == "forward" else DIVS[div], skew_alpha=0.1)
     torch.cuda.synchronize()
     assert status.item() == 0
     m = mask.bool()
@@ -423,8 +423,8 @@ def test_cfg1_full_size_sampled_rows(oracle, div):
                                    np.flatnonzero(lay.loss_mask == 0)[:2]]))
     ridx = torch.from_numpy(rows).to(dev())
     ref = oracle.kd_dense(_bits(s[ridx]), _bits(t[ridx]), lay.labels[rows], lay.loss_mask[rows])
-    if div == "reverse":
-        ref.update(oracle.div_dense(_bits(s[ridx]), _bits(t[ridx]), "reverse", mask=lay.loss_mask[rows]))
+    if div != "forward":
+        ref.update(oracle.div_dense(_bits(s[ridx]), _bits(t[ridx]), div, 0.1, mask=lay.loss_mask[rows]))
     gpu = dict(kd=kd[ridx].cpu().numpy().astype(np.float64), nll_s=nll[ridx].cpu().numpy().astype(np.float64),
                nll_t=tnll[ridx].cpu().numpy().astype(np.float64), grad=g[ridx].float().cpu().numpy().astype(np.float64))
     compare_kd(gpu, ref, lay.loss_mask[rows], amp_from_ref=div != "forward")
@@ -717,6 +717,41 @@ def test_teacher_topk_feeds_the_kd_loss(oracle):
     ref = oracle.kd_topk(_bits(s), rec["idx"], rec["val"], lay.labels, lay.loss_mask, tau=2.0)
     assert gpu["status"] == 0
     compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle, tau=2.0)
+
+
+@pytest.mark.parametrize("k", [10, 64])
+def test_cfg1_full_size_teacher_topk(oracle, k):
+    """The top-k record of config 1's teacher logits at their real size (32,768 x 151,936; the launch that
+    `bench.py --op teacher_topk` times): sampled rows bit-exact against the oracle's selection, every row through
+    properties that hold at any size (ids in range and distinct, values in decreasing order, the selected values
+    equal to the k largest of the row, not-scored rows as documented)."""
+    w = synth.config(1)
+    lay, _, t, mask, _ = _inputs(w)
+    T, V = w.n_tokens, w.vocab
+    _say(f"{w.name} full size teacher top-k, k={k}")
+    idx, val = _topk_gpu(t, k, mask, log_probs=False)
+    m = mask.bool()
+    assert ((idx >= 0) & (idx < V)).all()
+    assert (idx[~m] == torch.arange(k, device=dev(), dtype=torch.int32)).all() and (val[~m] == 0).all()
+    srt = idx[m].sort(dim=1).values
+    assert (srt[:, 1:] != srt[:, :-1]).all()                       # distinct ids
+    assert (val[m][:, 1:] <= val[m][:, :-1]).all()                 # largest first
+    rows_m = torch.nonzero(m).flatten()
+    for r0 in range(0, rows_m.numel(), 2048):                      # the k largest values of every scored row
+        rr = rows_m[r0:r0 + 2048]
+        top = torch.topk(t[rr].float(), k, dim=1).values
+        assert torch.equal(top, val[rr])
+        assert torch.equal(torch.gather(t[rr].float(), 1, idx[rr].long()), val[rr])   # ids point at those values
+    rows = _sample_rows(lay, 60, 17)
+    ridx = torch.from_numpy(rows).to(dev())
+    ref = oracle.teacher_topk(_bits(t[ridx]), k, lay.loss_mask[rows], False)
+    np.testing.assert_array_equal(idx[ridx].cpu().numpy(), ref["idx"])
+    np.testing.assert_array_equal(val[ridx].cpu().numpy().astype(np.float64), ref["val"])
+    # the log-softmax form of the same record, sampled rows
+    idx2, lp = _topk_gpu(t, k, mask, log_probs=True)
+    assert torch.equal(idx2, idx)
+    ref2 = oracle.teacher_topk(_bits(t[ridx]), k, lay.loss_mask[rows], True)
+    np.testing.assert_allclose(lp[ridx].cpu().numpy(), ref2["val"], rtol=0, atol=2e-5)
 
 
 # --------------------------------------------------------------------------- other divergences (Related Works)
