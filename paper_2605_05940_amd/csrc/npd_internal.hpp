@@ -57,6 +57,17 @@ hipError_t launch_cached_short_512(const KdArgs& a, int cs, int teacher_kind, hi
 hipError_t launch_cached_short_256(const KdArgs& a, int cs, int teacher_kind, hipStream_t stream);
 hipError_t launch_cached_forward_only(const KdArgs& a, int threads, int teacher_kind, hipStream_t stream);
 
+// arguments of the top-k kernels (npd_topk_impl.hpp)
+struct TopkArgs {
+  const uint16_t* t;
+  const uint8_t* mask;
+  int32_t* idx;
+  float* val;
+  int64_t stride;
+  int64_t T;
+  int32_t V, k, nvec, log_probs;
+};
+
 hipError_t launch_teacher_topk(int64_t T, int32_t V, int64_t stride, int32_t k, int log_probs, const uint16_t* t,
                                const uint8_t* mask, int32_t* idx, float* val, hipStream_t stream);
 

@@ -662,15 +662,17 @@ def test_teacher_topk_shapes(oracle, V, stride, k, log_probs):
     np.testing.assert_allclose(val.cpu().numpy(), ref["val"], rtol=0, atol=2e-5 if log_probs else 0)
 
 
-def test_teacher_topk_ties_and_degenerate_rows(oracle):
-    V, k = 151936, 64
+# k = 64 and 128 run with 512-thread workgroups, 129 and 200 with 1024-thread ones
+@pytest.mark.parametrize("k", [64, 128, 129, 200])
+def test_teacher_topk_ties_and_degenerate_rows(oracle, k):
+    V = 151936
     t = (torch.randn((6, V), device=dev()) * 3).to(torch.bfloat16)
     t[0, :] = 1.5                                    # constant row: ids 0..k-1 (slow path: every element ties)
     t[1, 1000:9000] = 50.0                           # 8000 equal maxima: the 64 lowest ids among them
     t[2, :] = 0.0
     t[2, ::2] = -0.0                                 # +0 and -0 are equal values
     t[3, 7] = 30.0
-    t[3, 100000:100063] = 30.0                       # exactly k tied maxima, one far from the others
+    t[3, 100000:100000 + k - 1] = 30.0               # exactly k tied maxima, one far from the others
     t[4, -1] = 99.0                                  # the last element of the row
     idx, val = _topk_gpu(t, k, None, False)
     ref = oracle.teacher_topk(_bits(t), k, None, False)
@@ -678,13 +680,15 @@ def test_teacher_topk_ties_and_degenerate_rows(oracle):
     np.testing.assert_array_equal(val.cpu().numpy().astype(np.float64), ref["val"])
     assert idx[0].tolist() == list(range(k)) and idx[1].tolist() == list(range(1000, 1000 + k))
     assert idx[2].tolist() == list(range(k)) and idx[4, 0].item() == V - 1
-    assert idx[3].tolist() == [7] + list(range(100000, 100063))
+    assert idx[3].tolist() == [7] + list(range(100000, 100000 + k - 1))
 
 
-def test_teacher_topk_negative_rows_and_tie_runs(oracle):
+@pytest.mark.parametrize("k", [64, 200])
+def test_teacher_topk_negative_rows_and_tie_runs(oracle, k):
     """Rows of log-probabilities (all negative), rows whose bound is zero, and tie runs at the cut that are
-    longer than the short list but fit the candidate list."""
-    V, k = 151936, 64
+    longer than the short list but fit the candidate list (3000 ties: within the 4096 of the 1024-thread
+    kernel, beyond the 2048 of the 512-thread one, which then takes the exact slow path; 1500 ties fit both)."""
+    V = 151936
     g = torch.Generator(device="cpu").manual_seed(synth.SEED + 77)
     base = torch.randn((8, V), generator=g) * 3
     t = base.clone()
@@ -695,6 +699,7 @@ def test_teacher_topk_negative_rows_and_tie_runs(oracle):
     t[3, 20000:23000] = 40.0                                      # 3000 equal maxima: a tie run at the cut
     t[4] = torch.where(base[4] > 6.0, base[4], torch.full((), -3.0e38))   # a handful of finite values
     t[4, :200] = 1.0
+    t[6, 70000:71500] = 40.0                                      # 1500 equal maxima
     t[5] = -base[5].abs()
     t[5, 100] = 0.0                                               # a single +0 above negatives
     t = t.to(torch.bfloat16).to(dev())
@@ -703,7 +708,7 @@ def test_teacher_topk_negative_rows_and_tie_runs(oracle):
         ref = oracle.teacher_topk(_bits(t), k, None, log_probs)
         np.testing.assert_array_equal(idx.cpu().numpy(), ref["idx"])
         np.testing.assert_allclose(val.cpu().numpy(), ref["val"], rtol=0, atol=2e-5 if log_probs else 0)
-    assert idx[3].tolist() == list(range(20000, 20000 + k))
+    assert idx[3].tolist() == list(range(20000, 20000 + k)) and idx[6].tolist() == list(range(70000, 70000 + k))
 
 
 def test_teacher_topk_feeds_the_kd_loss(oracle):
