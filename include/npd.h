@@ -39,7 +39,8 @@ typedef enum {
   NPD_OK = 0,
   NPD_ERR_NULL = 1,        /* a required pointer is NULL                                  */
   NPD_ERR_SHAPE = 2,       /* a size, stride or count is out of range                     */
-  NPD_ERR_VALUE = 3,       /* tau <= 0 or not finite, grad_scale not finite, lo > hi ...  */
+  NPD_ERR_VALUE = 3,       /* tau <= 0 or not finite, grad_scale not finite, lo > hi ...;
+                              a pointer that is not a multiple of its element size        */
   NPD_ERR_ALIAS = 4,       /* grad_out overlaps an input in a way the flags do not allow  */
   NPD_ERR_UNSUPPORTED = 5, /* a combination this build does not implement                 */
   NPD_ERR_WORKSPACE = 6,   /* workspace smaller than npd_workspace_bytes() says           */

@@ -26,6 +26,9 @@ size_t rows_bytes(int64_t T, int64_t stride, int64_t width, size_t elem) {
 // a row stride the byte extent of [T, stride] bf16 / fp32 arrays can be computed with in 64 bits
 bool stride_fits(int64_t T, int64_t stride) { return stride <= (INT64_MAX / 8) / T; }
 
+// a pointer that is not a multiple of its element size (NULL counts as aligned)
+bool misaligned(const void* p, uintptr_t elem) { return (reinterpret_cast<uintptr_t>(p) & (elem - 1)) != 0; }
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 npd_status check_desc(const npd_kd_desc* d) {
@@ -61,14 +64,14 @@ npd_status check_desc(const npd_kd_desc* d) {
 
 extern "C" {
 
-int npd_version(void) { return 103; }
+int npd_version(void) { return 104; }
 
 const char* npd_status_string(npd_status st) {
   switch (st) {
     case NPD_OK: return "ok";
     case NPD_ERR_NULL: return "a required pointer is NULL";
     case NPD_ERR_SHAPE: return "a size, stride or count is out of range";
-    case NPD_ERR_VALUE: return "a scalar argument or flag has an illegal value";
+    case NPD_ERR_VALUE: return "a scalar argument or flag has an illegal value, or a pointer is misaligned";
     case NPD_ERR_ALIAS: return "an output overlaps an input in a way the flags do not allow";
     case NPD_ERR_UNSUPPORTED: return "combination not supported by this build";
     case NPD_ERR_WORKSPACE: return "workspace too small or misaligned";
@@ -93,6 +96,10 @@ npd_status npd_kd_loss_fwd_bwd(const npd_kd_desc* desc, const void* student_logi
   const int64_t T = d.n_tokens;
   const int V = d.vocab;
   if (!student_logits || !loss_mask) return NPD_ERR_NULL;
+  if (misaligned(student_logits, 2) || misaligned(teacher_dense, 2) || misaligned(grad_out, 2) ||
+      misaligned(teacher_idx, 4) || misaligned(teacher_val, 4) || misaligned(labels, 4) || misaligned(kd_tok, 4) ||
+      misaligned(nll_tok, 4) || misaligned(teacher_nll_tok, 4) || misaligned(lse_tok, 4) || misaligned(dev_status, 4))
+    return NPD_ERR_VALUE;
   const bool fwd_only = (d.flags & NPD_FLAG_FWD_ONLY) != 0;
   const bool inplace = (d.flags & NPD_FLAG_INPLACE_GRAD) != 0;
 
@@ -174,6 +181,7 @@ npd_status npd_teacher_topk(int64_t n_tokens, int32_t vocab, int64_t teacher_str
   if (!teacher_logits || !topk_idx || !topk_val) return NPD_ERR_NULL;
   if (k > npd::kTopkMax || n_tokens > NPD_MAX_TOKENS || vocab > NPD_MAX_VOCAB) return NPD_ERR_UNSUPPORTED;
   if (!stride_fits(n_tokens, teacher_stride)) return NPD_ERR_SHAPE;
+  if (misaligned(teacher_logits, 2) || misaligned(topk_idx, 4) || misaligned(topk_val, 4)) return NPD_ERR_VALUE;
   const hipError_t e = npd::launch_teacher_topk(n_tokens, vocab, teacher_stride, k, (flags & NPD_TOPK_LOG_PROBS) != 0,
                                                 static_cast<const uint16_t*>(teacher_logits), loss_mask, topk_idx,
                                                 topk_val, static_cast<hipStream_t>(stream));
@@ -184,6 +192,10 @@ npd_status npd_segment_reduce(int64_t n_tokens, int32_t n_segments, const float*
                               const int32_t* cu_seqlens, float* seg_sum, int32_t* seg_count, float* seg_mean,
                               int32_t* token_to_sample, int32_t* dev_status, void* stream) {
   if (n_tokens < 0 || n_segments < 0) return NPD_ERR_SHAPE;
+  if (n_tokens > NPD_MAX_TOKENS) return NPD_ERR_UNSUPPORTED;
+  if (misaligned(values, 4) || misaligned(cu_seqlens, 4) || misaligned(seg_sum, 4) || misaligned(seg_count, 4) ||
+      misaligned(seg_mean, 4) || misaligned(token_to_sample, 4) || misaligned(dev_status, 4))
+    return NPD_ERR_VALUE;
   if (n_segments > 0 && (!loss_mask || !cu_seqlens)) return NPD_ERR_NULL;
   if (n_segments > 0 && (seg_sum || seg_mean) && !values) return NPD_ERR_NULL;
   const hipError_t e =
@@ -200,6 +212,10 @@ npd_status npd_delta_ifd_score(int32_t n_pairs, int32_t n_segments, const float*
   if (n_pairs < 0 || n_segments < 0) return NPD_ERR_SHAPE;
   if (!isfinite(lo) || !isfinite(hi) || lo > hi) return NPD_ERR_VALUE;
   if (flags & ~(uint32_t)NPD_IFD_REQUIRE_TEACHER_LE_1) return NPD_ERR_VALUE;
+  if (misaligned(mean_nll_student, 4) || misaligned(mean_nll_teacher, 4) || misaligned(seg_count, 4) ||
+      misaligned(pair_cond, 4) || misaligned(pair_uncond, 4) || misaligned(ifd_student, 4) ||
+      misaligned(ifd_teacher, 4) || misaligned(delta, 4) || misaligned(keep_count, 4))
+    return NPD_ERR_VALUE;
   if (n_pairs > 0 && (!mean_nll_student || !mean_nll_teacher || !seg_count || !pair_cond || !pair_uncond))
     return NPD_ERR_NULL;
   const hipError_t e = npd::launch_delta_ifd(n_pairs, n_segments, mean_nll_student, mean_nll_teacher, seg_count,

@@ -123,6 +123,12 @@ def test_kd_argument_validation(lib):
     assert _kd(lib, _desc(**nt), teacher=None) == E_VALUE           # gradient without a teacher
     assert _kd(lib, _desc(flags=1, **nt), teacher=None, grad=None, kd=FAKE + 0x700000) == E_VALUE
     assert lib.npd_workspace_bytes(ctypes.byref(_desc())) == 0
+    # pointers must be multiples of their element size
+    assert _kd(lib, _desc(), student=FAKE + 1) == E_VALUE
+    assert _kd(lib, _desc(), teacher=FAKE + 0x100001) == E_VALUE
+    assert _kd(lib, _desc(), grad=FAKE + 0x300001) == E_VALUE
+    assert _kd(lib, _desc(), labels=FAKE + 0x800002, nll=FAKE + 0x400000) == E_VALUE
+    assert _kd(lib, _desc(), kd=FAKE + 0x400002) == E_VALUE
     # limits of one call: positions, vocabulary, and strides whose byte extents would not fit 64 bits
     assert _kd(lib, _desc(n_tokens=2**31)) == E_UNSUP
     huge = (1 << 26) + 8
@@ -137,6 +143,8 @@ def test_segment_and_ifd_argument_validation(lib):
     assert lib.npd_segment_reduce(8, 2, FAKE, None, FAKE, FAKE, FAKE, FAKE, None, None, None) == E_NULL
     assert lib.npd_segment_reduce(8, 2, FAKE, FAKE, None, FAKE, FAKE, FAKE, None, None, None) == E_NULL
     assert lib.npd_segment_reduce(8, 2, None, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, None) == E_NULL
+    assert lib.npd_segment_reduce(8, 2, FAKE + 2, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, None) == E_VALUE
+    assert lib.npd_segment_reduce(2**31, 2, *([FAKE] * 8), None) == E_UNSUP
     args = [FAKE] * 5
     outs = [None] * 6
     assert lib.npd_delta_ifd_score(-1, 4, *args, 0.0, 1.0, 0, *outs, None) == E_SHAPE
@@ -144,6 +152,7 @@ def test_segment_and_ifd_argument_validation(lib):
     assert lib.npd_delta_ifd_score(2, 4, *args, float("nan"), 0.5, 0, *outs, None) == E_VALUE
     assert lib.npd_delta_ifd_score(2, 4, *args, 0.0, 1.0, 8, *outs, None) == E_VALUE
     assert lib.npd_delta_ifd_score(2, 4, None, FAKE, FAKE, FAKE, FAKE, 0.0, 1.0, 0, *outs, None) == E_NULL
+    assert lib.npd_delta_ifd_score(2, 4, FAKE + 1, FAKE, FAKE, FAKE, FAKE, 0.0, 1.0, 0, *outs, None) == E_VALUE
 
 
 def test_teacher_topk_argument_validation(lib):
@@ -156,6 +165,7 @@ def test_teacher_topk_argument_validation(lib):
     assert call(T=0) == E_SHAPE and call(V=0) == E_SHAPE and call(stride=63) == E_SHAPE
     assert call(T=2**31) == E_UNSUP and call(V=(1 << 26) + 8, stride=(1 << 26) + 8) == E_UNSUP
     assert call(stride=2**61) == E_SHAPE
+    assert call(t=FAKE + 1) == E_VALUE and call(idx=FAKE + 0x100002) == E_VALUE
     assert call(k=0) == E_SHAPE and call(k=65) == E_SHAPE
     assert call(flags=2) == E_VALUE
     assert call(t=None) == E_NULL and call(idx=None) == E_NULL and call(val=None) == E_NULL
