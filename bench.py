@@ -21,8 +21,15 @@ import torch
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 
 # HBM-side bytes per launch of the fused kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
-# counters read for a plain copy of known size (x2.000 and x1.000); summary in profiles/kd_cached_kernel_cfg1_hbm_traffic.md
-MEASURED_TRAFFIC_BYTES = {"cfg1_1b_dense": (14_854_249 + 9_732_739) * 1024}
+# counters read for a plain copy of known size (x2.000 and x1.000); summaries in profiles/kd_cached_kernel_cfg1_hbm_traffic.md
+# and profiles/kd_kernels_other_workloads_hbm_traffic.md.  KiB of fetches (scaled) + KiB of writes per launch; config 3's
+# "launch" is its two forward-only calls.
+MEASURED_TRAFFIC_BYTES = {"cfg1_1b_dense": (14_854_249 + 9_732_739) * 1024,
+                          "cfg2_topk64": (2 * 3_520_534 + 9_798_926) * 1024,
+                          "cfg3_delta_ifd": 2 * (2 * 7_659_974 + 2_053) * 1024,
+                          "cfg4_stress": (2 * 41_329_329 + 33_563_337) * 1024}
+# the teacher top-k record of config 1's teacher logits, by k
+MEASURED_TOPK_TRAFFIC_BYTES = {64: (2 * 3_428_426 + 16_384) * 1024}
 
 
 def algorithmic_bytes(w, lay):
@@ -296,7 +303,8 @@ def bench_teacher_topk(args, binding, synth, dev):
         "config": {"workload": f"{w.name}: teacher logits {T} x {V} bf16, top-{k} ids + log-probs",
                    "tokens": T, "scored_tokens": n_scored},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TOPK_TRAFFIC_BYTES.get(k) if args.config == 1 else None,
                      "kernel": "npd::teacher_topk_stream_kernel", "kernel_ms": kernel_ms,
                      "algorithmic_bytes_per_launch": alg_bytes},
     }
