@@ -1,8 +1,6 @@
-// Row-resident variant of the fused KD loss + gradient kernel (gfx950): the kernel template and its launcher.  The
-// instantiations are spread over several translation units (npd_kd_cached_*.hip) so that they compile in parallel.
-//
-// Row-resident variant of the fused KD loss + gradient kernel (gfx950): rows of 8,192 entries and more, 16-byte
-// aligned.
+// Row-resident variant of the fused KD loss + gradient kernel (gfx950), for rows of 8,192 entries and more, 16-byte
+// aligned: the kernel template and its launcher.  The instantiations are spread over several translation units
+// (npd_kd_cached_*.hip) so that they compile in parallel.
 //
 // One workgroup per token row.  A row of ~150k bf16 logits (student + teacher = 608 KB) does not fit one CU, but most
 // of it does: CB threads x CSR 128-bit groups of the student row stay in VGPRs (packed bf16, as loaded), CT groups
