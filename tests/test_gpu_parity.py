@@ -927,6 +927,77 @@ def test_shape_selection_boundaries(oracle, V):
     compare_kd(tk, rt, lay.loss_mask, lay.cu_seqlens, oracle, tau=2.0)
 
 
+# --------------------------------------------------------------------------- seeded random shapes
+
+def _random_case(i):
+    """Case i of a fixed, seeded list: vocabulary, row padding, teacher kind, temperature, weights and modes drawn
+    so that every kernel family, thread count and streamed / ragged / tail combination turns up somewhere."""
+    rng = np.random.default_rng(9000 + i)
+    V = int(np.exp(rng.uniform(np.log(200), np.log(300000))))
+    if rng.random() < 0.6:
+        V = max(8, V // 8 * 8)                                   # most vocabularies are multiples of 8
+    aligned = rng.random() < 0.8
+    stride = (V + 7) // 8 * 8 + 8 * int(rng.integers(0, 3)) if aligned else V + int(rng.integers(0, 2)) * 3 + (V % 2 == 0)
+    kind = rng.choice(["dense", "dense", "topk", "none"])
+    tau = float(rng.choice([0.5, 1.0, 1.0, 2.0, 3.7]))
+    scale = float(rng.choice([1.0, 1.0, -0.5, 3.0]))
+    fwd_only = kind == "none" or rng.random() < 0.2
+    inplace = (not fwd_only) and rng.random() < 0.3
+    ce = 0.1 if (not fwd_only and rng.random() < 0.3) else 0.0
+    div = rng.choice(["forward", "forward", "reverse", "skew", "skew_reverse"]) if kind == "dense" else "forward"
+    k = int(min(V, np.exp(rng.uniform(0, np.log(600))))) if kind == "topk" else 0
+    return dict(V=V, stride=int(stride), kind=str(kind), tau=tau, scale=scale, fwd_only=bool(fwd_only),
+                inplace=bool(inplace), ce=ce, div=str(div), k=max(1, k), alpha=float(rng.choice([0.1, 0.5, 0.9])))
+
+
+@pytest.mark.parametrize("i", range(96))
+def test_seeded_random_shapes(oracle, i):
+    c = _random_case(i)
+    V = c["V"]
+    T = 10 if V > 100000 else 24
+    w = synth.scaled(synth.config(1), n_rows=1, row_len=T, vocab=V, length_lo=3, length_hi=9, topk=c["k"])
+    _say(f"random case {i}: {c}")
+    lay, s, t, mask, labels = _inputs(w, c["stride"], dense_teacher=c["kind"] == "dense")
+    sb = _bits(s.contiguous())
+    tol = dict(grad_scale=c["scale"], tau=c["tau"], amp_from_ref=c["div"] != "forward" or c["ce"] != 0.0)
+    want_grad = not c["fwd_only"]
+    if c["kind"] == "dense":
+        tb = _bits(t.contiguous())
+        if c["div"] == "forward":
+            ref = oracle.kd_dense(sb, tb, lay.labels, lay.loss_mask, tau=c["tau"], grad_scale=c["scale"],
+                                  ce_grad_scale=c["ce"], want_grad=want_grad)
+        else:
+            ref = oracle.div_dense(sb, tb, c["div"], c["alpha"], labels=lay.labels, mask=lay.loss_mask, tau=c["tau"],
+                                   grad_scale=c["scale"], ce_grad_scale=c["ce"], want_grad=want_grad)
+            nl = oracle.kd_dense(sb, tb, lay.labels, lay.loss_mask, want_grad=False)
+            ref.update(nll_s=nl["nll_s"], nll_t=nl["nll_t"], lse_s=nl["lse_s"])
+        gpu = run_gpu_kd(s.clone() if c["inplace"] else s, mask, t=t, labels=labels, tau=c["tau"],
+                         grad_scale=c["scale"], ce_grad_scale=c["ce"], want_grad=want_grad, inplace=c["inplace"],
+                         divergence=0 if c["div"] == "forward" else DIVS[c["div"]], skew_alpha=c["alpha"])
+    elif c["kind"] == "topk":
+        idx, val = synth.make_topk_teacher(w, s)
+        ref = oracle.kd_topk(sb, idx.cpu().numpy(), val.cpu().numpy(), lay.labels, lay.loss_mask, tau=c["tau"],
+                             grad_scale=c["scale"], ce_grad_scale=c["ce"], want_grad=want_grad)
+        assert ref["bad_index_rows"] == 0
+        gpu = run_gpu_kd(s.clone() if c["inplace"] else s, mask, idx=idx, val=val, labels=labels, tau=c["tau"],
+                         grad_scale=c["scale"], ce_grad_scale=c["ce"], want_grad=want_grad, inplace=c["inplace"])
+    else:
+        nl = oracle.nll(sb, lay.labels, lay.loss_mask)
+        ref = dict(nll_s=nl["nll"], lse_s=nl["lse"])
+        gpu = run_gpu_kd(s, mask, labels=labels, want_grad=False)
+    assert gpu["status"] == 0
+    if not want_grad:
+        ref = {key: v for key, v in ref.items() if key != "grad"}
+    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle, **tol)
+    # the teacher-side record of the same logits (dense cases), k drawn like the top-k cases
+    if c["kind"] == "dense":
+        kk = int(min(V, 1 + (i * 37) % 300))
+        idx, val = _topk_gpu(t, kk, mask, True)
+        rk = oracle.teacher_topk(_bits(t.contiguous()), kk, lay.loss_mask, True)
+        np.testing.assert_array_equal(idx.cpu().numpy(), rk["idx"])
+        np.testing.assert_allclose(val.cpu().numpy(), rk["val"], rtol=0, atol=2e-5)
+
+
 # --------------------------------------------------------------------------- non-finite inputs stay in their row
 
 @pytest.mark.parametrize("V", [5003, 50264, 151936])
