@@ -159,7 +159,7 @@ static void row_div_dense(const double *s, const double *t, int64_t V, double ta
     const double p_s = exp(logp_s), p_t = exp(logp_t);
     if (divergence == DIV_REVERSE_KL) {
       if (p_s > 0.0) acc += p_s * (logp_s - logp_t);
-      u[c] = logp_s - logp_t + 1.0;
+      u[c] = p_s > 0.0 ? logp_s - logp_t + 1.0 : 0.0; /* p_S = 0: no term, and p_S (u - ubar) = 0 whatever u is */
     } else if (divergence == DIV_SKEW_KL) {
       const double m = alpha * p_t + (1.0 - alpha) * p_s;
       if (p_t > 0.0) acc += p_t * (logp_t - log(m));

@@ -204,7 +204,7 @@ __device__ __forceinline__ float div_grad_elem(float xs, float xt, const DivCoef
   const float ps = exp2_fast(lps);
   float w;
   if constexpr (DIV == kDivReverseKl) {
-    w = __builtin_fmaf(xs - xt, k.inv_tau, -k.K);
+    w = __builtin_fmaf(__builtin_fmaxf(xs - xt, -1.0e30f), k.inv_tau, -k.K);  // p_S = 0: finite times 0
   } else {
     float d = 0.0f, us = 0.0f;
     w = skew_elem<DIV>(lps, __builtin_fmaf(xt, k.c, -k.Lt), k.alpha, d, us) - k.ubar;

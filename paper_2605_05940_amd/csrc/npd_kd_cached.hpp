@@ -118,8 +118,10 @@ struct Sweep2Coef {
   DivCoef dv;  // skew forms
 };
 
+// An entry of probability 0 in the student (-inf, with the teacher at -inf or finite) has no gradient: the
+// difference is kept finite so that the product with e_S = 0 is 0 and not NaN.
 __device__ __forceinline__ float grad_reverse_elem(float xs, float xt, const Sweep2Coef& k) {
-  return exp2_fast(__builtin_fmaf(xs, k.c, -k.p.rs)) * __builtin_fmaf(xs - xt, k.ra, k.rb);
+  return exp2_fast(__builtin_fmaf(xs, k.c, -k.p.rs)) * __builtin_fmaf(__builtin_fmaxf(xs - xt, -1.0e30f), k.ra, k.rb);
 }
 
 __device__ __forceinline__ Sweep2Coef sweep2_coef(const Lse& S, const Lse& Tt, float c, float gscale, float cscale,

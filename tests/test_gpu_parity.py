@@ -1054,6 +1054,20 @@ def test_minus_infinity_marks_a_masked_vocabulary_entry(oracle, V):
         assert np.isfinite(rd["kd"]).all() and np.isfinite(rd["grad"]).all()
         gd = run_gpu_kd(s, mask, t=t, divergence=DIVS[div], skew_alpha=0.1)
         compare_kd(gd, rd, lay.loss_mask, lay.cu_seqlens, oracle, amp_from_ref=True)
+    # a vocabulary padded with -inf in both models: every divergence, the reverse KL included, is the one of the
+    # real entries, and the gradient on the padding is 0
+    t2 = t.clone()
+    t2[3, 100:200] = 1.0
+    s2 = s.clone()
+    s2[:, V - 70:] = float("-inf")
+    for div in ("reverse", "skew", "skew_reverse"):
+        rd = oracle.div_dense(_bits(s2), _bits(t2), div, 0.1, mask=lay.loss_mask)
+        assert np.isfinite(rd["kd"]).all() and np.isfinite(rd["grad"]).all()
+        gd = run_gpu_kd(s2, mask, t=t2, divergence=DIVS[div], skew_alpha=0.1)
+        compare_kd(gd, rd, lay.loss_mask, lay.cu_seqlens, oracle, amp_from_ref=True)
+        assert (gd["grad"][m][:, V - 70:] == 0).all()
+        fo = run_gpu_kd(s2, mask, t=t2, divergence=DIVS[div], skew_alpha=0.1, want_grad=False)
+        compare_kd(fo, dict(kd=rd["kd"]), lay.loss_mask, lay.cu_seqlens, oracle)
     # a stored top-k value of -inf is an entry of probability 0 as well
     val2 = val.clone()
     val2[:, -1] = float("-inf")

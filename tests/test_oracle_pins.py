@@ -622,3 +622,70 @@ def test_divergence_gradient_matches_autograd_with_composite_term_and_bf16_front
     b = oracle.div_dense(sb.double().numpy(), tb.double().numpy(), "skew_reverse", alpha, mask=mask)
     assert (a["kd"] == b["kd"]).all() and (a["grad"] == b["grad"]).all()
     assert a["kd"][1] == 0 and (a["grad"][1] == 0).all()
+
+
+# --------------------------------------------------------------------------- entries of probability 0 (-inf logits)
+
+def test_minus_infinity_logits_are_entries_of_probability_zero(oracle):
+    """A logit of -inf marks a vocabulary entry of probability 0 (a padded or banned token).  Pins: the library
+    softmax (which gives such entries exactly 0), the same problem on the reduced vocabulary, and the definition of
+    Eq. 2 with its p_T = 0 terms left out."""
+    rng = np.random.default_rng(77)
+    T, V, tau = 5, 40, 2.0
+    s, t = _rand(T, V, 2.0, rng), _rand(T, V, 2.0, rng)
+    banned = np.zeros(V, bool)
+    banned[[3, 11, 12, 39]] = True
+    labels = rng.choice(np.flatnonzero(~banned), T).astype(np.int32)
+
+    # (1) both models padded on the same entries: the problem on the reduced vocabulary, gradient 0 on the padding
+    s1, t1 = s.copy(), t.copy()
+    s1[:, banned] = -np.inf
+    t1[:, banned] = -np.inf
+    full = oracle.kd_dense(s1, t1, labels, tau=tau, grad_scale=0.7)
+    keep = np.flatnonzero(~banned)
+    relabel = np.searchsorted(keep, labels).astype(np.int32)
+    red = oracle.kd_dense(s[:, keep], t[:, keep], relabel, tau=tau, grad_scale=0.7)
+    np.testing.assert_allclose(full["kd"], red["kd"], rtol=1e-13)
+    np.testing.assert_allclose(full["nll_s"], red["nll_s"], rtol=1e-13)
+    np.testing.assert_allclose(full["nll_t"], red["nll_t"], rtol=1e-13)
+    np.testing.assert_allclose(full["grad"][:, keep], red["grad"], rtol=1e-12, atol=1e-15)
+    assert (full["grad"][:, banned] == 0).all()
+
+    # (2) only the teacher bans entries: Eq. 2 without the p_T = 0 terms, p_S still over the full vocabulary
+    out = oracle.kd_dense(s, t1, labels, tau=tau, grad_scale=1.0)
+    lps = torch.log_softmax(torch.from_numpy(s) / tau, -1)
+    pt = torch.softmax(torch.from_numpy(t1) / tau, -1)                     # exactly 0 on the banned entries
+    assert (pt[:, banned] == 0).all()
+    lpt = torch.log_softmax(torch.from_numpy(t[:, keep]) / tau, -1)
+    kl = (pt[:, keep] * (lpt - lps[:, keep])).sum(-1)
+    np.testing.assert_allclose(out["kd"], kl.numpy(), rtol=1e-12)
+    np.testing.assert_allclose(out["grad"], ((lps.exp() - pt) / tau).numpy(), rtol=1e-12, atol=1e-16)
+    assert np.isfinite(out["kd"]).all() and np.isfinite(out["grad"]).all()
+
+    # (3) the student gives probability 0 where the teacher does not: the divergence is infinite
+    s3 = s.copy()
+    s3[0, 5] = -np.inf
+    assert np.isposinf(oracle.kd_dense(s3, t, want_grad=False)["kd"][0])
+    # ... and its own label there has an infinite loss
+    lab = labels.copy()
+    lab[0] = 5
+    assert np.isposinf(oracle.kd_dense(s3, t, lab, want_grad=False)["nll_s"][0])
+
+    # (4) a top-k value of -inf is an entry the record does not have
+    k = 6
+    idx = np.stack([rng.choice(V, k, replace=False) for _ in range(T)]).astype(np.int32)
+    val = rng.normal(0, 1, (T, k))
+    val_inf = val.copy()
+    val_inf[:, 2] = -np.inf
+    a = oracle.kd_topk(s, idx, val_inf, tau=tau)
+    b = oracle.kd_topk(s, np.delete(idx, 2, axis=1), np.delete(val, 2, axis=1), tau=tau)
+    np.testing.assert_allclose(a["kd"], b["kd"], rtol=1e-13)
+    np.testing.assert_allclose(a["grad"], b["grad"], rtol=1e-12, atol=1e-16)
+
+    # (5) the other divergences: entries of probability 0 in both models contribute no term and no gradient
+    for div in ("reverse", "skew", "skew_reverse"):
+        fa = oracle.div_dense(s1, t1, div, 0.3, tau=tau)
+        re = oracle.div_dense(s[:, keep], t[:, keep], div, 0.3, tau=tau)
+        np.testing.assert_allclose(fa["kd"], re["kd"], rtol=1e-12)
+        np.testing.assert_allclose(fa["grad"][:, keep], re["grad"], rtol=1e-11, atol=1e-15)
+        assert (fa["grad"][:, banned] == 0).all()
