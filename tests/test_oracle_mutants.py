@@ -30,7 +30,9 @@ MUTANTS = [
     ("ifd_inverted", "is = mean_nll_student[ic] / mean_nll_student[iu];", "is = mean_nll_student[iu] / mean_nll_student[ic];", "delta_ifd"),
     ("zone_open_interval", "else if (d32 > (float)hi)", "else if (d32 >= (float)hi)", "delta_ifd"),
     ("teacher_topk_tie_rule", "(best < 0 || row[c] > row[best])", "(best < 0 || row[c] >= row[best])", "teacher_topk"),
-    ("reverse_kl_swapped", "if (p_s > 0.0) acc += p_s * (logp_s - logp_t);\n      u[c] = logp_s - logp_t + 1.0;", "if (p_s > 0.0) acc += p_s * (logp_t - logp_s);\n      u[c] = logp_t - logp_s + 1.0;", "divergence"),
+    ("reverse_kl_swapped", "if (p_s > 0.0) acc += p_s * (logp_s - logp_t);\n      u[c] = p_s > 0.0 ? logp_s - logp_t + 1.0 : 0.0;", "if (p_s > 0.0) acc += p_s * (logp_t - logp_s);\n      u[c] = p_s > 0.0 ? logp_t - logp_s + 1.0 : 0.0;", "divergence"),
+    ("reverse_kl_zero_probability_entry", "u[c] = p_s > 0.0 ? logp_s - logp_t + 1.0 : 0.0;", "u[c] = logp_s - logp_t + 1.0;", "minus_infinity"),
+    ("forward_kl_zero_probability_term", "if (p_t > 0.0) acc += p_t * (logp_t - logp_s);\n  }\n  if (kd) *kd = acc;\n  if (grad) {\n    for (int64_t c = 0; c < V; ++c) {", "acc += p_t * (logp_t - logp_s);\n  }\n  if (kd) *kd = acc;\n  if (grad) {\n    for (int64_t c = 0; c < V; ++c) {", "minus_infinity"),
     ("skew_weights_swapped", "const double m = alpha * p_t + (1.0 - alpha) * p_s;\n      if (p_t > 0.0)", "const double m = (1.0 - alpha) * p_t + alpha * p_s;\n      if (p_t > 0.0)", "divergence"),
     ("divergence_grad_without_mean", "grad[c] = grad_scale * (1.0 / tau) * exp(a[c] - lse_a) * (u[c] - ubar);", "grad[c] = grad_scale * (1.0 / tau) * exp(a[c] - lse_a) * u[c];", "divergence"),
 ]
