@@ -66,14 +66,20 @@ enum {
 /* npd_kd_desc.flags */
 enum {
   NPD_FLAG_FWD_ONLY = 1u,      /* no gradient: grad_out must be NULL                               */
-  NPD_FLAG_INPLACE_GRAD = 2u   /* grad_out == student_logits: each row is overwritten by its gradient */
+  NPD_FLAG_INPLACE_GRAD = 2u,  /* grad_out == student_logits: each row is overwritten by its gradient */
+  NPD_FLAG_NO_WORKSPACE = 4u   /* the caller brings no workspace: npd_workspace_bytes() is 0 and only kernels that
+                                  need none run (on rows of more than 20,480 logits with a dense teacher these are
+                                  slower than the ones that exchange partial sums through a workspace)           */
 };
 
 /* bits OR-ed into *dev_status by kernels */
 enum {
   NPD_DEV_BAD_LABEL = 1,      /* labels[p] outside [0, V) at a scored position        */
   NPD_DEV_BAD_TOPK_INDEX = 2, /* teacher_idx outside [0, V) at a scored position      */
-  NPD_DEV_BAD_CU_SEQLENS = 4  /* cu_seqlens decreasing or outside [0, T]              */
+  NPD_DEV_BAD_CU_SEQLENS = 4, /* cu_seqlens decreasing or outside [0, T]              */
+  NPD_DEV_GANG_TIMEOUT = 8    /* workgroups that share a row gave up waiting for one another (never in a healthy
+                                 run: every such wait is bounded so that a kernel cannot hang); the outputs of the
+                                 rows concerned are NaN                                                        */
 };
 
 /* zone codes written by npd_delta_ifd_score (Sec. 3.2, "Differential Difficulty") */
@@ -115,6 +121,13 @@ int npd_version(void);
 
 /* Static, never NULL. */
 const char* npd_status_string(npd_status st);
+
+/*
+ * Testing aid: how many times a workgroup of the row-gang kernels polls for the other workgroups of its row before
+ * it gives up (NPD_DEV_GANG_TIMEOUT).  polls <= 0 restores the default (about a second).  Returns the previous
+ * value.  A tiny limit lets a test reach the give-up path while every kernel still ends normally.  Process-wide.
+ */
+int npd_debug_gang_spin_limit(int polls);
 
 /*
  * Bytes of device workspace npd_kd_loss_fwd_bwd needs for `desc` (host call; 0 is a

@@ -15,15 +15,15 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("NPD_LIB_PATH") or os.path.join(HERE, "libnpd.so")
 
 NPD_TEACHER_DENSE_BF16, NPD_TEACHER_TOPK, NPD_TEACHER_NONE = 0, 1, 2
-NPD_FLAG_FWD_ONLY, NPD_FLAG_INPLACE_GRAD = 1, 2
+NPD_FLAG_FWD_ONLY, NPD_FLAG_INPLACE_GRAD, NPD_FLAG_NO_WORKSPACE = 1, 2, 4
 NPD_DIV_FORWARD_KL, NPD_DIV_REVERSE_KL, NPD_DIV_SKEW_KL, NPD_DIV_SKEW_REVERSE_KL = 0, 1, 2, 3
-NPD_DEV_BAD_LABEL, NPD_DEV_BAD_TOPK_INDEX, NPD_DEV_BAD_CU_SEQLENS = 1, 2, 4
+NPD_DEV_BAD_LABEL, NPD_DEV_BAD_TOPK_INDEX, NPD_DEV_BAD_CU_SEQLENS, NPD_DEV_GANG_TIMEOUT = 1, 2, 4, 8
 NPD_ZONE_DEGENERATE, NPD_ZONE_PROXIMAL, NPD_ZONE_DISCONNECT, NPD_ZONE_INVALID = 0, 1, 2, 3
 NPD_IFD_REQUIRE_TEACHER_LE_1 = 1
 NPD_TOPK_LOG_PROBS = 1
 
 EXPORTS = ("npd_version", "npd_status_string", "npd_workspace_bytes", "npd_kd_loss_fwd_bwd",
-           "npd_segment_reduce", "npd_delta_ifd_score", "npd_teacher_topk")
+           "npd_segment_reduce", "npd_delta_ifd_score", "npd_teacher_topk", "npd_debug_gang_spin_limit")
 
 
 class NpdError(RuntimeError):
@@ -56,6 +56,8 @@ def load() -> ctypes.CDLL:
         L.npd_version.restype = ctypes.c_int
         L.npd_status_string.restype = ctypes.c_char_p
         L.npd_status_string.argtypes = [ctypes.c_int]
+        L.npd_debug_gang_spin_limit.restype = ctypes.c_int
+        L.npd_debug_gang_spin_limit.argtypes = [ctypes.c_int]
         L.npd_workspace_bytes.restype = ctypes.c_size_t
         L.npd_workspace_bytes.argtypes = [ctypes.POINTER(KdDesc)]
         L.npd_kd_loss_fwd_bwd.restype = ctypes.c_int
@@ -109,11 +111,14 @@ def npd_kd_loss_fwd_bwd(student_logits: torch.Tensor, loss_mask: torch.Tensor, *
                         grad_out: Optional[torch.Tensor] = None, kd_tok: Optional[torch.Tensor] = None,
                         nll_tok: Optional[torch.Tensor] = None, teacher_nll_tok: Optional[torch.Tensor] = None,
                         lse_tok: Optional[torch.Tensor] = None, dev_status: Optional[torch.Tensor] = None,
-                        workspace: Optional[torch.Tensor] = None) -> None:
+                        workspace: Optional[torch.Tensor] = None, no_workspace: bool = False) -> None:
     """Enqueue the fused KD loss / gradient on the current stream (see ``npd_kd_loss_fwd_bwd`` in npd.h).
 
     The teacher kind follows from which teacher tensors are given; ``grad_out is None`` means forward
-    only; ``grad_out`` sharing storage with ``student_logits`` means the in-place gradient.
+    only; ``grad_out`` sharing storage with ``student_logits`` means the in-place gradient.  ``workspace``:
+    a uint8 tensor of at least ``npd_workspace_bytes`` bytes; if it is None one is taken from
+    ``workspace_for`` (a per-device tensor that this module keeps and grows).  ``no_workspace`` sets
+    ``NPD_FLAG_NO_WORKSPACE``.
     """
     T, V = student_logits.shape
     d = KdDesc()
@@ -140,7 +145,11 @@ def npd_kd_loss_fwd_bwd(student_logits: torch.Tensor, loss_mask: torch.Tensor, *
             raise ValueError("grad_out must have the shape and row stride of student_logits")
         if grad_out.data_ptr() == student_logits.data_ptr():
             flags |= NPD_FLAG_INPLACE_GRAD
+    if no_workspace:
+        flags |= NPD_FLAG_NO_WORKSPACE
     d.flags = flags
+    if workspace is None and not no_workspace:
+        workspace = workspace_for(int(load().npd_workspace_bytes(ctypes.byref(d))), student_logits.device)
     for name, t, n in (("loss_mask", loss_mask, T), ("labels", labels, T), ("kd_tok", kd_tok, T),
                        ("nll_tok", nll_tok, T), ("teacher_nll_tok", teacher_nll_tok, T), ("lse_tok", lse_tok, T)):
         if t is not None and (t.numel() != n or not t.is_contiguous()):
@@ -152,6 +161,23 @@ def npd_kd_loss_fwd_bwd(student_logits: torch.Tensor, loss_mask: torch.Tensor, *
         _ptr(loss_mask, torch.uint8), _ptr(grad_out, torch.bfloat16), _ptr(kd_tok, torch.float32),
         _ptr(nll_tok, torch.float32), _ptr(teacher_nll_tok, torch.float32), _ptr(lse_tok, torch.float32),
         _ptr(dev_status, torch.int32), _ptr(workspace), ws_bytes, _stream()))
+
+
+_workspaces = {}
+
+
+def workspace_for(n_bytes: int, device) -> Optional[torch.Tensor]:
+    """A device buffer of at least ``n_bytes`` bytes (None for 0), kept per device and grown on demand, for callers
+    that do not manage the workspace of ``npd_kd_loss_fwd_bwd`` themselves.  Calls that share it must be ordered on
+    one stream."""
+    if n_bytes == 0:
+        return None
+    key = torch.device(device).index or 0
+    ws = _workspaces.get(key)
+    if ws is None or ws.numel() < n_bytes:
+        ws = torch.empty(n_bytes, dtype=torch.uint8, device=device)
+        _workspaces[key] = ws
+    return ws
 
 
 def npd_workspace_bytes(n_tokens: int, vocab: int, teacher_kind: int = NPD_TEACHER_DENSE_BF16, topk: int = 0,

@@ -48,7 +48,7 @@ npd_status check_desc(const npd_kd_desc* d) {
   if (!isfinite(d->grad_scale) || !isfinite(d->ce_grad_scale)) return NPD_ERR_VALUE;
   if (d->ce_grad_scale != 0.0f && ((d->flags & NPD_FLAG_FWD_ONLY) || d->teacher_kind == NPD_TEACHER_NONE))
     return NPD_ERR_VALUE;  // a CE gradient needs a gradient buffer
-  if (d->flags & ~(uint32_t)(NPD_FLAG_FWD_ONLY | NPD_FLAG_INPLACE_GRAD)) return NPD_ERR_VALUE;
+  if (d->flags & ~(uint32_t)(NPD_FLAG_FWD_ONLY | NPD_FLAG_INPLACE_GRAD | NPD_FLAG_NO_WORKSPACE)) return NPD_ERR_VALUE;
   if ((d->flags & NPD_FLAG_FWD_ONLY) && (d->flags & NPD_FLAG_INPLACE_GRAD)) return NPD_ERR_VALUE;
   if (d->divergence < NPD_DIV_FORWARD_KL || d->divergence > NPD_DIV_SKEW_REVERSE_KL) return NPD_ERR_VALUE;
   if ((d->divergence == NPD_DIV_SKEW_KL || d->divergence == NPD_DIV_SKEW_REVERSE_KL) &&
@@ -64,7 +64,7 @@ npd_status check_desc(const npd_kd_desc* d) {
 
 extern "C" {
 
-int npd_version(void) { return 104; }
+int npd_version(void) { return 105; }
 
 const char* npd_status_string(npd_status st) {
   switch (st) {
@@ -80,9 +80,18 @@ const char* npd_status_string(npd_status st) {
   return "unknown status";
 }
 
+int npd_debug_gang_spin_limit(int polls) { return npd::set_gang_spin_limit(polls); }
+
 size_t npd_workspace_bytes(const npd_kd_desc* desc) {
-  (void)desc;
-  return 0;  // every kernel keeps its partial results in registers and LDS
+  if (check_desc(desc) != NPD_OK) return 0;
+  const npd_kd_desc& d = *desc;
+  // only the row-gang kernels (long rows, dense teacher, gradient, forward or reverse KL) exchange partial sums
+  // through device memory; every other kernel keeps them in registers and LDS
+  if (d.flags & (NPD_FLAG_FWD_ONLY | NPD_FLAG_NO_WORKSPACE)) return 0;
+  if (d.teacher_kind != NPD_TEACHER_DENSE_BF16) return 0;
+  if (d.divergence != NPD_DIV_FORWARD_KL && d.divergence != NPD_DIV_REVERSE_KL) return 0;
+  if (d.ce_grad_scale != 0.0f && d.tau != 1.0f) return 0;
+  return npd::gang_workspace_bytes(d.n_tokens, d.vocab, d.tau != 1.0f);
 }
 
 npd_status npd_kd_loss_fwd_bwd(const npd_kd_desc* desc, const void* student_logits, const void* teacher_dense,
@@ -121,7 +130,8 @@ npd_status npd_kd_loss_fwd_bwd(const npd_kd_desc* desc, const void* student_logi
     if (inplace != (grad_out == student_logits)) return NPD_ERR_ALIAS;
   }
   const size_t need = npd_workspace_bytes(desc);
-  if (need > 0 && (!workspace || workspace_bytes < need)) return NPD_ERR_WORKSPACE;
+  if (need > 0 && (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)))
+    return NPD_ERR_WORKSPACE;
 
   // overlap of the gradient with any input (other than the declared in-place case) or scalar output
   const Range rs = range_of(student_logits, rows_bytes(T, d.student_stride, V, 2));
@@ -168,6 +178,7 @@ npd_status npd_kd_loss_fwd_bwd(const npd_kd_desc* desc, const void* student_logi
   a.divergence = d.divergence;
   a.alpha = d.skew_alpha;
   a.need_lse1 = (d.tau != 1.0f && (nll_tok || teacher_nll_tok || lse_tok || d.ce_grad_scale != 0.0f)) ? 1 : 0;
+  a.ws = need > 0 ? static_cast<uint32_t*>(workspace) : nullptr;
 
   const hipError_t e = npd::launch_kd(a, d.teacher_kind, !fwd_only, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? NPD_OK : NPD_ERR_HIP;

@@ -34,6 +34,12 @@ struct KdArgs {
   int32_t need_lse1;   // tau != 1 and a tau = 1 quantity (nll, teacher nll, lse) is wanted
   int32_t divergence;  // Divergence
   float alpha;         // skew coefficient
+  // row-gang kernels (npd_kd_gang.hpp)
+  uint32_t* ws;          // scratch record, gang_workspace_bytes() bytes
+  int32_t gang;          // slices (workgroups) per row
+  int32_t gang_groups;   // 128-bit groups per slice
+  int32_t gang_pow2;     // gang rounded up to a power of two
+  int32_t spin_limit;    // polls before a waiting workgroup gives up
 };
 
 hipError_t launch_kd(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream);
@@ -44,6 +50,12 @@ hipError_t launch_div(const KdArgs& a, bool want_grad, hipStream_t stream);
 // row-resident kernels for large vocabularies (npd_kd_cached.hip)
 bool cached_path_applies(const KdArgs& a, int teacher_kind, bool want_grad);
 hipError_t launch_kd_cached(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream);
+
+// row-gang kernels for long rows with a dense teacher (npd_kd_gang.hip); `lse1`: tau != 1 and a tau = 1 quantity wanted
+bool gang_path_applies(const KdArgs& a, int teacher_kind, bool want_grad);
+size_t gang_workspace_bytes(int64_t T, int32_t V, bool lse1);
+hipError_t launch_kd_gang(const KdArgs& a, hipStream_t stream);
+int set_gang_spin_limit(int polls);  // returns the previous limit; <= 0 restores the default
 
 // compute units of the current device (cached per device)
 int compute_units();

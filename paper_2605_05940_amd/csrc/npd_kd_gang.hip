@@ -1,0 +1,60 @@
+// Row-gang KD kernels (npd_kd_gang.hpp): which calls they take, the scratch record they need, and the launch.
+#include <atomic>
+
+#include "npd_kd_gang.hpp"
+
+namespace npd {
+
+static std::atomic<int> g_spin_limit{kGangSpinLimitDefault};
+
+int set_gang_spin_limit(int polls) {
+  return g_spin_limit.exchange(polls > 0 ? polls : kGangSpinLimitDefault, std::memory_order_relaxed);
+}
+
+constexpr int kGangK = 10;  // 128-bit groups per thread and tensor: 80 of a thread's 128 registers hold its slice
+
+// slices per row: a slice has at most kGangK * 256 groups (20,480 logits)
+static int gang_size(int nvec) { return (nvec + kGangK * kGangThreads - 1) / (kGangK * kGangThreads); }
+
+// Dense teacher with gradient, forward or reverse KL, 16-byte aligned rows that span at least two slices.  (The CE
+// softmax of the composite loss has no temperature; this path covers it at tau = 1, where it shares the student's
+// exponentials.)
+bool gang_path_applies(const KdArgs& a, int teacher_kind, bool want_grad) {
+  if (teacher_kind != kDense || !want_grad) return false;
+  if (a.divergence != kForwardKl && a.divergence != kReverseKl) return false;
+  if (a.cscale != 0.0f && a.need_lse1) return false;
+  const int g = gang_size(a.nvec_s);
+  if (g < 2 || g > kGangMax) return false;
+  return a.T * (int64_t)g <= 0x7fffffffLL;  // one workgroup per slice, 1-D grid
+}
+
+size_t gang_workspace_bytes(int64_t T, int32_t V, bool lse1) {
+  const int g = gang_size(V / 8);
+  if (g < 2 || g > kGangMax || T * (int64_t)g > 0x7fffffffLL) return 0;
+  return (size_t)T * g * gang_words(lse1 ? 4 : 2) * sizeof(uint32_t);
+}
+
+template <bool LSE1, int DIVK>
+static hipError_t launch_gang(const KdArgs& a, hipStream_t stream) {
+  const size_t words = (size_t)a.T * a.gang * gang_words(LSE1 ? 4 : 2);
+  hipLaunchKernelGGL(gang_clear_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream, a.ws, words);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((kd_gang_kernel<kGangK, kDense, LSE1, DIVK>), dim3((unsigned)(a.T * a.gang)), dim3(kGangThreads), 0,
+                     stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_kd_gang(const KdArgs& a0, hipStream_t stream) {
+  KdArgs a = a0;
+  a.gang = gang_size(a.nvec_s);
+  a.gang_groups = (a.nvec_s + a.gang - 1) / a.gang;
+  a.gang_pow2 = 1;
+  while (a.gang_pow2 < a.gang) a.gang_pow2 *= 2;
+  a.spin_limit = g_spin_limit.load(std::memory_order_relaxed);
+  if (a.divergence == kReverseKl)
+    return a.need_lse1 ? launch_gang<true, kReverseKl>(a, stream) : launch_gang<false, kReverseKl>(a, stream);
+  return a.need_lse1 ? launch_gang<true, kForwardKl>(a, stream) : launch_gang<false, kForwardKl>(a, stream);
+}
+
+}  // namespace npd
