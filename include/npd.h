@@ -41,7 +41,8 @@ typedef enum {
   NPD_ERR_SHAPE = 2,       /* a size, stride or count is out of range                     */
   NPD_ERR_VALUE = 3,       /* tau <= 0 or not finite, grad_scale not finite, lo > hi ...;
                               a pointer that is not a multiple of its element size        */
-  NPD_ERR_ALIAS = 4,       /* grad_out overlaps an input in a way the flags do not allow  */
+  NPD_ERR_ALIAS = 4,       /* an output (or the workspace) overlaps an input or another
+                              output in a way the flags do not allow                      */
   NPD_ERR_UNSUPPORTED = 5, /* a combination this build does not implement                 */
   NPD_ERR_WORKSPACE = 6,   /* workspace smaller than npd_workspace_bytes() says           */
   NPD_ERR_HIP = 7          /* the HIP runtime refused the launch (hipGetLastError kept)   */
@@ -178,7 +179,9 @@ size_t npd_workspace_bytes(const npd_kd_desc* desc);
  *   teacher_nll_tok  fp32 [T] or NULL (dense teacher only)
  *   lse_tok          fp32 [T] or NULL
  *   dev_status       int32 [1] or NULL
- *   workspace        device, >= npd_workspace_bytes(desc) bytes, 256-byte aligned (NULL if 0)
+ *   workspace        device, >= npd_workspace_bytes(desc) bytes, 256-byte aligned (NULL if 0); scratch of the call
+ *                    (contents meaningless before and after); must not overlap any other argument, and two
+ *                    calls that may run at the same time need a workspace each
  *
  * Each gradient element is rounded to bf16 once (round to nearest even) from an fp32
  * value; all sums are accumulated in fp32.  A call's results are bitwise reproducible from

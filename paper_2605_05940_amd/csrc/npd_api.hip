@@ -60,31 +60,22 @@ npd_status check_desc(const npd_kd_desc* d) {
   return NPD_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-int npd_version(void) { return 105; }
-
-const char* npd_status_string(npd_status st) {
-  switch (st) {
-    case NPD_OK: return "ok";
-    case NPD_ERR_NULL: return "a required pointer is NULL";
-    case NPD_ERR_SHAPE: return "a size, stride or count is out of range";
-    case NPD_ERR_VALUE: return "a scalar argument or flag has an illegal value, or a pointer is misaligned";
-    case NPD_ERR_ALIAS: return "an output overlaps an input in a way the flags do not allow";
-    case NPD_ERR_UNSUPPORTED: return "combination not supported by this build";
-    case NPD_ERR_WORKSPACE: return "workspace too small or misaligned";
-    case NPD_ERR_HIP: return "the HIP runtime refused the launch";
+// true if an output range overlaps an input range or another output range
+bool any_alias(const Range* in, int n_in, const Range* out, int n_out) {
+  for (int o = 0; o < n_out; ++o) {
+    for (int i = 0; i < n_in; ++i)
+      if (overlaps(out[o], in[i])) return true;
+    for (int o2 = o + 1; o2 < n_out; ++o2)
+      if (overlaps(out[o], out[o2])) return true;
   }
-  return "unknown status";
+  return false;
 }
 
-int npd_debug_gang_spin_limit(int polls) { return npd::set_gang_spin_limit(polls); }
+Range opt_range(const void* p, size_t bytes) { return p ? range_of(p, bytes) : Range{0, 0}; }
 
-size_t npd_workspace_bytes(const npd_kd_desc* desc) {
-  if (check_desc(desc) != NPD_OK) return 0;
-  const npd_kd_desc& d = *desc;
+
+// workspace bytes of a call with a valid descriptor
+size_t workspace_bytes_of(const npd_kd_desc& d) {
   // only the row-gang kernels (long rows, dense teacher, gradient, forward or reverse KL) exchange partial sums
   // through device memory; every other kernel keeps them in registers and LDS
   if (d.flags & (NPD_FLAG_FWD_ONLY | NPD_FLAG_NO_WORKSPACE)) return 0;
@@ -94,11 +85,49 @@ size_t npd_workspace_bytes(const npd_kd_desc* desc) {
   return npd::gang_workspace_bytes(d.n_tokens, d.vocab, d.tau != 1.0f);
 }
 
-npd_status npd_kd_loss_fwd_bwd(const npd_kd_desc* desc, const void* student_logits, const void* teacher_dense,
-                               const int32_t* teacher_idx, const float* teacher_val, const int32_t* labels,
-                               const uint8_t* loss_mask, void* grad_out, float* kd_tok, float* nll_tok,
-                               float* teacher_nll_tok, float* lse_tok, int32_t* dev_status, void* workspace,
-                               size_t workspace_bytes, void* stream) {
+// Every input and output buffer of a KD call as a byte range (empty for arguments that are absent).
+struct KdBuffers {
+  Range in[6];   // student logits, dense teacher, top-k ids, top-k values, labels, loss mask
+  Range out[6];  // gradient, kd_tok, nll_tok, teacher_nll_tok, lse_tok, dev_status
+  bool overlaps_any(const Range& r) const {
+    for (const Range& x : in)
+      if (overlaps(r, x)) return true;
+    for (const Range& x : out)
+      if (overlaps(r, x)) return true;
+    return false;
+  }
+};
+
+KdBuffers kd_buffers(const npd_kd_desc& d, const void* student_logits, const void* teacher_dense,
+                     const int32_t* teacher_idx, const float* teacher_val, const int32_t* labels,
+                     const uint8_t* loss_mask, void* grad_out, float* kd_tok, float* nll_tok, float* teacher_nll_tok,
+                     float* lse_tok, int32_t* dev_status) {
+  const int64_t T = d.n_tokens;
+  const size_t kbytes = d.teacher_kind == NPD_TEACHER_TOPK ? (size_t)T * d.topk * 4 : 0;
+  auto opt = [](const void* p, size_t bytes) { return p ? range_of(p, bytes) : Range{0, 0}; };
+  KdBuffers b;
+  b.in[0] = range_of(student_logits, rows_bytes(T, d.student_stride, d.vocab, 2));
+  b.in[1] = opt(teacher_dense, d.teacher_kind == NPD_TEACHER_DENSE_BF16 ? rows_bytes(T, d.teacher_stride, d.vocab, 2) : 0);
+  b.in[2] = opt(teacher_idx, kbytes);
+  b.in[3] = opt(teacher_val, kbytes);
+  b.in[4] = opt(labels, (size_t)T * 4);
+  b.in[5] = range_of(loss_mask, (size_t)T);
+  b.out[0] = opt(grad_out, rows_bytes(T, d.student_stride, d.vocab, 2));
+  b.out[1] = opt(kd_tok, (size_t)T * 4);
+  b.out[2] = opt(nll_tok, (size_t)T * 4);
+  b.out[3] = opt(teacher_nll_tok, (size_t)T * 4);
+  b.out[4] = opt(lse_tok, (size_t)T * 4);
+  b.out[5] = opt(dev_status, 4);
+  return b;
+}
+
+// All argument checks of a KD call except those of the workspace; fills the kernel arguments (without workspace) and
+// the number of workspace bytes the call needs.  Runs before any HIP call.
+npd_status check_kd_call(const npd_kd_desc* desc, const void* student_logits, const void* teacher_dense,
+                         const int32_t* teacher_idx, const float* teacher_val, const int32_t* labels,
+                         const uint8_t* loss_mask, void* grad_out, float* kd_tok, float* nll_tok,
+                         float* teacher_nll_tok, float* lse_tok, int32_t* dev_status, npd::KdArgs* args,
+                         size_t* workspace_need) {
   npd_status st = check_desc(desc);
   if (st != NPD_OK) return st;
   const npd_kd_desc& d = *desc;
@@ -129,26 +158,22 @@ npd_status npd_kd_loss_fwd_bwd(const npd_kd_desc* desc, const void* student_logi
     if (!grad_out) return NPD_ERR_NULL;
     if (inplace != (grad_out == student_logits)) return NPD_ERR_ALIAS;
   }
-  const size_t need = npd_workspace_bytes(desc);
-  if (need > 0 && (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)))
-    return NPD_ERR_WORKSPACE;
 
-  // overlap of the gradient with any input (other than the declared in-place case) or scalar output
-  const Range rs = range_of(student_logits, rows_bytes(T, d.student_stride, V, 2));
-  if (grad_out) {
-    const Range rg = range_of(grad_out, rows_bytes(T, d.student_stride, V, 2));
-    if (!inplace && overlaps(rg, rs)) return NPD_ERR_ALIAS;
-    if (teacher_dense && overlaps(rg, range_of(teacher_dense, rows_bytes(T, d.teacher_stride, V, 2)))) return NPD_ERR_ALIAS;
-    if (teacher_idx && overlaps(rg, range_of(teacher_idx, (size_t)T * d.topk * 4))) return NPD_ERR_ALIAS;
-    if (teacher_val && overlaps(rg, range_of(teacher_val, (size_t)T * d.topk * 4))) return NPD_ERR_ALIAS;
-    if (labels && overlaps(rg, range_of(labels, (size_t)T * 4))) return NPD_ERR_ALIAS;
-    if (overlaps(rg, range_of(loss_mask, (size_t)T))) return NPD_ERR_ALIAS;
-    const float* outs[4] = {kd_tok, nll_tok, teacher_nll_tok, lse_tok};
-    for (const float* o : outs)
-      if (o && overlaps(rg, range_of(o, (size_t)T * 4))) return NPD_ERR_ALIAS;
+  // No output may overlap an input (other than the declared in-place gradient) or another output: a row's workgroup
+  // would read what another workgroup has already overwritten.
+  const KdBuffers b = kd_buffers(d, student_logits, teacher_dense, teacher_idx, teacher_val, labels, loss_mask, grad_out,
+                                 kd_tok, nll_tok, teacher_nll_tok, lse_tok, dev_status);
+  for (int o = 0; o < 6; ++o) {
+    for (int i = 0; i < 6; ++i) {
+      if (o == 0 && i == 0 && inplace) continue;
+      if (overlaps(b.out[o], b.in[i])) return NPD_ERR_ALIAS;
+    }
+    for (int o2 = o + 1; o2 < 6; ++o2)
+      if (overlaps(b.out[o], b.out[o2])) return NPD_ERR_ALIAS;
   }
 
-  npd::KdArgs a{};
+  npd::KdArgs& a = *args;
+  a = npd::KdArgs{};
   a.s = static_cast<const uint16_t*>(student_logits);
   a.t = static_cast<const uint16_t*>(teacher_dense);
   a.tidx = teacher_idx;
@@ -178,9 +203,58 @@ npd_status npd_kd_loss_fwd_bwd(const npd_kd_desc* desc, const void* student_logi
   a.divergence = d.divergence;
   a.alpha = d.skew_alpha;
   a.need_lse1 = (d.tau != 1.0f && (nll_tok || teacher_nll_tok || lse_tok || d.ce_grad_scale != 0.0f)) ? 1 : 0;
-  a.ws = need > 0 ? static_cast<uint32_t*>(workspace) : nullptr;
+  a.ws = nullptr;
+  *workspace_need = workspace_bytes_of(d);
+  return NPD_OK;
+}
 
-  const hipError_t e = npd::launch_kd(a, d.teacher_kind, !fwd_only, static_cast<hipStream_t>(stream));
+}  // namespace
+
+extern "C" {
+
+int npd_version(void) { return 105; }
+
+const char* npd_status_string(npd_status st) {
+  switch (st) {
+    case NPD_OK: return "ok";
+    case NPD_ERR_NULL: return "a required pointer is NULL";
+    case NPD_ERR_SHAPE: return "a size, stride or count is out of range";
+    case NPD_ERR_VALUE: return "a scalar argument or flag has an illegal value, or a pointer is misaligned";
+    case NPD_ERR_ALIAS: return "an output overlaps an input in a way the flags do not allow";
+    case NPD_ERR_UNSUPPORTED: return "combination not supported by this build";
+    case NPD_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case NPD_ERR_HIP: return "the HIP runtime refused the launch";
+  }
+  return "unknown status";
+}
+
+int npd_debug_gang_spin_limit(int polls) { return npd::set_gang_spin_limit(polls); }
+
+size_t npd_workspace_bytes(const npd_kd_desc* desc) {
+  if (check_desc(desc) != NPD_OK) return 0;
+  return workspace_bytes_of(*desc);
+}
+
+npd_status npd_kd_loss_fwd_bwd(const npd_kd_desc* desc, const void* student_logits, const void* teacher_dense,
+                               const int32_t* teacher_idx, const float* teacher_val, const int32_t* labels,
+                               const uint8_t* loss_mask, void* grad_out, float* kd_tok, float* nll_tok,
+                               float* teacher_nll_tok, float* lse_tok, int32_t* dev_status, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+  npd::KdArgs a{};
+  size_t need = 0;
+  const npd_status st = check_kd_call(desc, student_logits, teacher_dense, teacher_idx, teacher_val, labels, loss_mask,
+                                      grad_out, kd_tok, nll_tok, teacher_nll_tok, lse_tok, dev_status, &a, &need);
+  if (st != NPD_OK) return st;
+  if (need > 0) {
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+      return NPD_ERR_WORKSPACE;
+    const KdBuffers b = kd_buffers(*desc, student_logits, teacher_dense, teacher_idx, teacher_val, labels, loss_mask,
+                                   grad_out, kd_tok, nll_tok, teacher_nll_tok, lse_tok, dev_status);
+    if (b.overlaps_any(range_of(workspace, need))) return NPD_ERR_ALIAS;
+    a.ws = static_cast<uint32_t*>(workspace);
+  }
+  const bool want_grad = !(desc->flags & NPD_FLAG_FWD_ONLY);
+  const hipError_t e = npd::launch_kd(a, desc->teacher_kind, want_grad, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? NPD_OK : NPD_ERR_HIP;
 }
 
@@ -193,6 +267,12 @@ npd_status npd_teacher_topk(int64_t n_tokens, int32_t vocab, int64_t teacher_str
   if (k > npd::kTopkMax || n_tokens > NPD_MAX_TOKENS || vocab > NPD_MAX_VOCAB) return NPD_ERR_UNSUPPORTED;
   if (!stride_fits(n_tokens, teacher_stride)) return NPD_ERR_SHAPE;
   if (misaligned(teacher_logits, 2) || misaligned(topk_idx, 4) || misaligned(topk_val, 4)) return NPD_ERR_VALUE;
+  {
+    const Range in[2] = {range_of(teacher_logits, rows_bytes(n_tokens, teacher_stride, vocab, 2)),
+                         opt_range(loss_mask, (size_t)n_tokens)};
+    const Range out[2] = {range_of(topk_idx, (size_t)n_tokens * k * 4), range_of(topk_val, (size_t)n_tokens * k * 4)};
+    if (any_alias(in, 2, out, 2)) return NPD_ERR_ALIAS;
+  }
   const hipError_t e = npd::launch_teacher_topk(n_tokens, vocab, teacher_stride, k, (flags & NPD_TOPK_LOG_PROBS) != 0,
                                                 static_cast<const uint16_t*>(teacher_logits), loss_mask, topk_idx,
                                                 topk_val, static_cast<hipStream_t>(stream));
@@ -209,6 +289,13 @@ npd_status npd_segment_reduce(int64_t n_tokens, int32_t n_segments, const float*
     return NPD_ERR_VALUE;
   if (n_segments > 0 && (!loss_mask || !cu_seqlens)) return NPD_ERR_NULL;
   if (n_segments > 0 && (seg_sum || seg_mean) && !values) return NPD_ERR_NULL;
+  {
+    const size_t T = (size_t)n_tokens, S = (size_t)n_segments;
+    const Range in[3] = {opt_range(values, T * 4), opt_range(loss_mask, T), opt_range(cu_seqlens, (S + 1) * 4)};
+    const Range out[5] = {opt_range(seg_sum, S * 4), opt_range(seg_count, S * 4), opt_range(seg_mean, S * 4),
+                          opt_range(token_to_sample, T * 4), opt_range(dev_status, 4)};
+    if (any_alias(in, 3, out, 5)) return NPD_ERR_ALIAS;
+  }
   const hipError_t e =
       npd::launch_segment_reduce(n_tokens, n_segments, values, loss_mask, cu_seqlens, seg_sum, seg_count, seg_mean,
                                  token_to_sample, dev_status, static_cast<hipStream_t>(stream));
@@ -229,6 +316,14 @@ npd_status npd_delta_ifd_score(int32_t n_pairs, int32_t n_segments, const float*
     return NPD_ERR_VALUE;
   if (n_pairs > 0 && (!mean_nll_student || !mean_nll_teacher || !seg_count || !pair_cond || !pair_uncond))
     return NPD_ERR_NULL;
+  {
+    const size_t P = (size_t)n_pairs, S = (size_t)n_segments;
+    const Range in[5] = {opt_range(mean_nll_student, S * 4), opt_range(mean_nll_teacher, S * 4),
+                         opt_range(seg_count, S * 4), opt_range(pair_cond, P * 4), opt_range(pair_uncond, P * 4)};
+    const Range out[6] = {opt_range(ifd_student, P * 4), opt_range(ifd_teacher, P * 4), opt_range(delta, P * 4),
+                          opt_range(zone, P), opt_range(keep, P), opt_range(keep_count, 4)};
+    if (any_alias(in, 5, out, 6)) return NPD_ERR_ALIAS;
+  }
   const hipError_t e = npd::launch_delta_ifd(n_pairs, n_segments, mean_nll_student, mean_nll_teacher, seg_count,
                                              pair_cond, pair_uncond, lo, hi, flags, ifd_student, ifd_teacher, delta,
                                              zone, keep, keep_count, static_cast<hipStream_t>(stream));

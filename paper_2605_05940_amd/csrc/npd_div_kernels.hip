@@ -170,11 +170,8 @@ __global__ __launch_bounds__(BLOCK) void div_rows_kernel(const KdArgs a) {
 template <int BLOCK, int DIV>
 static hipError_t launch_block(const KdArgs& a, bool want_grad, hipStream_t stream) {
   const dim3 grid((unsigned)a.T), block(BLOCK);
-  if (want_grad)
-    hipLaunchKernelGGL((div_rows_kernel<BLOCK, DIV, true>), grid, block, 0, stream, a);
-  else
-    hipLaunchKernelGGL((div_rows_kernel<BLOCK, DIV, false>), grid, block, 0, stream, a);
-  return hipGetLastError();
+  if (want_grad) return launch_kernel(div_rows_kernel<BLOCK, DIV, true>, grid, block, 0, stream, a);
+  return launch_kernel(div_rows_kernel<BLOCK, DIV, false>, grid, block, 0, stream, a);
 }
 
 template <int DIV>

@@ -42,6 +42,20 @@ struct KdArgs {
   int32_t spin_limit;    // polls before a waiting workgroup gives up
 };
 
+// Enqueues `kernel` and returns this launch's own status: the thread's pending HIP error (something an earlier call
+// of the application left behind) is neither reported as ours nor cleared.  Arguments are converted to the kernel's
+// parameter types.
+template <class T>
+struct launch_param {
+  using type = T;
+};
+template <class... Params>
+inline hipError_t launch_kernel(void (*kernel)(Params...), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream,
+                                typename launch_param<Params>::type... params) {
+  void* argv[] = {const_cast<void*>(static_cast<const void*>(&params))...};
+  return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, argv, lds_bytes, stream);
+}
+
 hipError_t launch_kd(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream);
 
 // divergences other than the forward KL, dense teacher (npd_div_kernels.hip)

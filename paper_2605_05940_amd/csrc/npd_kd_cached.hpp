@@ -612,8 +612,7 @@ static hipError_t launch_cached_lse1(const KdArgs& a, hipStream_t stream) {
     // persistent: one workgroup per compute unit (a workgroup takes a CU's whole register file)
     const int64_t cus = compute_units();
     const unsigned grid = (unsigned)(!PERSIST || a.T < cus ? a.T : cus);
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(CB), lds_bytes, stream, a);
-    return hipGetLastError();
+    return launch_kernel(kernel, dim3(grid), dim3(CB), lds_bytes, stream, a);
   };
   if (a.need_lse1) return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, true, PERSIST, DIVK, CB, SHORT>);
   return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, false, PERSIST, DIVK, CB, SHORT>);

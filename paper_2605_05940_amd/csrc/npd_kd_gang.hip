@@ -37,12 +37,11 @@ size_t gang_workspace_bytes(int64_t T, int32_t V, bool lse1) {
 template <bool LSE1, int DIVK>
 static hipError_t launch_gang(const KdArgs& a, hipStream_t stream) {
   const size_t words = (size_t)a.T * a.gang * gang_words(LSE1 ? 4 : 2);
-  hipLaunchKernelGGL(gang_clear_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream, a.ws, words);
-  hipError_t e = hipGetLastError();
+  const hipError_t e =
+      launch_kernel(gang_clear_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream, a.ws, words);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((kd_gang_kernel<kGangK, kDense, LSE1, DIVK>), dim3((unsigned)(a.T * a.gang)), dim3(kGangThreads), 0,
-                     stream, a);
-  return hipGetLastError();
+  return launch_kernel(kd_gang_kernel<kGangK, kDense, LSE1, DIVK>, dim3((unsigned)(a.T * a.gang)), dim3(kGangThreads), 0,
+                       stream, a);
 }
 
 hipError_t launch_kd_gang(const KdArgs& a0, hipStream_t stream) {

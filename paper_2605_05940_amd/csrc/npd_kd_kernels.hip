@@ -210,11 +210,8 @@ __global__ __launch_bounds__(BLOCK) void kd_rows_kernel(const KdArgs a) {
 template <int BLOCK, int TEACHER>
 static hipError_t launch_block(const KdArgs& a, bool want_grad, hipStream_t stream) {
   const dim3 grid((unsigned)a.T), block(BLOCK);
-  if (want_grad)
-    hipLaunchKernelGGL((kd_rows_kernel<BLOCK, TEACHER, true>), grid, block, 0, stream, a);
-  else
-    hipLaunchKernelGGL((kd_rows_kernel<BLOCK, TEACHER, false>), grid, block, 0, stream, a);
-  return hipGetLastError();
+  if (want_grad) return launch_kernel(kd_rows_kernel<BLOCK, TEACHER, true>, grid, block, 0, stream, a);
+  return launch_kernel(kd_rows_kernel<BLOCK, TEACHER, false>, grid, block, 0, stream, a);
 }
 
 template <int TEACHER>

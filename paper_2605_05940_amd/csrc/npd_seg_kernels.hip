@@ -56,14 +56,12 @@ hipError_t launch_segment_reduce(int64_t T, int32_t S, const float* values, cons
   if (token_to_sample && T > 0) {
     const int64_t want = (T + kSegBlock - 1) / kSegBlock;
     const unsigned blocks = (unsigned)(want < 4096 ? want : 4096);
-    hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks), dim3(kSegBlock), 0, stream, token_to_sample, T, -1);
-    hipError_t e = hipGetLastError();
+    const hipError_t e = launch_kernel(fill_i32_kernel, dim3(blocks), dim3(kSegBlock), 0, stream, token_to_sample, T, -1);
     if (e != hipSuccess) return e;
   }
   if (S > 0) {
-    hipLaunchKernelGGL(segment_reduce_kernel, dim3((unsigned)S), dim3(kSegBlock), 0, stream, T, values, mask, cu,
-                       seg_sum, seg_count, seg_mean, token_to_sample, status);
-    return hipGetLastError();
+    return launch_kernel(segment_reduce_kernel, dim3((unsigned)S), dim3(kSegBlock), 0, stream, T, values, mask, cu,
+                         seg_sum, seg_count, seg_mean, token_to_sample, status);
   }
   return hipSuccess;
 }
@@ -112,16 +110,14 @@ hipError_t launch_delta_ifd(int32_t P, int32_t S, const float* ms, const float* 
                             float* ifd_t, float* delta, uint8_t* zone, uint8_t* keep, int32_t* keep_count,
                             hipStream_t stream) {
   if (keep_count) {
-    hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(kSegBlock), 0, stream, keep_count, (int64_t)1, 0);
-    hipError_t e = hipGetLastError();
+    const hipError_t e = launch_kernel(fill_i32_kernel, dim3(1), dim3(kSegBlock), 0, stream, keep_count, (int64_t)1, 0);
     if (e != hipSuccess) return e;
   }
   if (P > 0) {
     const int want = (P + kSegBlock - 1) / kSegBlock;
     const unsigned blocks = (unsigned)(want < 1024 ? want : 1024);
-    hipLaunchKernelGGL(delta_ifd_kernel, dim3(blocks), dim3(kSegBlock), 0, stream, P, S, ms, mt, cnt, pc, pu, lo, hi,
-                       flags, ifd_s, ifd_t, delta, zone, keep, keep_count);
-    return hipGetLastError();
+    return launch_kernel(delta_ifd_kernel, dim3(blocks), dim3(kSegBlock), 0, stream, P, S, ms, mt, cnt, pc, pu, lo, hi,
+                         flags, ifd_s, ifd_t, delta, zone, keep, keep_count);
   }
   return hipSuccess;
 }

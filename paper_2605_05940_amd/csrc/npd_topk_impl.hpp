@@ -561,15 +561,13 @@ hipError_t launch_stream(const TopkArgs& a, hipStream_t stream) {
   // visiting order: the first kSample groups spread over the row
   int step = ngroups > kSample ? (ngroups + kSample - 1) / kSample : 1;
   while (gcd_int(step, ngroups) != 1) ++step;
-  hipLaunchKernelGGL((teacher_topk_stream_kernel<kWindow, kSample>), dim3((unsigned)a.T), dim3(kTB), 0, stream, a,
-                     ngroups, step % ngroups == 0 ? 1 : step % ngroups);
-  return hipGetLastError();
+  return launch_kernel(teacher_topk_stream_kernel<kWindow, kSample>, dim3((unsigned)a.T), dim3(kTB), 0, stream, a,
+                       ngroups, step % ngroups == 0 ? 1 : step % ngroups);
 }
 
 #if NPD_TOPK_ANY_SHAPE
 hipError_t launch_any(const TopkArgs& a, hipStream_t stream) {
-  hipLaunchKernelGGL(teacher_topk_kernel, dim3((unsigned)a.T), dim3(kTB), 0, stream, a);
-  return hipGetLastError();
+  return launch_kernel(teacher_topk_kernel, dim3((unsigned)a.T), dim3(kTB), 0, stream, a);
 }
 #endif
 

@@ -137,6 +137,57 @@ def test_kd_argument_validation(lib):
     assert _kd(lib, _desc(teacher_stride=2**61)) == E_SHAPE
 
 
+def test_every_output_is_checked_against_every_input_and_output(lib):
+    """No output may overlap an input (other than the declared in-place gradient) or another output."""
+    L, K = FAKE + 0x800000, FAKE + 0x400000                         # labels, kd_tok: 64 bytes each
+    assert _kd(lib, _desc(), kd=FAKE + 64) == E_ALIAS               # kd_tok inside the student logits
+    assert _kd(lib, _desc(), kd=FAKE + 0x100000) == E_ALIAS         # ... inside the teacher logits
+    assert _kd(lib, _desc(), kd=FAKE + 0x200000 + 12) == E_ALIAS    # ... over the loss mask
+    assert _kd(lib, _desc(), labels=L, nll=L + 32) == E_ALIAS       # nll_tok over the labels
+    assert _kd(lib, _desc(), labels=L, kd=K, nll=K + 60) == E_ALIAS  # two outputs share four bytes
+    assert _kd(lib, _desc(), labels=L, kd=K, tnll=K) == E_ALIAS
+    assert _kd(lib, _desc(), lse=FAKE + 0x300000 + 8) == E_ALIAS    # lse_tok inside the gradient
+    assert lib.npd_kd_loss_fwd_bwd(ctypes.byref(_desc()), FAKE, FAKE + 0x100000, None, None, None, FAKE + 0x200000,
+                                   FAKE + 0x300000, K, None, None, None, K + 4, None, 0, None) == E_ALIAS  # dev_status
+    tk = _desc(teacher_kind=binding.NPD_TEACHER_TOPK, topk=8)
+    assert _kd(lib, tk, teacher=None, idx=FAKE + 0x600000, val=FAKE + 0x700000, kd=FAKE + 0x600000 + 16) == E_ALIAS
+    assert _kd(lib, tk, teacher=None, idx=FAKE + 0x600000, val=FAKE + 0x700000, grad=FAKE + 0x700000 - 64) == E_ALIAS
+    # the other entry points
+    t, idx, val = FAKE, FAKE + 0x100000, FAKE + 0x200000
+    assert lib.npd_teacher_topk(16, 64, 64, 8, 0, t, None, t + 128, val, None) == E_ALIAS
+    assert lib.npd_teacher_topk(16, 64, 64, 8, 0, t, None, idx, idx + 256, None) == E_ALIAS
+    assert lib.npd_teacher_topk(16, 64, 64, 8, 0, t, idx + 8, idx, val, None) == E_ALIAS   # record over the mask
+    v, m, cu, o = FAKE, FAKE + 0x1000, FAKE + 0x2000, FAKE + 0x3000
+    assert lib.npd_segment_reduce(8, 2, v, m, cu, v + 16, None, None, None, None, None) == E_ALIAS
+    assert lib.npd_segment_reduce(8, 2, v, m, cu, o, o + 4, None, None, None, None) == E_ALIAS
+    assert lib.npd_segment_reduce(8, 2, v, m, cu, None, None, None, m, None, None) == E_ALIAS
+    ins = [FAKE, FAKE + 0x1000, FAKE + 0x2000, FAKE + 0x3000, FAKE + 0x4000]
+    assert lib.npd_delta_ifd_score(2, 4, *ins, 0.0, 1.0, 0, ins[0], None, None, None, None, None, None) == E_ALIAS
+    assert lib.npd_delta_ifd_score(2, 4, *ins, 0.0, 1.0, 0, o, o + 4, None, None, None, None, None) == E_ALIAS
+    assert lib.npd_delta_ifd_score(2, 4, *ins, 0.0, 1.0, 0, None, None, None, o, o + 1, None, None) == E_ALIAS
+
+
+def test_workspace_rules(lib):
+    """Long rows with a dense teacher and a gradient exchange partial sums through a workspace: its size, what
+    happens without it."""
+    far = 1 << 44                                                   # fake buffers of several GB each, far apart
+    big = dict(n_tokens=64, vocab=151936, student_stride=151936, teacher_stride=151936)
+    args = dict(student=far, teacher=2 * far, mask=3 * far, grad=4 * far)
+    d = _desc(**big)
+    need = lib.npd_workspace_bytes(ctypes.byref(d))
+    assert need == 64 * 8 * 32                                      # 8 slices of <= 20,480 logits, 32 bytes each
+    assert lib.npd_workspace_bytes(ctypes.byref(_desc(tau=2.0, **big))) == 64 * 8 * 64
+    assert lib.npd_workspace_bytes(ctypes.byref(_desc(flags=binding.NPD_FLAG_NO_WORKSPACE, **big))) == 0
+    assert lib.npd_workspace_bytes(ctypes.byref(_desc(flags=binding.NPD_FLAG_FWD_ONLY, **big))) == 0
+    assert lib.npd_workspace_bytes(ctypes.byref(_desc(vocab=20480, n_tokens=64, student_stride=20480,
+                                                     teacher_stride=20480))) == 0   # one slice: nothing to exchange
+    assert lib.npd_workspace_bytes(ctypes.byref(_desc(tau=-1.0, **big))) == 0       # invalid descriptor
+    assert _kd(lib, d, **args) == E_WS                              # no workspace
+    assert _kd(lib, d, ws=5 * far, ws_bytes=need - 1, **args) == E_WS
+    assert _kd(lib, d, ws=5 * far + 128, ws_bytes=need, **args) == E_WS             # not 256-byte aligned
+    assert _kd(lib, d, ws=4 * far + 256, ws_bytes=need, **args) == E_ALIAS          # inside the gradient
+
+
 def test_segment_and_ifd_argument_validation(lib):
     assert lib.npd_segment_reduce(-1, 1, *([FAKE] * 8), None) == E_SHAPE
     assert lib.npd_segment_reduce(8, -1, *([FAKE] * 8), None) == E_SHAPE
