@@ -197,6 +197,30 @@ npd_status npd_kd_loss_fwd_bwd(const npd_kd_desc* desc, const void* student_logi
                                float* teacher_nll_tok, float* lse_tok, int32_t* dev_status, void* workspace,
                                size_t workspace_bytes, void* stream);
 
+/*
+ * The same call for callers that cannot allocate or hold a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Arguments, results and errors are those of npd_kd_loss_fwd_bwd without
+ * `workspace` / `workspace_bytes`; the scratch record comes from a fixed array of NPD_NOALLOC_WORKSPACE_BYTES bytes
+ * of device memory that is part of the library's code object (each GPU the library runs on holds its own copy until
+ * the process ends).  The call allocates and frees nothing.
+ *
+ *   - A call whose npd_workspace_bytes(desc) exceeds NPD_NOALLOC_WORKSPACE_BYTES returns NPD_ERR_WORKSPACE and
+ *     enqueues nothing (at tau = 1 the array covers n_tokens * ceil(vocab / 20480) <= 524,288, e.g. 65,536 positions
+ *     of a 151,936-entry vocabulary; at tau != 1 half of that).  Pass NPD_FLAG_NO_WORKSPACE, or use
+ *     npd_kd_loss_fwd_bwd with a workspace, for larger batches.
+ *   - Every call on a GPU uses that GPU's one array (cleared by the call itself before use): calls that overlap in
+ *     time on one GPU -- two streams, two host threads -- race on it and give wrong results.  Order them on one
+ *     stream.
+ *   - The first call on a device asks the runtime for the array's address (no allocation); make it outside stream
+ *     capture.
+ */
+#define NPD_NOALLOC_WORKSPACE_BYTES (16u << 20)
+npd_status npd_kd_loss_fwd_bwd_noalloc(const npd_kd_desc* desc, const void* student_logits,
+                                       const void* teacher_dense, const int32_t* teacher_idx,
+                                       const float* teacher_val, const int32_t* labels, const uint8_t* loss_mask,
+                                       void* grad_out, float* kd_tok, float* nll_tok, float* teacher_nll_tok,
+                                       float* lse_tok, int32_t* dev_status, void* stream);
+
 /* npd_teacher_topk flags */
 enum { NPD_TOPK_LOG_PROBS = 1u /* values = log-softmax of the k selected logits instead of the logits */ };
 

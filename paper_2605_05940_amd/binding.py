@@ -21,9 +21,11 @@ NPD_DEV_BAD_LABEL, NPD_DEV_BAD_TOPK_INDEX, NPD_DEV_BAD_CU_SEQLENS, NPD_DEV_GANG_
 NPD_ZONE_DEGENERATE, NPD_ZONE_PROXIMAL, NPD_ZONE_DISCONNECT, NPD_ZONE_INVALID = 0, 1, 2, 3
 NPD_IFD_REQUIRE_TEACHER_LE_1 = 1
 NPD_TOPK_LOG_PROBS = 1
+NOALLOC_WORKSPACE_BYTES = 16 << 20   # NPD_NOALLOC_WORKSPACE_BYTES
 
 EXPORTS = ("npd_version", "npd_status_string", "npd_workspace_bytes", "npd_kd_loss_fwd_bwd",
-           "npd_segment_reduce", "npd_delta_ifd_score", "npd_teacher_topk", "npd_debug_gang_spin_limit")
+           "npd_segment_reduce", "npd_delta_ifd_score", "npd_teacher_topk", "npd_debug_gang_spin_limit",
+           "npd_kd_loss_fwd_bwd_noalloc")
 
 
 class NpdError(RuntimeError):
@@ -62,6 +64,8 @@ def load() -> ctypes.CDLL:
         L.npd_workspace_bytes.argtypes = [ctypes.POINTER(KdDesc)]
         L.npd_kd_loss_fwd_bwd.restype = ctypes.c_int
         L.npd_kd_loss_fwd_bwd.argtypes = [ctypes.POINTER(KdDesc)] + [_vp] * 13 + [ctypes.c_size_t, _vp]
+        L.npd_kd_loss_fwd_bwd_noalloc.restype = ctypes.c_int
+        L.npd_kd_loss_fwd_bwd_noalloc.argtypes = [ctypes.POINTER(KdDesc)] + [_vp] * 13
         L.npd_segment_reduce.restype = ctypes.c_int
         L.npd_segment_reduce.argtypes = [ctypes.c_int64, ctypes.c_int32] + [_vp] * 9
         L.npd_delta_ifd_score.restype = ctypes.c_int
@@ -111,14 +115,16 @@ def npd_kd_loss_fwd_bwd(student_logits: torch.Tensor, loss_mask: torch.Tensor, *
                         grad_out: Optional[torch.Tensor] = None, kd_tok: Optional[torch.Tensor] = None,
                         nll_tok: Optional[torch.Tensor] = None, teacher_nll_tok: Optional[torch.Tensor] = None,
                         lse_tok: Optional[torch.Tensor] = None, dev_status: Optional[torch.Tensor] = None,
-                        workspace: Optional[torch.Tensor] = None, no_workspace: bool = False) -> None:
+                        workspace: Optional[torch.Tensor] = None, no_workspace: bool = False,
+                        noalloc: bool = False) -> None:
     """Enqueue the fused KD loss / gradient on the current stream (see ``npd_kd_loss_fwd_bwd`` in npd.h).
 
     The teacher kind follows from which teacher tensors are given; ``grad_out is None`` means forward
     only; ``grad_out`` sharing storage with ``student_logits`` means the in-place gradient.  ``workspace``:
     a uint8 tensor of at least ``npd_workspace_bytes`` bytes; if it is None one is taken from
     ``workspace_for`` (a per-device tensor that this module keeps and grows).  ``no_workspace`` sets
-    ``NPD_FLAG_NO_WORKSPACE``.
+    ``NPD_FLAG_NO_WORKSPACE``.  ``noalloc`` calls ``npd_kd_loss_fwd_bwd_noalloc`` instead (the library's built-in
+    scratch array; no workspace argument).
     """
     T, V = student_logits.shape
     d = KdDesc()
@@ -148,12 +154,22 @@ def npd_kd_loss_fwd_bwd(student_logits: torch.Tensor, loss_mask: torch.Tensor, *
     if no_workspace:
         flags |= NPD_FLAG_NO_WORKSPACE
     d.flags = flags
-    if workspace is None and not no_workspace:
+    if workspace is None and not no_workspace and not noalloc:
         workspace = workspace_for(int(load().npd_workspace_bytes(ctypes.byref(d))), student_logits.device)
     for name, t, n in (("loss_mask", loss_mask, T), ("labels", labels, T), ("kd_tok", kd_tok, T),
                        ("nll_tok", nll_tok, T), ("teacher_nll_tok", teacher_nll_tok, T), ("lse_tok", lse_tok, T)):
         if t is not None and (t.numel() != n or not t.is_contiguous()):
             raise ValueError(f"{name} must be contiguous with {n} elements")
+    if noalloc:
+        if workspace is not None:
+            raise ValueError("the no-allocation entry point takes no workspace")
+        _check(load().npd_kd_loss_fwd_bwd_noalloc(
+            ctypes.byref(d), _ptr(student_logits, torch.bfloat16), _ptr(teacher_dense, torch.bfloat16),
+            _ptr(teacher_idx, torch.int32), _ptr(teacher_val, torch.float32), _ptr(labels, torch.int32),
+            _ptr(loss_mask, torch.uint8), _ptr(grad_out, torch.bfloat16), _ptr(kd_tok, torch.float32),
+            _ptr(nll_tok, torch.float32), _ptr(teacher_nll_tok, torch.float32), _ptr(lse_tok, torch.float32),
+            _ptr(dev_status, torch.int32), _stream()))
+        return
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().npd_kd_loss_fwd_bwd(
         ctypes.byref(d), _ptr(student_logits, torch.bfloat16), _ptr(teacher_dense, torch.bfloat16),

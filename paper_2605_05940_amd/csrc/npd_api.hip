@@ -3,8 +3,15 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/npd.h"
 #include "npd_internal.hpp"
+
+// Scratch of npd_kd_loss_fwd_bwd_noalloc: one copy per GPU, held from the time the library is loaded on that GPU
+// until the process ends.  In host code the array's name is only a handle; its device address is asked for once per
+// device (hipGetSymbolAddress) and that pointer is what kernels get.
+static __device__ __align__(256) unsigned char scratch[NPD_NOALLOC_WORKSPACE_BYTES];
 
 namespace {
 
@@ -73,6 +80,27 @@ bool any_alias(const Range* in, int n_in, const Range* out, int n_out) {
 
 Range opt_range(const void* p, size_t bytes) { return p ? range_of(p, bytes) : Range{0, 0}; }
 
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> noalloc_scratch_ptr[kMaxDevices];  // zero-initialised
+
+// device address of the current device's scratch array (nullptr and *err set on failure)
+void* noalloc_scratch_address(hipError_t* err) {
+  int dev = 0;
+  *err = hipGetDevice(&dev);
+  if (*err != hipSuccess) return nullptr;
+  if (dev < 0 || dev >= kMaxDevices) {
+    *err = hipErrorInvalidDevice;
+    return nullptr;
+  }
+  void* p = noalloc_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (*err != hipSuccess) return nullptr;
+    noalloc_scratch_ptr[dev].store(p, std::memory_order_release);  // racing host threads store the same address
+  }
+  return p;
+}
 
 // workspace bytes of a call with a valid descriptor
 size_t workspace_bytes_of(const npd_kd_desc& d) {
@@ -252,6 +280,28 @@ npd_status npd_kd_loss_fwd_bwd(const npd_kd_desc* desc, const void* student_logi
                                    grad_out, kd_tok, nll_tok, teacher_nll_tok, lse_tok, dev_status);
     if (b.overlaps_any(range_of(workspace, need))) return NPD_ERR_ALIAS;
     a.ws = static_cast<uint32_t*>(workspace);
+  }
+  const bool want_grad = !(desc->flags & NPD_FLAG_FWD_ONLY);
+  const hipError_t e = npd::launch_kd(a, desc->teacher_kind, want_grad, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? NPD_OK : NPD_ERR_HIP;
+}
+
+npd_status npd_kd_loss_fwd_bwd_noalloc(const npd_kd_desc* desc, const void* student_logits,
+                                       const void* teacher_dense, const int32_t* teacher_idx,
+                                       const float* teacher_val, const int32_t* labels, const uint8_t* loss_mask,
+                                       void* grad_out, float* kd_tok, float* nll_tok, float* teacher_nll_tok,
+                                       float* lse_tok, int32_t* dev_status, void* stream) {
+  npd::KdArgs a{};
+  size_t need = 0;
+  const npd_status st = check_kd_call(desc, student_logits, teacher_dense, teacher_idx, teacher_val, labels, loss_mask,
+                                      grad_out, kd_tok, nll_tok, teacher_nll_tok, lse_tok, dev_status, &a, &need);
+  if (st != NPD_OK) return st;
+  if (need > (size_t)NPD_NOALLOC_WORKSPACE_BYTES) return NPD_ERR_WORKSPACE;  // the built-in scratch is too small
+  if (need > 0) {
+    hipError_t e = hipSuccess;
+    void* scratch = noalloc_scratch_address(&e);
+    if (!scratch) return NPD_ERR_HIP;
+    a.ws = static_cast<uint32_t*>(scratch);
   }
   const bool want_grad = !(desc->flags & NPD_FLAG_FWD_ONLY);
   const hipError_t e = npd::launch_kd(a, desc->teacher_kind, want_grad, static_cast<hipStream_t>(stream));

@@ -169,7 +169,7 @@ def test_every_output_is_checked_against_every_input_and_output(lib):
 
 def test_workspace_rules(lib):
     """Long rows with a dense teacher and a gradient exchange partial sums through a workspace: its size, what
-    happens without it."""
+    happens without it, and the limit of the entry point that brings its own."""
     far = 1 << 44                                                   # fake buffers of several GB each, far apart
     big = dict(n_tokens=64, vocab=151936, student_stride=151936, teacher_stride=151936)
     args = dict(student=far, teacher=2 * far, mask=3 * far, grad=4 * far)
@@ -186,6 +186,18 @@ def test_workspace_rules(lib):
     assert _kd(lib, d, ws=5 * far, ws_bytes=need - 1, **args) == E_WS
     assert _kd(lib, d, ws=5 * far + 128, ws_bytes=need, **args) == E_WS             # not 256-byte aligned
     assert _kd(lib, d, ws=4 * far + 256, ws_bytes=need, **args) == E_ALIAS          # inside the gradient
+    # the entry point with built-in scratch refuses what its array cannot hold, before any HIP call
+    limit = 16 << 20
+    assert binding.NOALLOC_WORKSPACE_BYTES == limit
+    too_many = limit // (8 * 32) + 1
+    dn = _desc(**dict(big, n_tokens=too_many))
+    assert lib.npd_workspace_bytes(ctypes.byref(dn)) > limit
+    call = lambda desc, **kw: lib.npd_kd_loss_fwd_bwd_noalloc(
+        ctypes.byref(desc), kw.get("student", far), 2 * far, None, None, None, 3 * far, 4 * far, None, None, None,
+        None, None, None)
+    assert call(dn) == E_WS
+    assert call(_desc(tau=0.0, **big)) == E_VALUE                   # same argument checks as the main entry point
+    assert call(d, student=None) == E_NULL
 
 
 def test_segment_and_ifd_argument_validation(lib):
