@@ -61,6 +61,8 @@ def main():
                     help="kd: the fused loss step (default); teacher_topk: the teacher-side top-k record; membench: "
                          "arithmetic-free streaming kernels over arrays of the workload's size (practical ceilings)")
     ap.add_argument("--topk", type=int, default=64, help="k of --op teacher_topk")
+    ap.add_argument("--all-scored", action="store_true",
+                    help="score every position (no prompt or padding rows): the rate of a batch without write-only rows")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run a plain 2 GiB device-to-device copy (untimed), so that a rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE run holds a kernel of known traffic to scale the counters by")
@@ -80,6 +82,8 @@ def main():
         return bench_memory_system(args, synth, dev)
     w = synth.config(args.config)
     lay = synth.make_layout(w)
+    if args.all_scored:
+        lay.loss_mask[:] = 1
     T, V, S = w.n_tokens, w.vocab, lay.n_segments
 
     s = torch.empty((T, V), dtype=torch.bfloat16, device=dev)
@@ -209,9 +213,9 @@ def main():
 
 def bench_memory_system(args, synth, dev):
     """What the memory system gives each access mix of the KD kernels: arithmetic-free row-streaming kernels
-    (``paper_2605_05940_amd/membench``) over three arrays the size of the workload's logits, every workgroup size
+    (``bench_membench/``) over three arrays the size of the workload's logits, every workgroup size
     with and without the non-temporal hint, plus the runtime's own fill and copy.  Context for `roofline.frac`."""
-    from paper_2605_05940_amd import membench
+    import bench_membench as membench
     membench.load()
     w = synth.config(args.config)
     rows, groups = w.n_tokens, w.vocab // 8
@@ -252,17 +256,24 @@ def bench_memory_system(args, synth, dev):
             best = max(variants, key=variants.get)
             patterns[f"{name}/{order}"] = {"best_gbs": variants[best], "best_variant": best,
                                            "frac_of_peak": variants[best] / HBM_PEAK_GBS, "variants_gbs": variants}
+    need = membench.gang_scratch_bytes(rows, groups)
+    if need:
+        scratch = torch.empty(need, dtype=torch.uint8, device=dev)
+        gbs = rate(lambda: membench.run_gang(a, b, o, scratch, rows, groups), 3)
+        patterns["gang_read_2_then_write_1/rows"] = {"best_gbs": gbs, "best_variant": "256_nt", "frac_of_peak": gbs / HBM_PEAK_GBS,
+                                                     "variants_gbs": {"256_nt": gbs}}
     runtime = {"fill_gbs": rate(lambda: o.zero_(), 1), "copy_gbs": rate(lambda: o.copy_(a), 2)}
     print(json.dumps({
         "metric": "memory_system_stream_rate_2_reads_1_write",
-        "value": max(patterns[p]["best_gbs"] for p in ("read_2_write_1/rows", "row_read_2_then_write_1/rows")
-                     if p in patterns),
+        "value": max(patterns[p]["best_gbs"] for p in ("read_2_write_1/rows", "row_read_2_then_write_1/rows",
+                                                       "gang_read_2_then_write_1/rows") if p in patterns),
         "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True,
         "data": "synthetic", "dtype": "u8",
         "config": {"workload": f"three arrays of {rows} rows x {groups * 16} bytes ({w.name}'s logit tensors), 128-bit "
                                f"accesses; order rows = one workgroup per row (4 requests in flight per thread), "
-                               f"address = one short-lived workgroup per consecutive run of groups; value = best "
-                               f"2-reads-1-write rate in row order (the order a row-reduction kernel can produce)"},
+                               f"address = one short-lived workgroup per consecutive run of groups; gang = a row shared by "
+                               f"short-lived workgroups that exchange before they write; value = best 2-reads-1-write "
+                               f"rate among the orders a row-reduction kernel can produce"},
         "peak_gbs": HBM_PEAK_GBS, "patterns": patterns, "runtime": runtime}))
 
 

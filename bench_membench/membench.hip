@@ -2,7 +2,8 @@
 // kernels (read only; write only; one read + one write; two reads + one write), in two orders: the one those kernels
 // use -- one workgroup per row of 16-byte groups, a thread owns every THREADS-th group, several loads in flight per
 // thread -- and, for comparison, plain address order (one short-lived workgroup per THREADS consecutive groups), which
-// a kernel that must reduce over a row before it can write cannot produce.  Their rates are what the KD kernels'
+// a kernel that must reduce over a row before it can write cannot produce -- unless several workgroups share a row: the
+// row-gang pattern (npd_membench_gang) is the order of the row-gang KD kernels.  Their rates are what the KD kernels'
 // roofline fractions are read against; they are a measurement aid, not part of the loss path, and live in a library
 // of their own (libnpd_membench.so).
 #include <hip/hip_runtime.h>
@@ -100,6 +101,73 @@ __global__ __launch_bounds__(THREADS) void row_then_write_kernel(const u32x4* __
   }
 }
 
+// Two reads + one write by row gangs: a row is shared by `gang` short-lived workgroups of 256 threads, consecutive
+// workgroups are consecutive slices of a row; each reads its slice of both inputs into registers (K groups per thread
+// and array, kept apart as a kernel that needs both values would), posts six words to a scratch record, waits (a
+// bounded number of polls) until all slices of its row have posted, and then writes its slice -- the access order of
+// the row-gang KD kernels without their arithmetic.  Posted words carry their own validity: the record is cleared to
+// kGangEmpty by gang_clear_kernel before each pass.
+constexpr uint32_t kGangEmpty = 0xffffffffu;
+constexpr int kGangWords = 8, kGangUsed = 6, kGangMax = 32, kGangK = 10;
+
+__global__ __launch_bounds__(256) void gang_clear_kernel(uint32_t* p, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = kGangEmpty;
+}
+
+template <int K>
+__global__ __launch_bounds__(256, 4) void gang_rows_kernel(const u32x4* __restrict__ a, const u32x4* __restrict__ b,
+                                                           u32x4* __restrict__ o, int row_groups, int slice_groups,
+                                                           int gang, uint32_t* scratch, int spin_limit) {
+  __shared__ uint32_t xch[kGangMax * kGangWords];
+  __shared__ uint32_t red[4];
+  const int row = blockIdx.x / gang, slice = blockIdx.x % gang, tid = threadIdx.x;
+  const size_t base = (size_t)row * row_groups;
+  const int g0 = slice * slice_groups;
+  const int g1 = g0 + slice_groups < row_groups ? g0 + slice_groups : row_groups;
+  u32x4 ra[K], rb[K];
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    const int g = g0 + k * 256 + tid;
+    ra[k] = rb[k] = u32x4{0, 0, 0, 0};
+    if (g < g1) {
+      ra[k] = __builtin_nontemporal_load(a + base + g);
+      rb[k] = __builtin_nontemporal_load(b + base + g);
+    }
+  }
+  uint32_t f = 0;  // something that depends on every load of the thread
+#pragma unroll
+  for (int k = 0; k < K; ++k) f ^= ra[k].x ^ rb[k].y;
+  for (int off = 32; off > 0; off >>= 1) f ^= __shfl_xor(f, off, 64);
+  if ((tid & 63) == 0) red[tid >> 6] = f;
+  __syncthreads();
+  f = red[0] ^ red[1] ^ red[2] ^ red[3];
+  if (tid < kGangUsed) {
+    uint32_t w = f + tid;
+    if (w == kGangEmpty) w = 0;
+    __hip_atomic_store(scratch + ((size_t)blockIdx.x) * kGangWords + tid, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  for (int w = tid; w < gang * kGangUsed; w += 256) {
+    const int s = w / kGangUsed, j = w - s * kGangUsed;
+    const uint32_t* p = scratch + ((size_t)row * gang + s) * kGangWords + j;
+    uint32_t v;
+    int spins = 0;
+    while ((v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) == kGangEmpty && ++spins <= spin_limit)
+      __builtin_amdgcn_s_sleep(8);
+    xch[s * kGangWords + j] = v;
+  }
+  __syncthreads();
+  uint32_t mix = 0;
+  for (int s = 0; s < gang; ++s) mix |= xch[s * kGangWords] & 0u;  // the stores depend on the exchange; adds nothing
+#pragma unroll
+  for (int k = K - 1; k >= 0; --k) {
+    const int g = g0 + k * 256 + tid;
+    u32x4 v = ra[k] ^ rb[k];
+    v.x ^= mix;
+    if (g < g1) __builtin_nontemporal_store(v, o + base + g);
+  }
+}
+
 template <int PATTERN, int THREADS, bool NT>
 hipError_t launch(int order, const void* a, const void* b, void* o, int64_t rows, int row_groups,
                   hipStream_t stream) {
@@ -172,6 +240,34 @@ int npd_membench_run(int pattern, int order, int threads, int nontemporal, const
     case kRowRead2ThenWrite1: return (int)launch_threads<kRowRead2ThenWrite1>(order, threads, nt, a, b, o, rows, row_groups, s);
     default: return (int)hipErrorInvalidValue;
   }
+}
+
+// Bytes of scratch npd_membench_gang needs for `rows` rows of `row_groups` groups (0: the shape is not supported).
+size_t npd_membench_gang_scratch_bytes(int64_t rows, int32_t row_groups) {
+  if (rows <= 0 || row_groups <= 0) return 0;
+  const int gang = (row_groups + kGangK * 256 - 1) / (kGangK * 256);
+  if (gang > kGangMax || rows * gang > 0x7fffffffLL) return 0;
+  return (size_t)rows * gang * kGangWords * sizeof(uint32_t);
+}
+
+// Enqueues one pass of the row-gang pattern (two reads + one write; see gang_rows_kernel) over `rows` rows of
+// `row_groups` 16-byte groups: device arrays a, b, o as in npd_membench_run, `scratch` a device buffer of
+// npd_membench_gang_scratch_bytes() bytes.  Returns 0 or a hipError_t value (invalid arguments: nothing enqueued).
+int npd_membench_gang(const void* a, const void* b, void* o, int64_t rows, int32_t row_groups, void* scratch,
+                      void* stream) {
+  const size_t bytes = npd_membench_gang_scratch_bytes(rows, row_groups);
+  if (!a || !b || !o || !scratch || bytes == 0) return (int)hipErrorInvalidValue;
+  if (((uintptr_t)a | (uintptr_t)b | (uintptr_t)o | (uintptr_t)scratch) & 15u) return (int)hipErrorInvalidValue;
+  const int gang = (row_groups + kGangK * 256 - 1) / (kGangK * 256);
+  const int slice_groups = (row_groups + gang - 1) / gang;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t words = bytes / sizeof(uint32_t);
+  hipLaunchKernelGGL(gang_clear_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, s,
+                     static_cast<uint32_t*>(scratch), words);
+  hipLaunchKernelGGL((gang_rows_kernel<kGangK>), dim3((unsigned)(rows * gang)), dim3(256), 0, s,
+                     static_cast<const u32x4*>(a), static_cast<const u32x4*>(b), static_cast<u32x4*>(o), row_groups,
+                     slice_groups, gang, static_cast<uint32_t*>(scratch), 1 << 20);
+  return (int)hipGetLastError();
 }
 
 }  // extern "C"

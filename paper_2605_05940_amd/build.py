@@ -10,8 +10,6 @@ import tempfile
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libnpd.so")
-MEMBENCH_SRC = os.path.join(HERE, "membench", "membench.hip")
-MEMBENCH_LIB = os.path.join(HERE, "membench", "libnpd_membench.so")
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
@@ -28,9 +26,8 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(verbose: bool = False, extra=(), out: str = LIB, jobs: int = 6, membench: bool = True) -> str:
-    """Every source becomes an object of its own (in parallel), then one shared library; the memory-system
-    benchmark kernels (``membench/``) become a small library of their own."""
+def build(verbose: bool = False, extra=(), out: str = LIB, jobs: int = 6) -> str:
+    """Every source becomes an object of its own (in parallel), then one shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = tempfile.mkdtemp(prefix="npd_build_")
     try:
@@ -42,14 +39,11 @@ def build(verbose: bool = False, extra=(), out: str = LIB, jobs: int = 6, memben
             subprocess.check_call(cmd)
             return obj
         with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as pool:
-            todo = sources() + ([MEMBENCH_SRC] if membench else [])
-            objs = list(pool.map(compile_one, todo))
-        links = [(out, objs[:len(sources())])] + ([(MEMBENCH_LIB, objs[-1:])] if membench else [])
-        for lib, parts in links:
-            cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", lib, *parts]
-            if verbose:
-                print(" ".join(cmd), flush=True)
-            subprocess.check_call(cmd)
+            objs = list(pool.map(compile_one, sources()))
+        cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", out, *objs]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
     finally:
         shutil.rmtree(tmp, ignore_errors=True)
     return out

@@ -57,17 +57,13 @@ static RowShape forward_grad_shape(const KdArgs& a, int teacher_kind) {
 // kept: threads per workgroup by row length.  Measured (32,768 rows, dense forward-only, % of 8 TB/s, 1024 / 512 /
 // 256 threads): V = 32,000: 50 / 75 / 84, 65,536: 79 / 88 / 85, 100,352: 87 / 87 / 85, 128,256: 88 / 87 / 85,
 // 151,936: 87 / 87 / 84, 262,144: 84 / 86 / 81.
-#ifndef NPD_FWD_CB_A
-#define NPD_FWD_CB_A 5120   // up to this many 128-bit groups per row: 256 threads
-#endif
-#ifndef NPD_FWD_CB_B
-#define NPD_FWD_CB_B 13000  // up to this many: 512 threads; beyond: 1024
-#endif
+constexpr int kForwardGroups256 = 5120;   // up to this many 128-bit groups per row: 256 threads
+constexpr int kForwardGroups512 = 13000;  // up to this many: 512 threads; beyond: 1024
 static int forward_only_threads(const KdArgs& a) {
   const int nvec = a.nvec_s;
   if (nvec < 1024) return 0;
-  if (nvec <= NPD_FWD_CB_A) return 256;
-  if (nvec <= NPD_FWD_CB_B) return 512;
+  if (nvec <= kForwardGroups256) return 256;
+  if (nvec <= kForwardGroups512) return 512;
   return 1024;
 }
 

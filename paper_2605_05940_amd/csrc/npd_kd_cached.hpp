@@ -19,6 +19,8 @@
 // npd_kd_kernels.hip (same helpers, same merge tree).  The same kernel carries the reverse KL (two sweeps) and the
 // skew forms (three sweeps) of the dense-teacher divergences.
 #pragma once
+#include <atomic>
+
 #include "npd_device.hpp"
 #include "npd_internal.hpp"
 
@@ -40,55 +42,35 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t row_rsrc(const uint16_t* row, int nvec) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(row), 0, nvec * 16, 0x00020000);
 }
-// persistent workgroups (NPD_PERSIST) also request the next row's resident student groups during the gradient sweep
-#ifndef NPD_PERSIST_PREFETCH
-#define NPD_PERSIST_PREFETCH true
-#endif
-#ifndef NPD_NT_RESIDENT
-#define NPD_NT_RESIDENT 2
-#endif
-#ifndef NPD_NT_REREAD
-#define NPD_NT_REREAD 2
-#endif
+// Cache-policy bits of the loads (2 = non-temporal).  Measured on 32,768 x 151,936 (one workgroup per row): the hint
+// on loads of groups that stay on chip and on second reads, 4.59 ms against 4.69 ms without; on the first read of a
+// group that will be read again it costs 2 % (the second read then misses L2 more often).
+constexpr int kNtResident = 2;  // loads of groups that stay on chip (registers or LDS) and are not read again
+constexpr int kNtReread = 2;    // the second, last read of a group
 // `once`: the group stays on chip after this load (registers or LDS) and is not read again
 template <int GB = kGroupBytes>
 __device__ __forceinline__ uint4 ld_group(__amdgpu_buffer_rsrc_t r, int voff, int it, bool checked,
                                           bool once = false, bool last = false) {
   u32x4 v;
-  if (once && NPD_NT_RESIDENT)
-    v = checked ? __builtin_amdgcn_raw_buffer_load_b128(r, voff + it * GB, 0, NPD_NT_RESIDENT)
-                : __builtin_amdgcn_raw_buffer_load_b128(r, voff, it * GB, NPD_NT_RESIDENT);
-  else if (last && NPD_NT_REREAD)
-    v = checked ? __builtin_amdgcn_raw_buffer_load_b128(r, voff + it * GB, 0, NPD_NT_REREAD)
-                : __builtin_amdgcn_raw_buffer_load_b128(r, voff, it * GB, NPD_NT_REREAD);
+  if (once && kNtResident)
+    v = checked ? __builtin_amdgcn_raw_buffer_load_b128(r, voff + it * GB, 0, kNtResident)
+                : __builtin_amdgcn_raw_buffer_load_b128(r, voff, it * GB, kNtResident);
+  else if (last && kNtReread)
+    v = checked ? __builtin_amdgcn_raw_buffer_load_b128(r, voff + it * GB, 0, kNtReread)
+                : __builtin_amdgcn_raw_buffer_load_b128(r, voff, it * GB, kNtReread);
   else
     v = checked ? __builtin_amdgcn_raw_buffer_load_b128(r, voff + it * GB, 0, 0)
                 : __builtin_amdgcn_raw_buffer_load_b128(r, voff, it * GB, 0);
   return make_uint4(v.x, v.y, v.z, v.w);
 }
-__device__ __forceinline__ void st_group_stream(__amdgpu_buffer_rsrc_t r, int voff, int it, bool checked,
-                                                const uint4& v) {
-  const u32x4 w = {v.x, v.y, v.z, v.w};
-  if (checked)
-    __builtin_amdgcn_raw_buffer_store_b128(w, r, voff + it * kGroupBytes, 0, 2);  // 2 = non-temporal
-  else
-    __builtin_amdgcn_raw_buffer_store_b128(w, r, voff, it * kGroupBytes, 2);
-}
-
 __device__ __forceinline__ uint4 ld16(const uint16_t* row, int group) {
   return reinterpret_cast<const uint4*>(row)[group];
 }
-#ifndef NPD_NT_STREAM2
-#define NPD_NT_STREAM2 1
-#endif
-// second (last) read of a group of the streamed part
+// second (last) read of a group of the streamed part of a row longer than the cache: with the non-temporal hint
+// (65,536 x 262,144 in place: 17.1 ms against 17.5 ms without)
 __device__ __forceinline__ uint4 ld16_last(const uint16_t* row, int group) {
-#if NPD_NT_STREAM2
   const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row) + group);
   return make_uint4(v.x, v.y, v.z, v.w);
-#else
-  return ld16(row, group);
-#endif
 }
 __device__ __forceinline__ void st16_stream(uint16_t* row, int group, const uint4& v) {
   u32x4 w = {v.x, v.y, v.z, v.w};
@@ -216,14 +198,13 @@ __device__ __forceinline__ void accum8(const uint4& vs, const uint4& vt, float c
 // CB = threads per workgroup (1024, or 512 / 256 for shorter rows, so that a thread still holds 10 .. 19 groups and
 // several rows are in flight per CU).  SHORT: the row may have fewer than CS groups per thread; every group is then
 // range-checked by the buffer hardware and by a per-thread bound on its use.
-template <int CS, int CSR, int CT, int D, int TEACHER, bool GRAD, bool LSE1, bool PERSIST, int DIVK = kForwardKl,
-          int CB = kCB, bool SHORT = false>
+template <int CS, int CSR, int CT, int D, int TEACHER, bool GRAD, bool LSE1, int DIVK = kForwardKl, int CB = kCB,
+          bool SHORT = false>
 __global__ __launch_bounds__(CB, 4) void kd_cached_kernel(const KdArgs a) {
   constexpr int GB = CB * 16;
   static_assert(DIVK == kForwardKl || (TEACHER == kDense && GRAD), "the other divergences need the full teacher row");
   constexpr bool REV = DIVK == kReverseKl;
   constexpr bool SKEW = DIVK == kSkewKl || DIVK == kSkewReverseKl;  // three sweeps: normalisers, D and ubar, gradient
-  static_assert(!SKEW || !PERSIST, "the three-sweep forms are not persistent");
   // groups parked for sweep 2, [CB][LS]: a thread's groups are contiguous, so one base register plus an immediate
   // offset addresses them all
   extern __shared__ uint4 lds_t[];
@@ -239,34 +220,29 @@ __global__ __launch_bounds__(CB, 4) void kd_cached_kernel(const KdArgs a) {
   const int tid = threadIdx.x;
   const int voff = tid * 16;
   const int V = a.V, nvec = a.nvec_s;  // only launched with 16-byte aligned rows: nvec = V / 8
-  const int64_t T = a.T;
-  const int64_t G = gridDim.x;
   const float c = a.c;
   const bool lse1_t = LSE1 && a.tnll != nullptr;
   // without SHORT: launched only for rows of more than (CS - 1) * CB groups, so every one of the first CS groups
   // per thread is full except, when the row has at most CS * CB groups, the last one
   const int nit = (nvec + CB - 1) / CB;  // 128-bit groups per thread
 
-  // A workgroup owns rows blockIdx.x, blockIdx.x + G, ... (one row each unless PERSIST); rows that are not scored
-  // are dealt with on the way (scalars 0, gradient row zero-filled, logits never read).
-  auto next_scored = [&](int64_t r) -> int64_t {
-    while (r < T && !a.mask[r]) {
-      if (tid == 0) {
-        if (a.kd) a.kd[r] = 0.0f;
-        if (a.nll) a.nll[r] = 0.0f;
-        if (a.tnll) a.tnll[r] = 0.0f;
-        if (a.lse) a.lse[r] = 0.0f;
-      }
-      if constexpr (GRAD) {
-        uint16_t* grow0 = a.g + r * a.s_stride;
-        const uint4 z = make_uint4(0, 0, 0, 0);
-        for (int i = tid; i < nvec; i += CB) st16_stream(grow0, i, z);
-        for (int e = nvec * 8 + tid; e < V; e += CB) grow0[e] = 0;
-      }
-      r += G;
+  // One workgroup per row.  A row that is not scored: scalars 0, gradient row zero-filled, logits never read.
+  const int64_t row = blockIdx.x;
+  if (!a.mask[row]) {
+    if (tid == 0) {
+      if (a.kd) a.kd[row] = 0.0f;
+      if (a.nll) a.nll[row] = 0.0f;
+      if (a.tnll) a.tnll[row] = 0.0f;
+      if (a.lse) a.lse[row] = 0.0f;
     }
-    return r;
-  };
+    if constexpr (GRAD) {
+      uint16_t* grow0 = a.g + row * a.s_stride;
+      const uint4 z = make_uint4(0, 0, 0, 0);
+      for (int i = tid; i < nvec; i += CB) st16_stream(grow0, i, z);
+      for (int e = nvec * 8 + tid; e < V; e += CB) grow0[e] = 0;
+    }
+    return;
+  }
 
   uint4 sreg[CSR > 0 ? CSR : 1];  // the first CSR groups of the student row, as loaded (packed bf16)
   uint4 sst[D], tst[D];           // student groups beyond CSR / teacher groups in flight
@@ -275,18 +251,12 @@ __global__ __launch_bounds__(CB, 4) void kd_cached_kernel(const KdArgs a) {
     for (int it = 0; it < CSR; ++it) sreg[it] = ld_group<GB>(rs, voff, it, SHORT || (it) == CS - 1, true);
   };
 
-  int64_t row = next_scored(blockIdx.x);
-  if (PERSIST && NPD_PERSIST_PREFETCH && row < T) request_student(row_rsrc(a.s + row * a.s_stride, nvec));
-
-  while (row < T) {
-    const int64_t nrow = PERSIST ? next_scored(row + G) : T;
+  {
     const uint16_t* srow = a.s + row * a.s_stride;
     const uint16_t* trow = TEACHER == kDense ? a.t + row * a.t_stride : nullptr;
     uint16_t* grow = GRAD ? a.g + row * a.s_stride : nullptr;
     const __amdgpu_buffer_rsrc_t rs = row_rsrc(srow, nvec);
     const __amdgpu_buffer_rsrc_t rt = row_rsrc(TEACHER == kDense ? trow : srow, nvec);
-    // the student row to request while this row's gradient is written (this row again if it is the last)
-    const __amdgpu_buffer_rsrc_t rnext = row_rsrc(a.s + (nrow < T ? nrow : row) * a.s_stride, nvec);
 
     int y = -1;
     float s_y = 0.0f, t_y = 0.0f;
@@ -303,10 +273,9 @@ __global__ __launch_bounds__(CB, 4) void kd_cached_kernel(const KdArgs a) {
 #pragma unroll
     for (int i = 0; i < NS; ++i) acc[i].init();
 
-    // ---- sweep 1, first CS groups per thread: the register-resident student groups are requested first
-    // (or already were, during the previous row); the other student groups and the teacher groups are
-    // requested D ahead of their use
-    if constexpr (!(PERSIST && NPD_PERSIST_PREFETCH)) request_student(rs);
+    // ---- sweep 1, first CS groups per thread: the register-resident student groups are requested first; the
+    // other student groups and the teacher groups are requested D ahead of their use
+    request_student(rs);
 #pragma unroll
     for (int d = 0; d < D; ++d) {
       if constexpr (TEACHER == kDense) tst[d] = ld_group<GB>(rt, voff, d, SHORT || (d) == CS - 1, GRAD ? d < CT : true);
@@ -512,7 +481,6 @@ __global__ __launch_bounds__(CB, 4) void kd_cached_kernel(const KdArgs a) {
       if ((TEACHER == kTopk && bad_index) || (ce && bad_label)) {  // uniform: the row cannot be differentiated
         const uint16_t qnan = 0x7fc0;
         for (int e = tid; e < V; e += CB) grow[e] = qnan;
-        if constexpr (PERSIST && NPD_PERSIST_PREFETCH) request_student(rnext);
       } else {
         // sub-group tail and streamed part first (read most recently), then the first CS groups backwards
         for (int e = nvec * 8 + tid; e < V; e += CB) {
@@ -533,7 +501,6 @@ __global__ __launch_bounds__(CB, 4) void kd_cached_kernel(const KdArgs a) {
           }
         }
         if (k.folded) {  // uniform
-          // a register-resident student group makes room, once used, for the same group of the next row
           if constexpr (SKEW) asm volatile("" ::: "memory");  // see walk_back
 #pragma unroll
           for (int q = 0; q < CS; ++q) {  // the same walk as walk_back, spelled out (register allocation differs)
@@ -560,7 +527,6 @@ __global__ __launch_bounds__(CB, 4) void kd_cached_kernel(const KdArgs a) {
               const uint4 gq = grad8<TEACHER, true, DIVK>(vs, vt, k);
               if ((!SHORT && it < CS - 1) || it * CB + tid < nvec) st16_stream(grow, it * CB + tid, gq);
             }
-            if (PERSIST && NPD_PERSIST_PREFETCH && it < CSR) sreg[it < CSR ? it : 0] = ld_group<GB>(rnext, voff, it, SHORT || (it) == CS - 1);
             __builtin_amdgcn_sched_barrier(0);
           }
         } else {
@@ -572,7 +538,6 @@ __global__ __launch_bounds__(CB, 4) void kd_cached_kernel(const KdArgs a) {
               st16_stream(grow, i, grad8<TEACHER, false, DIVK>(vs, vt, k));
             }
           }
-          if constexpr (PERSIST && NPD_PERSIST_PREFETCH) request_student(rnext);
         }
         if (TEACHER == kTopk || ce) {  // uniform
           // the k support positions and the label position get their final values once the dense stores of the
@@ -595,46 +560,37 @@ __global__ __launch_bounds__(CB, 4) void kd_cached_kernel(const KdArgs a) {
         }
       }
     }
-    row = nrow;
   }
 }
 
-template <int CS, int CSR, int CT, int D, int TEACHER, bool GRAD, bool PERSIST, int DIVK = kForwardKl, int CB = kCB,
-          bool SHORT = false>
+template <int CS, int CSR, int CT, int D, int TEACHER, bool GRAD, int DIVK = kForwardKl, int CB = kCB, bool SHORT = false>
 static hipError_t launch_cached_lse1(const KdArgs& a, hipStream_t stream) {
-  const size_t lds_bytes = CT > 0 ? (size_t)(CT | 1) * CB * sizeof(uint4) : 0;
+  constexpr size_t lds_bytes = CT > 0 ? (size_t)(CT | 1) * CB * sizeof(uint4) : 0;
   auto launch = [&](auto kernel) -> hipError_t {
-    if (lds_bytes > 0) {  // more than the default 64 KB of dynamic LDS has to be asked for (cheap, idempotent)
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-      if (e != hipSuccess) return e;
+    if (lds_bytes > 0) {
+      // more than the default 64 KB of dynamic LDS has to be asked for, once per kernel and device
+      static std::atomic<uint64_t> asked[1];  // bit d: done on device d (devices beyond 63 ask every time)
+      int dev = 0;
+      if (hipGetDevice(&dev) != hipSuccess) dev = 64;
+      if (dev < 0 || dev >= 64 || !((asked[0].load(std::memory_order_acquire) >> dev) & 1u)) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        if (dev >= 0 && dev < 64) asked[0].fetch_or(uint64_t(1) << dev, std::memory_order_release);
+      }
     }
-    // persistent: one workgroup per compute unit (a workgroup takes a CU's whole register file)
-    const int64_t cus = compute_units();
-    const unsigned grid = (unsigned)(!PERSIST || a.T < cus ? a.T : cus);
-    return launch_kernel(kernel, dim3(grid), dim3(CB), lds_bytes, stream, a);
+    return launch_kernel(kernel, dim3((unsigned)a.T), dim3(CB), lds_bytes, stream, a);
   };
-  if (a.need_lse1) return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, true, PERSIST, DIVK, CB, SHORT>);
-  return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, false, PERSIST, DIVK, CB, SHORT>);
+  if (a.need_lse1) return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, true, DIVK, CB, SHORT>);
+  return launch(kd_cached_kernel<CS, CSR, CT, D, TEACHER, GRAD, false, DIVK, CB, SHORT>);
 }
 
-// Tuning knobs of the dense-teacher gradient kernel (measured on MI355X, 32,768 x 151,936): how many student
-// groups per thread stay in registers, how far ahead teacher / non-resident student groups are requested, and
-// whether workgroups are persistent.  Times are flat (+-2 %) for 8..16 resident groups; 12 leaves the register
-// allocator enough room to avoid spills, whose reloads would stall the load pipeline.
-#ifndef NPD_CSR
-#define NPD_CSR 12
-#endif
-#ifndef NPD_CSR_FWD
-#define NPD_CSR_FWD 16  // forward KL with 1024 threads: 4.53 ms with 12 resident groups, 4.48 ms with 16 (config 1)
-#endif
-#ifndef NPD_TOPK_CSR
-#define NPD_TOPK_CSR 12
-#endif
-#ifndef NPD_TD
-#define NPD_TD 2
-#endif
-#ifndef NPD_PERSIST
-#define NPD_PERSIST false
-#endif
+// Shape of the dense-teacher gradient kernels (measured on MI355X, 32,768 x 151,936): how many student groups per
+// thread stay in registers and how far ahead teacher / non-resident student groups are requested.  Times are flat
+// (+-2 %) for 8..16 resident groups; 12 leaves the register allocator enough room to avoid spills, whose reloads
+// would stall the load pipeline.
+constexpr int kResidentGroups = 12;
+constexpr int kResidentGroupsForward = 16;  // forward KL with 1024 threads: 4.53 ms with 12 resident groups, 4.48 ms with 16
+constexpr int kResidentGroupsTopk = 12;
+constexpr int kAhead = 2;
 }  // namespace npd

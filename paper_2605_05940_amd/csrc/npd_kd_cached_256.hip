@@ -6,11 +6,11 @@ namespace npd {
 template <int CS>
 static hipError_t launch_short(const KdArgs& a, int teacher_kind, hipStream_t stream) {
   constexpr int CB = 256;
-  constexpr int CSR = NPD_CSR < CS ? NPD_CSR : CS;
+  constexpr int CSR = kResidentGroups < CS ? kResidentGroups : CS;
   if (teacher_kind == kDense)
-    return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, false, kForwardKl, CB, true>(a, stream);
+    return launch_cached_lse1<CS, CSR, 9, kAhead, kDense, true, kForwardKl, CB, true>(a, stream);
   constexpr int TCL = CS - CSR < 9 ? CS - CSR : 9;  // top-k teacher: the LDS parks student groups
-  return launch_cached_lse1<CS, CSR, TCL, 3, kTopk, true, false, kForwardKl, CB, true>(a, stream);
+  return launch_cached_lse1<CS, CSR, TCL, 3, kTopk, true, kForwardKl, CB, true>(a, stream);
 }
 
 hipError_t launch_cached_short_256(const KdArgs& a, int cs, int teacher_kind, hipStream_t stream) {

@@ -5,11 +5,11 @@ namespace npd {
 
 template <int CS>
 static hipError_t launch_divergence(const KdArgs& a, hipStream_t stream) {
-  constexpr int CSR = NPD_CSR < CS ? NPD_CSR : CS;
+  constexpr int CSR = kResidentGroups < CS ? kResidentGroups : CS;
   if (a.divergence == kReverseKl)
-    return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, NPD_PERSIST, kReverseKl>(a, stream);
-  if (a.divergence == kSkewKl) return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, false, kSkewKl>(a, stream);
-  return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, false, kSkewReverseKl>(a, stream);
+    return launch_cached_lse1<CS, CSR, 9, kAhead, kDense, true, kReverseKl>(a, stream);
+  if (a.divergence == kSkewKl) return launch_cached_lse1<CS, CSR, 9, kAhead, kDense, true, kSkewKl>(a, stream);
+  return launch_cached_lse1<CS, CSR, 9, kAhead, kDense, true, kSkewReverseKl>(a, stream);
 }
 
 hipError_t launch_cached_divergence_1024(const KdArgs& a, int cs, hipStream_t stream) {

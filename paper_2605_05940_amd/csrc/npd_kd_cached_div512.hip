@@ -6,12 +6,12 @@ namespace npd {
 template <int CS>
 static hipError_t launch_divergence(const KdArgs& a, hipStream_t stream) {
   constexpr int CB = 512;
-  constexpr int CSR = NPD_CSR < CS ? NPD_CSR : CS;
+  constexpr int CSR = kResidentGroups < CS ? kResidentGroups : CS;
   if (a.divergence == kReverseKl)
-    return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, false, kReverseKl, CB, true>(a, stream);
+    return launch_cached_lse1<CS, CSR, 9, kAhead, kDense, true, kReverseKl, CB, true>(a, stream);
   if (a.divergence == kSkewKl)
-    return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, false, kSkewKl, CB, true>(a, stream);
-  return launch_cached_lse1<CS, CSR, 9, NPD_TD, kDense, true, false, kSkewReverseKl, CB, true>(a, stream);
+    return launch_cached_lse1<CS, CSR, 9, kAhead, kDense, true, kSkewKl, CB, true>(a, stream);
+  return launch_cached_lse1<CS, CSR, 9, kAhead, kDense, true, kSkewReverseKl, CB, true>(a, stream);
 }
 
 hipError_t launch_cached_divergence_512(const KdArgs& a, int cs, hipStream_t stream) {

@@ -5,13 +5,13 @@ namespace npd {
 
 template <int CS>
 static hipError_t launch_forward(const KdArgs& a, int teacher_kind, hipStream_t stream) {
-  constexpr int CSRF = NPD_CSR_FWD < CS ? NPD_CSR_FWD : CS;
-  if (teacher_kind == kDense) return launch_cached_lse1<CS, CSRF, 9, NPD_TD, kDense, true, NPD_PERSIST>(a, stream);
+  constexpr int CSRF = kResidentGroupsForward < CS ? kResidentGroupsForward : CS;
+  if (teacher_kind == kDense) return launch_cached_lse1<CS, CSRF, 9, kAhead, kDense, true>(a, stream);
   // top-k teacher: only the student row is dense; what does not fit the registers is parked in LDS, so the whole
   // row is on chip for the gradient sweep
-  constexpr int TCSR = CS < NPD_TOPK_CSR ? CS : NPD_TOPK_CSR;
+  constexpr int TCSR = CS < kResidentGroupsTopk ? CS : kResidentGroupsTopk;
   constexpr int TCL = CS - TCSR < 9 ? CS - TCSR : 9;
-  return launch_cached_lse1<CS, TCSR, TCL, 3, kTopk, true, false>(a, stream);
+  return launch_cached_lse1<CS, TCSR, TCL, 3, kTopk, true>(a, stream);
 }
 
 hipError_t launch_cached_forward_1024(const KdArgs& a, int cs, int teacher_kind, hipStream_t stream) {

@@ -7,9 +7,9 @@ namespace npd {
 template <int CB>
 static hipError_t launch_forward_only(const KdArgs& a, int teacher_kind, hipStream_t stream) {
   switch (teacher_kind) {
-    case kDense: return launch_cached_lse1<19, 0, 0, 4, kDense, false, false, kForwardKl, CB, true>(a, stream);
-    case kTopk: return launch_cached_lse1<19, 0, 0, 4, kTopk, false, false, kForwardKl, CB, true>(a, stream);
-    default: return launch_cached_lse1<19, 0, 0, 4, kNone, false, false, kForwardKl, CB, true>(a, stream);
+    case kDense: return launch_cached_lse1<19, 0, 0, 4, kDense, false, kForwardKl, CB, true>(a, stream);
+    case kTopk: return launch_cached_lse1<19, 0, 0, 4, kTopk, false, kForwardKl, CB, true>(a, stream);
+    default: return launch_cached_lse1<19, 0, 0, 4, kNone, false, kForwardKl, CB, true>(a, stream);
   }
 }
 

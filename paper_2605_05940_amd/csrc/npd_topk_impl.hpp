@@ -258,10 +258,7 @@ __device__ __forceinline__ void rank_sort(TopkShared& sh, const unsigned long lo
   __syncthreads();
 }
 
-#ifndef NPD_TOPK_DIRECT
-#define NPD_TOPK_DIRECT 192
-#endif
-constexpr int kDirectRankMax = NPD_TOPK_DIRECT;  // lists up to this length are rank-sorted as they are
+constexpr int kDirectRankMax = 192;  // lists up to this length are rank-sorted as they are
 
 // Orders the n >= k candidate words in sh.cand (all distinct: the ids differ) and writes the first k as the row's
 // record.  Called by all threads after a barrier that made the candidates visible; ends with a barrier.

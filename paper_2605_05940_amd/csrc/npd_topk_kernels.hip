@@ -23,12 +23,8 @@
 // Measured on MI355X, 32,768 x 151,936, k = 10 / 64 / 256: window 8 with a 4-group sample 1.72 / 2.04 / 2.77 ms,
 // 8 with 8 1.62 / 1.80 / 2.48, 12 with 12 1.57 / 1.69 / 2.29 (a larger sample gives a tighter bound, hence fewer
 // candidates to cut and order); 12 groups are what fits 64 VGPRs, i.e. two workgroups per CU.
-#ifndef NPD_TOPK_WINDOW
 #define NPD_TOPK_WINDOW 12
-#endif
-#ifndef NPD_TOPK_SAMPLE
 #define NPD_TOPK_SAMPLE 12
-#endif
 #define NPD_TOPK_ANY_SHAPE 1
 #include "npd_topk_impl.hpp"
 
@@ -42,9 +38,7 @@ hipError_t launch_stream(const TopkArgs& a, hipStream_t stream);  // npd_topk_ke
 // while a fourth is in its ordering phase.  Measured on config 1's teacher logits (k = 10 / 64 / 256): 1024 threads
 // 1.11 / 1.23 / 1.65 ms, 512 threads with an 8-group window 1.07 / 1.16 / 1.94 ms (with more candidates per row the
 // smaller list capacity and the narrower sample cost more than the overlap brings).
-#ifndef NPD_TOPK_SMALL_K
-#define NPD_TOPK_SMALL_K 128
-#endif
+constexpr int kSmallK = 128;
 
 hipError_t launch_teacher_topk(int64_t T, int32_t V, int64_t stride, int32_t k, int log_probs, const uint16_t* t,
                                const uint8_t* mask, int32_t* idx, float* val, hipStream_t stream) {
@@ -60,7 +54,7 @@ hipError_t launch_teacher_topk(int64_t T, int32_t V, int64_t stride, int32_t k, 
   const bool aligned = (reinterpret_cast<uintptr_t>(t) & 15u) == 0 && stride % 8 == 0;
   a.nvec = aligned ? V / 8 : 0;
   a.log_probs = log_probs;
-  if (a.nvec >= 1024) return k <= NPD_TOPK_SMALL_K ? topk512::launch_stream(a, stream) : topk1024::launch_stream(a, stream);
+  if (a.nvec >= 1024) return k <= kSmallK ? topk512::launch_stream(a, stream) : topk1024::launch_stream(a, stream);
   return topk1024::launch_any(a, stream);
 }
 

@@ -62,8 +62,9 @@ def check_row_canaries(full, T, V, stride):
 
 
 def run_gpu_kd(s, mask, *, t=None, idx=None, val=None, labels=None, tau=1.0, grad_scale=1.0, want_grad=True,
-               inplace=False, want_tnll=None, ce_grad_scale=0.0, divergence=0, skew_alpha=0.0):
-    """Call npd_kd_loss_fwd_bwd with guarded outputs.  Returns a dict of host numpy arrays."""
+               inplace=False, want_tnll=None, ce_grad_scale=0.0, divergence=0, skew_alpha=0.0, no_workspace=False):
+    """Call npd_kd_loss_fwd_bwd with guarded outputs.  Returns a dict of host numpy arrays.  `no_workspace`: set
+    NPD_FLAG_NO_WORKSPACE (the kernels that keep a whole row in one workgroup instead of the row-gang kernels)."""
     T, V = s.shape
     stride = s.stride(0)
     status = torch.zeros(1, dtype=torch.int32, device=dev())
@@ -84,7 +85,7 @@ def run_gpu_kd(s, mask, *, t=None, idx=None, val=None, labels=None, tau=1.0, gra
                                 grad_scale=grad_scale, ce_grad_scale=ce_grad_scale, divergence=divergence,
                                 skew_alpha=skew_alpha, grad_out=g, kd_tok=kd.t if kd else None,
                                 nll_tok=nll.t if nll else None, teacher_nll_tok=tnll.t if tnll else None,
-                                lse_tok=lse.t, dev_status=status)
+                                lse_tok=lse.t, dev_status=status, no_workspace=no_workspace)
     torch.cuda.synchronize()
     out = dict(status=int(status.item()))
     for name, buf in (("kd", kd), ("nll_s", nll), ("nll_t", tnll), ("lse_s", lse)):

@@ -5,7 +5,7 @@ import ctypes
 import pytest
 import torch
 
-from paper_2605_05940_amd import membench
+import bench_membench as membench
 
 HIP_INVALID_VALUE = 1
 FAKE = 0x10000
@@ -55,3 +55,34 @@ def test_membench_patterns_move_what_they_say(threads, nt):
             torch.cuda.synchronize()
             assert torch.equal(o, expect[name]), (name, order)
             assert (full[:guard] == 0xA5).all() and (full[guard + n:] == 0xA5).all(), (name, order)
+
+
+def test_membench_gang_validates_on_the_host():
+    lib = membench.load()
+    assert membench.gang_scratch_bytes(32768, 18992) == 32768 * 8 * 32      # 8 slices of at most 2,560 groups
+    assert membench.gang_scratch_bytes(4, 33 * 2560) == 0                   # more than 32 slices per row
+    assert membench.gang_scratch_bytes(0, 100) == 0
+    assert lib.npd_membench_gang(FAKE, FAKE + 0x1000, FAKE + 0x2000, 4, 100, None, None) == HIP_INVALID_VALUE
+    assert lib.npd_membench_gang(FAKE, FAKE + 0x1000, FAKE + 0x2004, 4, 100, FAKE + 0x3000, None) == HIP_INVALID_VALUE
+    assert lib.npd_membench_gang(None, FAKE + 0x1000, FAKE + 0x2000, 4, 100, FAKE + 0x3000, None) == HIP_INVALID_VALUE
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("groups", [2560 + 37, 3 * 2560, 1000])
+def test_membench_gang_moves_what_it_says(groups):
+    dev = torch.device("cuda:0")
+    rows = 9
+    n = rows * groups * 16
+    gen = torch.Generator(device="cpu").manual_seed(6)
+    a = torch.randint(0, 256, (n,), dtype=torch.uint8, generator=gen).to(dev)
+    b = torch.randint(0, 256, (n,), dtype=torch.uint8, generator=gen).to(dev)
+    guard = 4096
+    full = torch.full((n + 2 * guard,), 0xA5, dtype=torch.uint8, device=dev)
+    o = full[guard:guard + n]
+    scratch = torch.zeros(membench.gang_scratch_bytes(rows, groups), dtype=torch.uint8, device=dev)
+    for _ in range(2):                       # the second pass finds the first one's words in the record
+        full.fill_(0xA5)
+        membench.run_gang(a, b, o, scratch, rows, groups)
+        torch.cuda.synchronize()
+        assert torch.equal(o, a ^ b)
+        assert (full[:guard] == 0xA5).all() and (full[guard + n:] == 0xA5).all()
