@@ -28,6 +28,9 @@
  *     KL(p_S || (1 - alpha) p_T + alpha p_S), each with its gradient with respect to the student logits
  *   - per-sample reduction over cu_seqlens under the response mask
  *   - IFD (Eq. 3), Delta-IFD (Eq. 4) and the three curation zones of Sec. 3.2
+ *   - the policy-latency monitor of the appendix ("Analysis of Policy Latency": mean
+ *     D_KL(pi_learner || pi_generator) of a step against the near-policy bound epsilon) and
+ *     the perplexity of a sample (the PPL filter of the data-filter ablation)
  *
  * The temperature tau divides student and teacher logits alike; tau = 1 is Eq. 2
  * exactly.  No tau^2 factor is applied (a caller folds it into grad_scale).
@@ -521,8 +524,10 @@ int npd_oracle_segment_reduce(int64_t T, int32_t S, const double *x, const uint8
  *   zone    = DEGENERATE if Delta < lo, DISCONNECT if Delta > hi, else PROXIMAL (Sec. 3.2;
  *             the paper's lo is 0 and hi its threshold tau); the comparison is made on
  *             Delta rounded to binary32, the precision the zone decision is specified in.
- *   INVALID when either sample has no scored position, a denominator is 0, or
- *             anything is non-finite; IFD and Delta are then NaN.
+ *   INVALID when either sample has no scored position, a denominator is 0, one of the
+ *             four mean losses is not finite (NaN, or an infinite loss: a response the
+ *             model gives probability 0 has no difficulty ratio), or a result is not
+ *             finite; IFD and Delta are then NaN.
  *   keep    = zone is PROXIMAL (and, if flag bit 0 is set, IFD_teacher <= 1, the extra
  *             condition named in the description of the proximal zone).
  * Returns the number of kept pairs.
@@ -537,7 +542,9 @@ int32_t npd_oracle_delta_ifd(int32_t P, const double *mean_nll_student, const do
     double is = NAN, it = NAN, d = NAN;
     uint8_t z = ZONE_INVALID, kp = 0;
     const int ok_counts = seg_count[ic] > 0 && seg_count[iu] > 0;
-    if (ok_counts && mean_nll_student[iu] != 0.0 && mean_nll_teacher[iu] != 0.0) {
+    const int ok_means = isfinite(mean_nll_student[ic]) && isfinite(mean_nll_student[iu]) &&
+                         isfinite(mean_nll_teacher[ic]) && isfinite(mean_nll_teacher[iu]);
+    if (ok_counts && ok_means && mean_nll_student[iu] != 0.0 && mean_nll_teacher[iu] != 0.0) {
       is = mean_nll_student[ic] / mean_nll_student[iu];
       it = mean_nll_teacher[ic] / mean_nll_teacher[iu];
       d = it - is;
@@ -563,6 +570,66 @@ int32_t npd_oracle_delta_ifd(int32_t P, const double *mean_nll_student, const do
     kept += kp;
   }
   return kept;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Policy latency and perplexity.                                             */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * Policy latency (appendix, "Analysis of Policy Latency"): the paper tracks
+ * D_KL(pi_learner || pi_generator) between the model being trained and the model that
+ * generated the rollouts, and calls training near-policy while that distance stays within
+ * a small threshold, D_KL <= epsilon (it reports epsilon ~ 0.10); a refresh of the rollouts
+ * is due when the distance goes beyond it.
+ *
+ * kl_tok[p] is the KL divergence of the two next-token distributions at position p (Eq. 2's
+ * form with the learner's distribution leading).  Over the packed layout:
+ *   seg_mean[i], seg_count[i]  mean of kl_tok over the scored positions of sample i, their
+ *                              number (mean 0 for an empty sample)
+ *   batch_count                scored positions owned by any sample
+ *   batch_mean                 sum of kl_tok over those positions / batch_count: the step's
+ *                              D_KL, every scored token weighing the same (0 if none)
+ *   return value               1 if the batch left the near-policy regime, batch_mean >
+ *                              epsilon (or is not a number), else 0.  The comparison is made
+ *                              on the mean rounded to binary32, the precision the decision
+ *                              is specified in.
+ * Returns -1 for a cu_seqlens that decreases or leaves [0, T].
+ */
+int npd_oracle_policy_lag(int64_t T, int32_t S, const double *kl_tok, const uint8_t *mask, const int32_t *cu,
+                          double epsilon, double *seg_mean, int32_t *seg_count, double *batch_mean,
+                          int64_t *batch_count) {
+  for (int32_t i = 0; i < S; ++i)
+    if (cu[i] > cu[i + 1]) return -1;
+  if (S > 0 && (cu[0] < 0 || cu[S] > T)) return -1;
+  double total = 0.0;
+  int64_t n_total = 0;
+  for (int32_t i = 0; i < S; ++i) {
+    double acc = 0.0;
+    int32_t n = 0;
+    for (int64_t p = cu[i]; p < cu[i + 1]; ++p) {
+      if (mask[p]) {
+        acc += kl_tok[p];
+        n += 1;
+      }
+    }
+    if (seg_mean) seg_mean[i] = n > 0 ? acc / (double)n : 0.0;
+    if (seg_count) seg_count[i] = n;
+    total += acc;
+    n_total += n;
+  }
+  const double mean = n_total > 0 ? total / (double)n_total : 0.0;
+  if (batch_mean) *batch_mean = mean;
+  if (batch_count) *batch_count = n_total;
+  return !((float)mean <= (float)epsilon);
+}
+
+/*
+ * Perplexity of a sample, PPL = exp(mean CE loss over its scored positions): the filter metric
+ * the paper's data-filter ablation compares Delta-IFD with.  0 for an empty sample.
+ */
+void npd_oracle_perplexity(int32_t S, const double *mean_nll, const int32_t *seg_count, double *ppl) {
+  for (int32_t i = 0; i < S; ++i) ppl[i] = seg_count[i] > 0 ? exp(mean_nll[i]) : 0.0;
 }
 
 /* ------------------------------------------------------------------------- */

@@ -50,6 +50,10 @@ def lib():
         L.npd_oracle_teacher_topk_bf16.argtypes = [_i64, _i64, _i32, _p, _i64, _p, ctypes.c_int, _p, _p]
         L.npd_oracle_segment_reduce.restype = ctypes.c_int
         L.npd_oracle_segment_reduce.argtypes = [_i64, _i32, _p, _p, _p, _p, _p, _p, _p]
+        L.npd_oracle_policy_lag.restype = ctypes.c_int
+        L.npd_oracle_policy_lag.argtypes = [_i64, _i32, _p, _p, _p, _f64, _p, _p, _p, _p]
+        L.npd_oracle_perplexity.restype = None
+        L.npd_oracle_perplexity.argtypes = [_i32, _p, _p, _p]
         L.npd_oracle_delta_ifd.restype = _i32
         L.npd_oracle_delta_ifd.argtypes = [_i32, _p, _p, _p, _p, _p, _f64, _f64, _u32, _p, _p, _p, _p, _p]
         _lib = L
@@ -221,3 +225,32 @@ def delta_ifd(mean_nll_student, mean_nll_teacher, seg_count, pair_cond, pair_unc
     kept = lib().npd_oracle_delta_ifd(P, _ptr(ms), _ptr(mt), _ptr(cnt), _ptr(pc), _ptr(pu), lo, hi, flags,
                                       _ptr(ifd_s), _ptr(ifd_t), _ptr(delta), _ptr(zone), _ptr(keep))
     return dict(ifd_student=ifd_s, ifd_teacher=ifd_t, delta=delta, zone=zone, keep=keep, keep_count=int(kept))
+
+
+def policy_lag(kl_tok, mask, cu_seqlens, epsilon=0.10):
+    """Policy-latency monitor: per-sample and per-batch mean of a per-position KL(learner || generator) over the scored
+    positions, and whether the batch left the near-policy regime (batch mean > epsilon)."""
+    x = _c(kl_tok, np.float64)
+    T = x.shape[0]
+    mask = _c(mask, np.uint8)
+    cu = _c(cu_seqlens, np.int32)
+    S = cu.shape[0] - 1
+    seg_mean = np.empty(S)
+    seg_count = np.empty(S, np.int32)
+    batch_mean = np.zeros(1)
+    batch_count = np.zeros(1, np.int64)
+    rc = lib().npd_oracle_policy_lag(T, S, _ptr(x), _ptr(mask), _ptr(cu), float(epsilon), _ptr(seg_mean),
+                                     _ptr(seg_count), _ptr(batch_mean), _ptr(batch_count))
+    if rc < 0:
+        raise ValueError("cu_seqlens is not a non-decreasing sequence inside [0, T]")
+    return dict(seg_mean=seg_mean, seg_count=seg_count, batch_mean=float(batch_mean[0]),
+                batch_count=int(batch_count[0]), exceeded=int(rc))
+
+
+def perplexity(mean_nll, seg_count):
+    """PPL = exp(mean CE loss) per sample; 0 for samples without a scored position."""
+    m = _c(mean_nll, np.float64)
+    c = _c(seg_count, np.int32)
+    out = np.empty(m.shape[0])
+    lib().npd_oracle_perplexity(m.shape[0], _ptr(m), _ptr(c), _ptr(out))
+    return out

@@ -334,6 +334,99 @@ def test_packing_invariance(oracle):
     assert seg["count"].tolist() == [28, 48, 68, 91, 0]
 
 
+# --------------------------------------------------------------------------- policy latency, perplexity (appendix)
+
+def test_perplexity_of_a_uniform_model_is_the_vocabulary_size(oracle):
+    # uniform next-token distribution over V entries: CE loss ln V at every position, so PPL = V exactly
+    for V in (2, 1024, 151936):
+        s = np.full((9, V), -3.25)
+        lab = RNG.integers(0, V, 9)
+        mask = np.array([1, 1, 0, 1, 1, 1, 0, 0, 1], np.uint8)
+        cu = np.array([0, 4, 4, 9], np.int32)                       # a sample of 3 scored, an empty one, one of 3
+        nl = oracle.nll(s, lab, mask)
+        seg = oracle.segment_reduce(nl["nll"], mask, cu)
+        ppl = oracle.perplexity(seg["mean"], seg["count"])
+        assert ppl[0] == pytest.approx(V, rel=1e-12) and ppl[2] == pytest.approx(V, rel=1e-12)
+        assert ppl[1] == 0.0 and seg["count"].tolist() == [3, 0, 3]
+
+
+def test_perplexity_is_the_geometric_mean_of_inverse_token_probabilities(oracle):
+    # PPL = (prod_t 1 / p(y_t))^(1/n), written with the library softmax and python floats
+    V, T = 37, 11
+    s = _rand(T, V, 3.0)
+    lab = RNG.integers(0, V, T)
+    mask = np.ones(T, np.uint8)
+    mask[[2, 7]] = 0
+    p = torch.softmax(torch.from_numpy(s), 1).numpy()
+    prod, n = 1.0, 0
+    for t in range(T):
+        if mask[t]:
+            prod *= 1.0 / p[t, lab[t]]
+            n += 1
+    nl = oracle.nll(s, lab, mask)
+    seg = oracle.segment_reduce(nl["nll"], mask, np.array([0, T], np.int32))
+    assert oracle.perplexity(seg["mean"], seg["count"])[0] == pytest.approx(prod ** (1.0 / n), rel=1e-12)
+
+
+def test_policy_lag_is_zero_when_learner_and_generator_coincide(oracle):
+    V, T = 53, 40
+    gen = _rand(T, V)
+    mask = (RNG.random(T) < 0.7).astype(np.uint8)
+    cu = np.array([0, 13, 13, 31, 40], np.int32)
+    kl = oracle.kd_dense(gen, gen.copy(), None, mask, want_grad=False)["kd"]      # KL(learner || generator), learner == generator
+    out = oracle.policy_lag(kl, mask, cu, 0.10)
+    assert out["batch_mean"] == 0.0 and out["exceeded"] == 0 and (out["seg_mean"] == 0.0).all()
+    assert out["batch_count"] == int(mask.sum())
+    assert oracle.policy_lag(kl, mask, cu, 0.0)["exceeded"] == 0                  # on-policy: D_KL <= 0 holds at 0
+
+
+def test_policy_lag_brute_force_and_threshold(oracle):
+    V, T = 41, 64
+    gen, learner = _rand(T, V), None
+    learner = gen + RNG.normal(0.0, 0.6, size=(T, V))
+    mask = (RNG.random(T) < 0.75).astype(np.uint8)
+    cu = np.array([3, 20, 21, 21, 50, 60], np.int32)               # positions 0..2 and 60.. belong to no sample
+    mask[20] = 1
+    # KL(learner || generator): the learner's distribution leads, so it sits in the teacher slot of Eq. 2's form
+    kl = oracle.kd_dense(gen, learner, None, mask, want_grad=False)["kd"]
+    pl = torch.log_softmax(torch.from_numpy(learner), 1)
+    pg = torch.log_softmax(torch.from_numpy(gen), 1)
+    ref_tok = (pl.exp() * (pl - pg)).sum(1).numpy()
+    np.testing.assert_allclose(kl[mask == 1], ref_tok[mask == 1], rtol=0, atol=1e-12)
+    out = oracle.policy_lag(kl, mask, cu, 0.10)
+    total, n = 0.0, 0
+    for i in range(len(cu) - 1):
+        acc, k = 0.0, 0
+        for p in range(cu[i], cu[i + 1]):
+            if mask[p]:
+                acc += ref_tok[p]
+                k += 1
+        assert out["seg_count"][i] == k
+        assert out["seg_mean"][i] == pytest.approx(acc / k if k else 0.0, abs=1e-12)
+        total, n = total + acc, n + k
+    assert out["batch_count"] == n and n < int(mask.sum())          # unowned positions are not counted
+    assert out["batch_mean"] == pytest.approx(total / n, abs=1e-12)
+    # the step mean weighs every scored token the same: the count-weighted mean of the sample means
+    w = out["seg_count"].astype(np.float64)
+    assert out["batch_mean"] == pytest.approx(float((out["seg_mean"] * w).sum() / w.sum()), abs=1e-12)
+    assert abs(out["batch_mean"] - out["seg_mean"][out["seg_count"] > 0].mean()) > 1e-4   # ... not the mean of means
+    # near-policy regime: D_KL <= epsilon (closed); beyond it the batch is flagged
+    m = out["batch_mean"]
+    assert oracle.policy_lag(kl, mask, cu, m * 1.01)["exceeded"] == 0
+    assert oracle.policy_lag(kl, mask, cu, m * 0.99)["exceeded"] == 1
+    assert oracle.policy_lag(kl, mask, cu, float(np.float32(m)))["exceeded"] == 0     # equality is inside
+    assert oracle.policy_lag(np.full(T, 0.10), mask, cu, 0.10)["exceeded"] == 0
+    kl_nan = kl.copy()
+    kl_nan[cu[0]] = np.nan
+    mask[cu[0]] = 1
+    assert oracle.policy_lag(kl_nan, mask, cu, 0.10)["exceeded"] == 1                 # a broken monitor is not "near"
+    assert oracle.policy_lag(kl, np.zeros(T, np.uint8), cu, 0.10) == dict(
+        seg_mean=pytest.approx(np.zeros(5)), seg_count=pytest.approx(np.zeros(5)), batch_mean=0.0, batch_count=0,
+        exceeded=0)
+    with pytest.raises(ValueError):
+        oracle.policy_lag(kl, mask, np.array([0, 9, 4], np.int32), 0.10)
+
+
 # --------------------------------------------------------------------------- Delta-IFD (Eq. 3, Eq. 4, zones)
 
 def _golden_rows():
