@@ -273,8 +273,9 @@ npd_status npd_segment_reduce(int64_t n_tokens, int32_t n_segments, const float*
  *   keep    = zone == PROXIMAL  [and IFD_teacher <= 1 if NPD_IFD_REQUIRE_TEACHER_LE_1]
  *   keep_count[0] = number of kept pairs (written, not accumulated)
  *
- * INVALID: a sample of the pair has seg_count == 0, a denominator is 0, or a value is
- * not finite; ifd_* and delta are then NaN and keep = 0.  All arithmetic in fp32.
+ * INVALID: a sample of the pair has seg_count == 0, a denominator is 0, one of the four mean
+ * losses is not finite (also where plain division would give a finite ratio, 1 / inf = 0), or a
+ * result is not finite; ifd_* and delta are then NaN and keep = 0.  All arithmetic in fp32.
  *
  *   mean_nll_student, mean_nll_teacher fp32 [S]; seg_count int32 [S]; pair_cond, pair_uncond
  *   int32 [P], entries in [0, S) (an entry outside marks the pair INVALID);
@@ -286,6 +287,40 @@ npd_status npd_delta_ifd_score(int32_t n_pairs, int32_t n_segments, const float*
                                const int32_t* pair_uncond, float lo, float hi, uint32_t flags, float* ifd_student,
                                float* ifd_teacher, float* delta, uint8_t* zone, uint8_t* keep, int32_t* keep_count,
                                void* stream);
+
+/*
+ * Policy-latency monitor (appendix, "Analysis of Policy Latency"): the paper tracks
+ * D_KL(pi_learner || pi_generator) between the model being trained and the model that generated the
+ * rollouts, calls training near-policy while D_KL <= epsilon (it reports epsilon ~ 0.10) and names a
+ * refresh of the rollouts as due when the distance goes beyond.
+ *
+ * kl_tok is the per-position KL of the two next-token distributions: kd_tok of a forward-only
+ * npd_kd_loss_fwd_bwd call with the generator's logits as student_logits and the learner's as
+ * teacher_dense (Eq. 2's form puts the teacher slot's distribution first).  Over the packed layout:
+ *
+ *   seg_kl_mean[i], seg_count[i]  mean of kl_tok over the scored positions of sample i, and their number
+ *                                 (as npd_segment_reduce; a bad segment: NaN / 0 and NPD_DEV_BAD_CU_SEQLENS)
+ *   batch_count[0]                scored positions that a sample owns
+ *   batch_kl_mean[0]              sum of kl_tok over those positions / batch_count: the step's D_KL, every
+ *                                 scored position weighing the same (0 if there is none)
+ *   lag_exceeded[0]               1 if batch_kl_mean > epsilon or is not a number, else 0 (the bound is closed)
+ *
+ *   kl_tok fp32 [T], loss_mask uint8 [T], cu_seqlens int32 [S+1]; every output may be NULL.
+ *   epsilon finite, >= 0.  A cu_seqlens that decreases or leaves [0, T] gives batch_kl_mean NaN, count 0,
+ *   lag_exceeded 1 and NPD_DEV_BAD_CU_SEQLENS.  Fixed summation order: reproducible.
+ */
+npd_status npd_policy_lag(int64_t n_tokens, int32_t n_segments, const float* kl_tok, const uint8_t* loss_mask,
+                          const int32_t* cu_seqlens, float epsilon, float* seg_kl_mean, int32_t* seg_count,
+                          float* batch_kl_mean, int32_t* batch_count, int32_t* lag_exceeded, int32_t* dev_status,
+                          void* stream);
+
+/*
+ * Perplexity of every packed sample, PPL = exp(mean CE loss over its scored positions) -- the PPL filter that the
+ * paper's data-filter ablation compares Delta-IFD with -- from the per-sample means and counts npd_segment_reduce
+ * gives for nll_tok: seg_ppl[i] = exp(seg_mean_nll[i]), or 0 where seg_count[i] == 0.  All arrays [S], required.
+ */
+npd_status npd_segment_ppl(int32_t n_segments, const float* seg_mean_nll, const int32_t* seg_count, float* seg_ppl,
+                           void* stream);
 
 #ifdef __cplusplus
 }

@@ -25,7 +25,7 @@ NOALLOC_WORKSPACE_BYTES = 16 << 20   # NPD_NOALLOC_WORKSPACE_BYTES
 
 EXPORTS = ("npd_version", "npd_status_string", "npd_workspace_bytes", "npd_kd_loss_fwd_bwd",
            "npd_segment_reduce", "npd_delta_ifd_score", "npd_teacher_topk", "npd_debug_gang_spin_limit",
-           "npd_kd_loss_fwd_bwd_noalloc")
+           "npd_kd_loss_fwd_bwd_noalloc", "npd_policy_lag", "npd_segment_ppl")
 
 
 class NpdError(RuntimeError):
@@ -71,6 +71,10 @@ def load() -> ctypes.CDLL:
         L.npd_delta_ifd_score.restype = ctypes.c_int
         L.npd_delta_ifd_score.argtypes = ([ctypes.c_int32, ctypes.c_int32] + [_vp] * 5 +
                                           [ctypes.c_float, ctypes.c_float, ctypes.c_uint32] + [_vp] * 7)
+        L.npd_policy_lag.restype = ctypes.c_int
+        L.npd_policy_lag.argtypes = [ctypes.c_int64, ctypes.c_int32] + [_vp] * 3 + [ctypes.c_float] + [_vp] * 7
+        L.npd_segment_ppl.restype = ctypes.c_int
+        L.npd_segment_ppl.argtypes = [ctypes.c_int32] + [_vp] * 4
         L.npd_teacher_topk.restype = ctypes.c_int
         L.npd_teacher_topk.argtypes = ([ctypes.c_int64, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
                                         ctypes.c_uint32] + [_vp] * 5)
@@ -256,3 +260,30 @@ def npd_teacher_topk(teacher_logits: torch.Tensor, k: int, *, topk_idx: torch.Te
     _check(load().npd_teacher_topk(T, V, _row_stride(teacher_logits), k, NPD_TOPK_LOG_PROBS if log_probs else 0,
                                    _ptr(teacher_logits, torch.bfloat16), _ptr(loss_mask, torch.uint8),
                                    _ptr(topk_idx, torch.int32), _ptr(topk_val, torch.float32), _stream()))
+
+
+def npd_policy_lag(kl_tok: torch.Tensor, loss_mask: torch.Tensor, cu_seqlens: torch.Tensor, epsilon: float = 0.10, *,
+                   seg_kl_mean: Optional[torch.Tensor] = None, seg_count: Optional[torch.Tensor] = None,
+                   batch_kl_mean: Optional[torch.Tensor] = None, batch_count: Optional[torch.Tensor] = None,
+                   lag_exceeded: Optional[torch.Tensor] = None, dev_status: Optional[torch.Tensor] = None) -> None:
+    """Enqueue the policy-latency monitor on the current stream (see ``npd_policy_lag`` in npd.h)."""
+    T = loss_mask.numel()
+    S = cu_seqlens.numel() - 1
+    for name, t, n in (("kl_tok", kl_tok, T), ("seg_kl_mean", seg_kl_mean, S), ("seg_count", seg_count, S),
+                       ("batch_kl_mean", batch_kl_mean, 1), ("batch_count", batch_count, 1),
+                       ("lag_exceeded", lag_exceeded, 1)):
+        if t is not None and (t.numel() != n or not t.is_contiguous()):
+            raise ValueError(f"{name} must be contiguous with {n} elements")
+    _check(load().npd_policy_lag(
+        T, S, _ptr(kl_tok, torch.float32), _ptr(loss_mask, torch.uint8), _ptr(cu_seqlens, torch.int32), epsilon,
+        _ptr(seg_kl_mean, torch.float32), _ptr(seg_count, torch.int32), _ptr(batch_kl_mean, torch.float32),
+        _ptr(batch_count, torch.int32), _ptr(lag_exceeded, torch.int32), _ptr(dev_status, torch.int32), _stream()))
+
+
+def npd_segment_ppl(seg_mean_nll: torch.Tensor, seg_count: torch.Tensor, seg_ppl: torch.Tensor) -> None:
+    """Enqueue PPL = exp(mean NLL) per sample on the current stream (see ``npd_segment_ppl`` in npd.h)."""
+    S = seg_mean_nll.numel()
+    if seg_count.numel() != S or seg_ppl.numel() != S:
+        raise ValueError("inconsistent sizes")
+    _check(load().npd_segment_ppl(S, _ptr(seg_mean_nll, torch.float32), _ptr(seg_count, torch.int32),
+                                  _ptr(seg_ppl, torch.float32), _stream()))

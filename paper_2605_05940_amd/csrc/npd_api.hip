@@ -380,4 +380,45 @@ npd_status npd_delta_ifd_score(int32_t n_pairs, int32_t n_segments, const float*
   return e == hipSuccess ? NPD_OK : NPD_ERR_HIP;
 }
 
+npd_status npd_policy_lag(int64_t n_tokens, int32_t n_segments, const float* kl_tok, const uint8_t* loss_mask,
+                          const int32_t* cu_seqlens, float epsilon, float* seg_kl_mean, int32_t* seg_count,
+                          float* batch_kl_mean, int32_t* batch_count, int32_t* lag_exceeded, int32_t* dev_status,
+                          void* stream) {
+  if (n_tokens < 0 || n_segments < 0) return NPD_ERR_SHAPE;
+  if (n_tokens > NPD_MAX_TOKENS) return NPD_ERR_UNSUPPORTED;
+  if (!(epsilon >= 0.0f) || !isfinite(epsilon)) return NPD_ERR_VALUE;
+  if (misaligned(kl_tok, 4) || misaligned(cu_seqlens, 4) || misaligned(seg_kl_mean, 4) || misaligned(seg_count, 4) ||
+      misaligned(batch_kl_mean, 4) || misaligned(batch_count, 4) || misaligned(lag_exceeded, 4) ||
+      misaligned(dev_status, 4))
+    return NPD_ERR_VALUE;
+  if (n_segments > 0 && (!kl_tok || !loss_mask || !cu_seqlens)) return NPD_ERR_NULL;
+  {
+    const size_t T = (size_t)n_tokens, S = (size_t)n_segments;
+    const Range in[3] = {opt_range(kl_tok, T * 4), opt_range(loss_mask, T), opt_range(cu_seqlens, (S + 1) * 4)};
+    const Range out[6] = {opt_range(seg_kl_mean, S * 4), opt_range(seg_count, S * 4), opt_range(batch_kl_mean, 4),
+                          opt_range(batch_count, 4),      opt_range(lag_exceeded, 4),  opt_range(dev_status, 4)};
+    if (any_alias(in, 3, out, 6)) return NPD_ERR_ALIAS;
+  }
+  const hipError_t e =
+      npd::launch_policy_lag(n_tokens, n_segments, kl_tok, loss_mask, cu_seqlens, epsilon, seg_kl_mean, seg_count,
+                             batch_kl_mean, batch_count, lag_exceeded, dev_status, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? NPD_OK : NPD_ERR_HIP;
+}
+
+npd_status npd_segment_ppl(int32_t n_segments, const float* seg_mean_nll, const int32_t* seg_count, float* seg_ppl,
+                           void* stream) {
+  if (n_segments < 0) return NPD_ERR_SHAPE;
+  if (misaligned(seg_mean_nll, 4) || misaligned(seg_count, 4) || misaligned(seg_ppl, 4)) return NPD_ERR_VALUE;
+  if (n_segments > 0 && (!seg_mean_nll || !seg_count || !seg_ppl)) return NPD_ERR_NULL;
+  {
+    const size_t S = (size_t)n_segments;
+    const Range in[2] = {opt_range(seg_mean_nll, S * 4), opt_range(seg_count, S * 4)};
+    const Range out[1] = {opt_range(seg_ppl, S * 4)};
+    if (any_alias(in, 2, out, 1)) return NPD_ERR_ALIAS;
+  }
+  const hipError_t e =
+      npd::launch_segment_ppl(n_segments, seg_mean_nll, seg_count, seg_ppl, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? NPD_OK : NPD_ERR_HIP;
+}
+
 }  // extern "C"

@@ -106,4 +106,10 @@ hipError_t launch_delta_ifd(int32_t P, int32_t S, const float* ms, const float* 
                             float* ifd_t, float* delta, uint8_t* zone, uint8_t* keep, int32_t* keep_count,
                             hipStream_t stream);
 
+hipError_t launch_policy_lag(int64_t T, int32_t S, const float* kl, const uint8_t* mask, const int32_t* cu,
+                             float epsilon, float* seg_mean, int32_t* seg_count, float* batch_mean,
+                             int32_t* batch_count, int32_t* exceeded, int32_t* status, hipStream_t stream);
+
+hipError_t launch_segment_ppl(int32_t S, const float* mean_nll, const int32_t* cnt, float* ppl, hipStream_t stream);
+
 }  // namespace npd

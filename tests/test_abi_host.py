@@ -218,6 +218,22 @@ def test_segment_and_ifd_argument_validation(lib):
     assert lib.npd_delta_ifd_score(2, 4, FAKE + 1, FAKE, FAKE, FAKE, FAKE, 0.0, 1.0, 0, *outs, None) == E_VALUE
 
 
+def test_policy_lag_and_ppl_argument_validation(lib):
+    kl, m, cu, o = FAKE, FAKE + 0x1000, FAKE + 0x2000, FAKE + 0x3000
+    call = lambda T=8, S=2, kl=kl, m=m, cu=cu, eps=0.1, outs=(None,) * 6: lib.npd_policy_lag(
+        T, S, kl, m, cu, ctypes.c_float(eps), *outs, None)
+    assert call(T=-1) == E_SHAPE and call(S=-1) == E_SHAPE and call(T=2**31) == E_UNSUP
+    assert call(eps=-0.1) == E_VALUE and call(eps=float("nan")) == E_VALUE and call(eps=float("inf")) == E_VALUE
+    assert call(kl=None) == E_NULL and call(m=None) == E_NULL and call(cu=None) == E_NULL
+    assert call(kl=FAKE + 2) == E_VALUE
+    assert call(outs=(kl + 8, None, None, None, None, None)) == E_ALIAS        # seg_kl_mean over kl_tok
+    assert call(outs=(None, None, o, o, None, None)) == E_ALIAS                # two scalar outputs on one word
+    assert call(outs=(None, None, None, None, m + 4, None)) == E_ALIAS         # lag_exceeded over the mask
+    ppl = lambda S=4, a=FAKE, c=FAKE + 0x1000, p=FAKE + 0x2000: lib.npd_segment_ppl(S, a, c, p, None)
+    assert ppl(S=-1) == E_SHAPE and ppl(a=None) == E_NULL and ppl(p=None) == E_NULL and ppl(c=FAKE + 0x1002) == E_VALUE
+    assert ppl(p=FAKE + 8) == E_ALIAS and ppl(p=FAKE + 0x1000) == E_ALIAS
+
+
 def test_teacher_topk_argument_validation(lib):
     ok = (16, 64, 64, 8, 0, FAKE, None, FAKE + 0x100000, FAKE + 0x200000, None)
     def call(**kw):

@@ -788,6 +788,86 @@ def test_policy_lag_monitor_is_the_same_entry_point_with_roles_swapped(oracle):
     assert np.abs(rev["kd"] - ref["kd"]).max() > 1e-3      # the direction matters
 
 
+def _policy_lag_gpu(kl, mask, cu, eps):
+    S = cu.numel() - 1
+    seg_mean, seg_cnt = Guarded(S, torch.float32), Guarded(S, torch.int32)
+    bmean, bcnt, exc = Guarded(1, torch.float32), Guarded(1, torch.int32), Guarded(1, torch.int32)
+    status = torch.zeros(1, dtype=torch.int32, device=dev())
+    binding.npd_policy_lag(kl, mask, cu, eps, seg_kl_mean=seg_mean.t, seg_count=seg_cnt.t, batch_kl_mean=bmean.t,
+                           batch_count=bcnt.t, lag_exceeded=exc.t, dev_status=status)
+    torch.cuda.synchronize()
+    return dict(seg_mean=seg_mean.check().cpu().numpy().astype(np.float64), seg_count=seg_cnt.check().cpu().numpy(),
+                batch_mean=float(bmean.check().item()), batch_count=int(bcnt.check().item()),
+                exceeded=int(exc.check().item()), status=int(status.item()))
+
+
+def test_policy_lag_and_perplexity_at_full_vocabulary(oracle):
+    """The appendix's policy-latency monitor, end to end on the GPU at V = 151,936: per-position KL(learner ||
+    generator) from the forward-only KD call with the roles swapped, its per-sample and per-step means, the
+    near-policy decision against epsilon, and the perplexity of every sample from the same call's NLLs -- all three
+    against the oracle."""
+    w = synth.scaled(synth.config(1), n_rows=2, row_len=160, vocab=151936, length_lo=8, length_hi=64)
+    lay, gen, _, mask, labels = _inputs(w, dense_teacher=False)
+    # a learner a few optimiser steps away from the generator: small logit drift
+    g = torch.Generator(device=dev()).manual_seed(41)
+    learner = (gen.float() + 0.35 * torch.randn(gen.shape, device=dev(), generator=g)).to(torch.bfloat16)
+    cu = torch.from_numpy(lay.cu_seqlens).to(dev())
+    T, S = w.n_tokens, lay.n_segments
+    kl, nll = torch.empty(T, device=dev()), torch.empty(T, device=dev())
+    binding.npd_kd_loss_fwd_bwd(gen, mask, teacher_dense=learner, labels=labels, kd_tok=kl, teacher_nll_tok=nll)
+    ref_tok = oracle.kd_dense(_bits(gen), _bits(learner), lay.labels, lay.loss_mask, want_grad=False)
+    ref = oracle.policy_lag(ref_tok["kd"], lay.loss_mask, lay.cu_seqlens, 0.10)
+    assert 0.01 < ref["batch_mean"] < 1.0
+    for eps in (0.10, ref["batch_mean"] * 0.9, ref["batch_mean"] * 1.1, 0.0, 5.0):
+        got = _policy_lag_gpu(kl, mask, cu, eps)
+        want = oracle.policy_lag(ref_tok["kd"], lay.loss_mask, lay.cu_seqlens, eps)
+        assert got["status"] == 0 and got["exceeded"] == want["exceeded"], eps
+        assert got["batch_count"] == want["batch_count"] == int(lay.loss_mask.sum())
+        np.testing.assert_array_equal(got["seg_count"], want["seg_count"])
+        assert abs(got["batch_mean"] - want["batch_mean"]) <= 1e-3 * want["batch_mean"]
+        np.testing.assert_allclose(got["seg_mean"], want["seg_mean"], rtol=1e-3, atol=1e-7)
+    assert _policy_lag_gpu(kl, mask, cu, ref["batch_mean"] * 0.9)["exceeded"] == 1
+    assert _policy_lag_gpu(kl, mask, cu, ref["batch_mean"] * 1.1)["exceeded"] == 0
+    # learner == generator: exactly on-policy
+    binding.npd_kd_loss_fwd_bwd(gen, mask, teacher_dense=gen.clone(), kd_tok=kl)
+    same = _policy_lag_gpu(kl, mask, cu, 0.0)
+    assert same["batch_mean"] == 0.0 and same["exceeded"] == 0 and (same["seg_mean"] == 0.0).all()
+    # perplexity of the learner on every sample: exp of the per-sample mean NLL
+    seg = _segment_gpu(nll, mask, cu, want_t2s=False)
+    ppl = Guarded(S, torch.float32)
+    binding.npd_segment_ppl(torch.from_numpy(seg["mean"].astype(np.float32)).to(dev()),
+                            torch.from_numpy(seg["count"]).to(dev()), ppl.t)
+    torch.cuda.synchronize()
+    rseg = oracle.segment_reduce(ref_tok["nll_t"], lay.loss_mask, lay.cu_seqlens)
+    rppl = oracle.perplexity(rseg["mean"], rseg["count"])
+    got = ppl.check().cpu().numpy().astype(np.float64)
+    assert (got[rseg["count"] == 0] == 0).all() and (rseg["count"] == 0).any()
+    nz = rseg["count"] > 0
+    np.testing.assert_allclose(got[nz], rppl[nz], rtol=1e-3)      # exp amplifies the 1e-4 bar of the mean by ~12
+    assert rppl[nz].min() > 1e3                                    # random logits: perplexity of the order of V
+
+
+def test_policy_lag_edge_cases():
+    f32 = lambda a: torch.tensor(a, dtype=torch.float32, device=dev())
+    u8 = lambda a: torch.tensor(a, dtype=torch.uint8, device=dev())
+    i32 = lambda a: torch.tensor(a, dtype=torch.int32, device=dev())
+    kl = f32([0.5, 0.25, 9.0, 0.125, 0.125, 7.0, 1.0, 3.0])
+    mask = u8([1, 1, 0, 1, 1, 1, 1, 1])
+    out = _policy_lag_gpu(kl, mask, i32([1, 3, 3, 5]), 0.10)       # position 0 and 5.. belong to no sample
+    assert out["batch_count"] == 3 and out["batch_mean"] == float(np.float32(0.5) / np.float32(3)) and out["exceeded"] == 1
+    np.testing.assert_array_equal(out["seg_count"], [1, 0, 2])
+    np.testing.assert_array_equal(out["seg_mean"], np.float32([0.25, 0.0, 0.125]))
+    assert _policy_lag_gpu(kl, mask, i32([3, 5]), 0.125)["exceeded"] == 0                   # the bound is closed
+    assert _policy_lag_gpu(kl, u8([0] * 8), i32([0, 8]), 0.10) == dict(
+        seg_mean=pytest.approx(np.zeros(1)), seg_count=pytest.approx(np.zeros(1)), batch_mean=0.0, batch_count=0,
+        exceeded=0, status=0)
+    bad = _policy_lag_gpu(kl, mask, i32([0, 6, 4, 8]), 0.10)       # decreasing boundaries
+    assert bad["status"] == binding.NPD_DEV_BAD_CU_SEQLENS and np.isnan(bad["batch_mean"]) and bad["exceeded"] == 1
+    assert bad["batch_count"] == 0
+    nan = _policy_lag_gpu(f32([0.1, float("nan"), 0.1]), u8([1, 1, 1]), i32([0, 3]), 0.10)
+    assert np.isnan(nan["batch_mean"]) and nan["exceeded"] == 1 and nan["status"] == 0
+
+
 # --------------------------------------------------------------------------- teacher-side top-k record (Sec. 3.1)
 
 def _topk_gpu(t, k, mask=None, log_probs=True):
