@@ -11,7 +11,9 @@ NLLs.  Prints ONE JSON line.
 (Alg. 1 Phase 2: not part of the student step, so not part of the headline line).
 """
 import argparse
+import ctypes
 import json
+import os
 import sys
 import time
 
@@ -20,16 +22,26 @@ import torch
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 
-# HBM-side bytes per launch of the fused kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
-# counters read for a plain copy of known size (x2.000 and x1.000); summaries in profiles/kd_cached_kernel_cfg1_hbm_traffic.md
-# and profiles/kd_kernels_other_workloads_hbm_traffic.md.  KiB of fetches (scaled) + KiB of writes per launch; config 3's
-# "launch" is its two forward-only calls.
-MEASURED_TRAFFIC_BYTES = {"cfg1_1b_dense": (14_854_249 + 9_732_739) * 1024,
-                          "cfg2_topk64": (2 * 3_520_534 + 9_798_926) * 1024,
-                          "cfg3_delta_ifd": 2 * (2 * 7_659_974 + 2_053) * 1024,
-                          "cfg4_stress": (2 * 41_329_329 + 33_563_337) * 1024}
-# the teacher top-k record of config 1's teacher logits, by k
-MEASURED_TOPK_TRAFFIC_BYTES = {64: (2 * 3_428_426 + 16_384) * 1024}
+# HBM-side bytes per launch of the dominant kernel, counted by rocprofv3 (--pmc FETCH_SIZE, then WRITE_SIZE, each scaled by
+# what the same counter reads for a plain copy of known size) in earlier runs of this very command: bench_hbm_traffic.json
+# holds one record per workload with the kernel and the library version it was counted on.  `roofline.traffic` is printed
+# only when both match what this run launches; otherwise null (the record says what it was measured on).
+TRAFFIC_RECORD = os.path.join(os.path.dirname(os.path.abspath(__file__)), "bench_hbm_traffic.json")
+
+
+def counted_traffic(workload, kernel, version):
+    """(bytes per launch or None, provenance string) for `workload` as launched by `kernel` of library `version`."""
+    try:
+        with open(TRAFFIC_RECORD) as f:
+            rec = json.load(f).get(workload)
+    except (OSError, ValueError):
+        return None, "no traffic record"
+    if rec is None:
+        return None, "no traffic record for this workload"
+    src = f"{rec['profile']} ({rec['kernel']}, libnpd {rec['npd_version']})"
+    if rec["kernel"] != kernel or rec["npd_version"] != version:
+        return None, f"stale: counted on {src}; this run launches {kernel}, libnpd {version}"
+    return int(1024 * (rec["fetch_kib"] * rec["fetch_scale"] + rec["write_kib"] * rec["write_scale"])), src
 
 
 def algorithmic_bytes(w, lay):
@@ -61,6 +73,10 @@ def main():
                     help="kd: the fused loss step (default); teacher_topk: the teacher-side top-k record; membench: "
                          "arithmetic-free streaming kernels over arrays of the workload's size (practical ceilings)")
     ap.add_argument("--topk", type=int, default=64, help="k of --op teacher_topk")
+    ap.add_argument("--no-workspace", action="store_true",
+                    help="set NPD_FLAG_NO_WORKSPACE: time the kernels that keep a whole row in one workgroup")
+    ap.add_argument("--skip-all-scored", action="store_true",
+                    help="do not add the few extra launches with every position scored (roofline.all_scored)")
     ap.add_argument("--all-scored", action="store_true",
                     help="score every position (no prompt or padding rows): the rate of a batch without write-only rows")
     ap.add_argument("--traffic-calibration", action="store_true",
@@ -118,6 +134,7 @@ def main():
     status = torch.zeros(1, dtype=torch.int32, device=dev)
 
     kernel_events = []
+    all_scored_events = []
     div_code = ("forward", "reverse", "skew", "skew_reverse").index(args.divergence)
     if div_code and not (dense and not w.paired):
         print("bench.py: --divergence applies to the dense-teacher training configurations", file=sys.stderr)
@@ -132,7 +149,7 @@ def main():
             binding.npd_kd_loss_fwd_bwd(t, mask, labels=labels, nll_tok=tnll, dev_status=status)
         elif dense:
             binding.npd_kd_loss_fwd_bwd(s, mask, teacher_dense=t, labels=labels, tau=w.tau, grad_scale=1.0,
-                                        divergence=div_code, skew_alpha=args.skew_alpha,
+                                        divergence=div_code, skew_alpha=args.skew_alpha, no_workspace=args.no_workspace,
                                         grad_out=g, kd_tok=kd, nll_tok=nll, teacher_nll_tok=tnll, dev_status=status)
         else:
             binding.npd_kd_loss_fwd_bwd(s, mask, teacher_idx=idx, teacher_val=val, labels=labels, tau=w.tau,
@@ -177,9 +194,51 @@ def main():
     alg_bytes = algorithmic_bytes(w, lay)
     achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
     n_scored = int(lay.loss_mask.sum())
-    traffic = MEASURED_TRAFFIC_BYTES.get(w.name) if div_code == 0 else None
+    version = binding.version()
+    kernel_name = kd_kernel_name(binding, w, T, V, div_code, args.no_workspace)
+    traffic, traffic_source = counted_traffic(w.name if div_code == 0 else f"{w.name}/{args.divergence}", kernel_name,
+                                              version)
     # v_exp_f32 per student logit: one per tensor in the loss sweep, one per tensor in the gradient sweep
     exps_per_logit = 2 if w.paired else (4 if dense else 2)
+    # keep the last timed step's outputs for the check against the oracle (the extra timing below overwrites them)
+    last = dict(kd=kd.clone(), nll=nll.clone(), tnll=tnll.clone(), seg_sum=seg_sum.clone(), mean_s=mean_s.clone(),
+                mean_t=mean_t.clone(), seg_cnt=seg_cnt.clone(), delta=delta.clone(), zone=zone.clone(),
+                grad=None if g is None else g)
+
+    # The same launch with every position scored (no prompt or padding rows, whose gradient rows are only zero-filled):
+    # the rate of a batch that is all responses.  A few launches, outside the headline timing.
+    all_scored = None
+    if not w.paired and not args.all_scored and not args.skip_all_scored:
+        keep_mask = mask.clone()
+        mask.fill_(1)
+        for i in range(2 + max(3, args.steps // 4)):
+            if w.inplace:
+                s.copy_(pristine)
+            if i >= 2:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+            if dense:
+                binding.npd_kd_loss_fwd_bwd(s, mask, teacher_dense=t, labels=labels, tau=w.tau, divergence=div_code,
+                                            skew_alpha=args.skew_alpha, no_workspace=args.no_workspace, grad_out=g,
+                                            kd_tok=kd, nll_tok=nll,
+                                            teacher_nll_tok=tnll, dev_status=status)
+            else:
+                binding.npd_kd_loss_fwd_bwd(s, mask, teacher_idx=idx, teacher_val=val, labels=labels, tau=w.tau,
+                                            grad_out=g, kd_tok=kd, nll_tok=nll, dev_status=status)
+            if i >= 2:
+                e1.record()
+                all_scored_events.append((e0, e1))
+        torch.cuda.synchronize()
+        ms = float(np.mean([a.elapsed_time(b) for a, b in all_scored_events]))
+        per_row = (2 * (2 * V) + 2 * V) if dense else (2 * V + 2 * V + w.topk * 8)
+        all_scored = {"kernel_ms": ms, "achieved": T * per_row / (ms * 1e-3) / 1e9,
+                      "frac": T * per_row / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                      "note": "same batch with every position scored (no write-only rows)"}
+        mask.copy_(keep_mask)    # and the gradient of the timed workload again, for the check below
+        if w.inplace:
+            s.copy_(pristine)
+        fused(False)
+        torch.cuda.synchronize()
 
     out = {
         "metric": "kd_fwd_bwd_logit_tokens_per_sec", "value": T * args.steps / elapsed, "unit": "tokens/s",
@@ -193,21 +252,24 @@ def main():
                    "tokens": T, "scored_tokens": n_scored, "segments": S, "pairs": P,
                    "io_dtype": "bf16 logits and gradient, fp32 accumulation"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "npd::kd_cached_kernel (fused KD loss + gradient)" if div_code == 0 else
-                               f"npd::kd_cached_kernel ({args.divergence} divergence + gradient)",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
+                     "kernel": f"npd::{kernel_name}", "npd_version": version,
                      "kernel_ms": kernel_ms,
                      "kernel_ms_median": float(np.median(kernel_all)), "kernel_ms_min": float(kernel_all.min()),
                      "algorithmic_bytes_per_launch": alg_bytes,
                      "counter_gbs": (traffic / (kernel_ms * 1e-3) / 1e9) if traffic else None,
                      "scored_tokens_per_sec": n_scored / (kernel_ms * 1e-3),
-                     "exp_per_sec": n_scored * V * exps_per_logit / (kernel_ms * 1e-3)},
+                     "exp_per_sec": n_scored * V * exps_per_logit / (kernel_ms * 1e-3),
+                     "all_scored": all_scored},
         "context": "paper reports only a pipeline-level 8.1x train-time speed-up of NPD over DistiLLM-2 on "
                    "unnamed NPUs; not comparable to this kernel",
     }
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, lay, s if pristine is None else pristine, t, idx, val)
+        base, check = cpu_baseline_and_check(w, lay, s if pristine is None else pristine, t, idx, val, last,
+                                             lay.cu_seqlens, args.divergence, args.skew_alpha)
+        out["cpu_baseline"] = base
+        out["verification"] = check
     print(json.dumps(out))
 
 
@@ -334,34 +396,98 @@ def bench_teacher_topk(args, binding, synth, dev):
     print(json.dumps(out))
 
 
-def cpu_baseline(w, lay, s, t, idx, val, budget_s=15.0, chunk=512, max_rows=1 << 30):
-    """The float64 oracle, as it stands, on the first rows of the same batch, on this machine's host cores."""
+def kd_kernel_name(binding, w, T, V, div_code, no_workspace=False):
+    """The kernel family a call of this workload takes (aligned, contiguous rows), as the library reports it."""
+    d = binding.KdDesc()
+    d.n_tokens, d.vocab, d.student_stride, d.teacher_stride = T, V, V, V
+    d.teacher_kind = (binding.NPD_TEACHER_NONE if w.paired else
+                      binding.NPD_TEACHER_DENSE_BF16 if w.teacher == "dense" else binding.NPD_TEACHER_TOPK)
+    d.topk = w.topk if w.teacher == "topk" else 0
+    d.flags = binding.NPD_FLAG_FWD_ONLY if w.paired else (binding.NPD_FLAG_INPLACE_GRAD if w.inplace else 0)
+    if no_workspace:
+        d.flags |= binding.NPD_FLAG_NO_WORKSPACE
+    d.tau, d.grad_scale, d.divergence, d.skew_alpha = w.tau, 1.0, div_code, 0.1
+    return binding.load().npd_kd_kernel_name(ctypes.byref(d)).decode()
+
+
+def cpu_baseline_and_check(w, lay, s, t, idx, val, last, cu_host, divergence="forward", alpha=0.1, budget_s=15.0,
+                           chunk=512, grad_chunks=4):
+    """The float64 oracle, as it stands, on the first rows of the same batch, on this machine's host cores -- timed (the
+    `cpu_baseline` object) and, since it computes them anyway, compared with what the last timed step left on the GPU
+    (the `verification` object): per-sample sums of the per-position losses for every sample the oracle covered within
+    its time budget, sample counts, and every gradient element of the first `grad_chunks` blocks of rows."""
     from paper_2605_05940_amd import synth
     from oracle import npd_oracle
-    rows = 0
-    spent = 0.0
-    while rows < min(max_rows, w.n_tokens) and spent < budget_s:
-        r0, r1 = rows, min(rows + chunk, w.n_tokens)
+    T = w.n_tokens
+    rows, spent = 0, 0.0
+    ref = {key: np.zeros(T) for key in ("kd", "nll_s", "nll_t")}
+    grad_err, grad_rows = 0.0, 0
+    while rows < T and spent < budget_s:
+        r0, r1 = rows, min(rows + chunk, T)
         sb = synth.bf16_bits(s[r0:r1])
         lab, m = lay.labels[r0:r1], lay.loss_mask[r0:r1]
         if w.paired:
             tb = synth.bf16_bits(t[r0:r1])
             t0 = time.perf_counter()
-            npd_oracle.nll(sb, lab, m)
-            npd_oracle.nll(tb, lab, m)
+            a = npd_oracle.nll(sb, lab, m)
+            b = npd_oracle.nll(tb, lab, m)
+            spent += time.perf_counter() - t0
+            ref["nll_s"][r0:r1], ref["nll_t"][r0:r1] = a["nll"], b["nll"]
+            o = None
         elif w.teacher == "dense":
             tb = synth.bf16_bits(t[r0:r1])
             t0 = time.perf_counter()
-            npd_oracle.kd_dense(sb, tb, lab, m, tau=w.tau)
+            if divergence == "forward":
+                o = npd_oracle.kd_dense(sb, tb, lab, m, tau=w.tau)
+            else:
+                o = npd_oracle.kd_dense(sb, tb, lab, m, tau=w.tau, want_grad=False)
+                o.update(npd_oracle.div_dense(sb, tb, divergence, alpha, mask=m, tau=w.tau))
+            spent += time.perf_counter() - t0
+            ref["kd"][r0:r1], ref["nll_s"][r0:r1], ref["nll_t"][r0:r1] = o["kd"], o["nll_s"], o["nll_t"]
         else:
             ib, vb = idx[r0:r1].cpu().numpy(), val[r0:r1].cpu().numpy()
             t0 = time.perf_counter()
-            npd_oracle.kd_topk(sb, ib, vb, lab, m, tau=w.tau)
-        spent += time.perf_counter() - t0
+            o = npd_oracle.kd_topk(sb, ib, vb, lab, m, tau=w.tau)
+            spent += time.perf_counter() - t0
+            ref["kd"][r0:r1], ref["nll_s"][r0:r1] = o["kd"], o["nll_s"]
+        if o is not None and last["grad"] is not None and grad_rows < grad_chunks * chunk:
+            got = last["grad"][r0:r1].float().cpu().numpy()
+            grad_err = max(grad_err, float(np.abs(got - o["grad"]).max()))
+            grad_rows += r1 - r0
         rows = r1
-    return {"value": rows / spent, "unit": "tokens/s", "cores": npd_oracle.threads(), "kind": "oracle",
-            "sample": f"first {rows} of {w.n_tokens} token rows of the same batch (masked rows included), "
+    base = {"value": rows / spent, "unit": "tokens/s", "cores": npd_oracle.threads(), "kind": "oracle",
+            "sample": f"first {rows} of {T} token rows of the same batch (masked rows included), "
                       f"float64 C oracle with OpenMP, {spent:.1f} s of wall time"}
+
+    # per-sample comparison over the samples that lie inside the rows the oracle covered
+    cu = np.asarray(cu_host)
+    covered = np.flatnonzero(cu[1:] <= rows)
+    cu_cov = cu[:len(covered) + 1] if len(covered) else cu[:1]
+
+    def rel_err(gpu_per_sample, key, mean):
+        if len(covered) == 0:
+            return None
+        seg = npd_oracle.segment_reduce(ref[key][:rows], lay.loss_mask[:rows], cu_cov, want_token_to_sample=False)
+        want = seg["mean"] if mean else seg["sum"]
+        got = gpu_per_sample.cpu().numpy().astype(np.float64)[:len(covered)]
+        nz = seg["count"] > 0
+        return float((np.abs(got[nz] - want[nz]) / np.maximum(np.abs(want[nz]), 1e-30)).max()) if nz.any() else 0.0
+
+    check = {"rows_checked": rows, "samples_checked": int(len(covered)),
+             "max_rel_err_per_sample_kd": None if w.paired else rel_err(last["seg_sum"], "kd", False),
+             "max_rel_err_per_sample_nll": rel_err(last["mean_s"], "nll_s", True),
+             "max_rel_err_per_sample_teacher_nll": rel_err(last["mean_t"], "nll_t", True) if w.teacher == "dense" else None,
+             "max_abs_err_grad": grad_err if grad_rows else None, "grad_rows_checked": grad_rows,
+             "seg_count_mismatches": None, "tolerance": {"per_sample_rel": 1e-3, "grad_max_abs": 2e-3}}
+    if len(covered):
+        seg = npd_oracle.segment_reduce(ref["nll_s"][:rows], lay.loss_mask[:rows], cu_cov, want_token_to_sample=False)
+        check["seg_count_mismatches"] = int((last["seg_cnt"].cpu().numpy()[:len(covered)] != seg["count"]).sum())
+    errs = [check[k] for k in ("max_rel_err_per_sample_kd", "max_rel_err_per_sample_nll",
+                               "max_rel_err_per_sample_teacher_nll") if check[k] is not None]
+    check["ok"] = bool(all(e <= 1e-3 for e in errs) and (check["max_abs_err_grad"] is None or
+                                                          check["max_abs_err_grad"] <= 2e-3)
+                       and not check["seg_count_mismatches"])
+    return base, check
 
 
 if __name__ == "__main__":

@@ -124,6 +124,13 @@ int npd_version(void);
 const char* npd_status_string(npd_status st);
 
 /*
+ * Name of the kernel family npd_kd_loss_fwd_bwd launches for `desc` when every row is 16-byte aligned and the
+ * workspace npd_workspace_bytes() asks for is given ("kd_gang_kernel", "kd_cached_kernel", "kd_rows_kernel",
+ * "div_rows_kernel"; "" for an invalid desc): lets a benchmark or profile say what it measured.  Static string.
+ */
+const char* npd_kd_kernel_name(const npd_kd_desc* desc);
+
+/*
  * Testing aid: how many times a workgroup of the row-gang kernels polls for the other workgroups of its row before
  * it gives up (NPD_DEV_GANG_TIMEOUT).  polls <= 0 restores the default (about a second).  Returns the previous
  * value.  A tiny limit lets a test reach the give-up path while every kernel still ends normally.  Process-wide.

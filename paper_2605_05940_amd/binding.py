@@ -25,7 +25,7 @@ NOALLOC_WORKSPACE_BYTES = 16 << 20   # NPD_NOALLOC_WORKSPACE_BYTES
 
 EXPORTS = ("npd_version", "npd_status_string", "npd_workspace_bytes", "npd_kd_loss_fwd_bwd",
            "npd_segment_reduce", "npd_delta_ifd_score", "npd_teacher_topk", "npd_debug_gang_spin_limit",
-           "npd_kd_loss_fwd_bwd_noalloc", "npd_policy_lag", "npd_segment_ppl")
+           "npd_kd_loss_fwd_bwd_noalloc", "npd_policy_lag", "npd_segment_ppl", "npd_kd_kernel_name")
 
 
 class NpdError(RuntimeError):
@@ -60,6 +60,8 @@ def load() -> ctypes.CDLL:
         L.npd_status_string.argtypes = [ctypes.c_int]
         L.npd_debug_gang_spin_limit.restype = ctypes.c_int
         L.npd_debug_gang_spin_limit.argtypes = [ctypes.c_int]
+        L.npd_kd_kernel_name.restype = ctypes.c_char_p
+        L.npd_kd_kernel_name.argtypes = [ctypes.POINTER(KdDesc)]
         L.npd_workspace_bytes.restype = ctypes.c_size_t
         L.npd_workspace_bytes.argtypes = [ctypes.POINTER(KdDesc)]
         L.npd_kd_loss_fwd_bwd.restype = ctypes.c_int

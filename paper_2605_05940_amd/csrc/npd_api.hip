@@ -258,6 +258,23 @@ const char* npd_status_string(npd_status st) {
 
 int npd_debug_gang_spin_limit(int polls) { return npd::set_gang_spin_limit(polls); }
 
+const char* npd_kd_kernel_name(const npd_kd_desc* desc) {
+  if (check_desc(desc) != NPD_OK) return "";
+  const npd_kd_desc& d = *desc;
+  npd::KdArgs a{};
+  a.T = d.n_tokens;
+  a.V = d.vocab;
+  a.nvec_s = (d.student_stride % 8 == 0 && (d.teacher_kind != NPD_TEACHER_DENSE_BF16 || d.teacher_stride % 8 == 0))
+                 ? d.vocab / 8
+                 : 0;
+  a.cscale = d.ce_grad_scale;
+  a.divergence = d.divergence;
+  a.need_lse1 = d.tau != 1.0f;
+  uint32_t some_workspace = 0;
+  a.ws = workspace_bytes_of(d) > 0 ? &some_workspace : nullptr;  // only tested against null
+  return npd::kd_kernel_name(a, d.teacher_kind, !(d.flags & NPD_FLAG_FWD_ONLY));
+}
+
 size_t npd_workspace_bytes(const npd_kd_desc* desc) {
   if (check_desc(desc) != NPD_OK) return 0;
   return workspace_bytes_of(*desc);

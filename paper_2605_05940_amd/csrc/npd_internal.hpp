@@ -57,6 +57,7 @@ inline hipError_t launch_kernel(void (*kernel)(Params...), dim3 grid, dim3 block
 }
 
 hipError_t launch_kd(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream);
+const char* kd_kernel_name(const KdArgs& a, int teacher_kind, bool want_grad);
 
 // divergences other than the forward KL, dense teacher (npd_div_kernels.hip)
 hipError_t launch_div(const KdArgs& a, bool want_grad, hipStream_t stream);

@@ -221,6 +221,14 @@ static hipError_t launch_teacher(const KdArgs& a, bool want_grad, hipStream_t st
   return launch_block<64, TEACHER>(a, want_grad, stream);
 }
 
+// the kernel family launch_kd picks for these arguments
+const char* kd_kernel_name(const KdArgs& a, int teacher_kind, bool want_grad) {
+  if (a.ws && gang_path_applies(a, teacher_kind, want_grad)) return "kd_gang_kernel";
+  if (cached_path_applies(a, teacher_kind, want_grad)) return "kd_cached_kernel";
+  if (a.divergence != kForwardKl) return "div_rows_kernel";
+  return "kd_rows_kernel";
+}
+
 hipError_t launch_kd(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream) {
   if (a.ws && gang_path_applies(a, teacher_kind, want_grad)) return launch_kd_gang(a, stream);
   if (cached_path_applies(a, teacher_kind, want_grad)) return launch_kd_cached(a, teacher_kind, want_grad, stream);
