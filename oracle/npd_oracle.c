@@ -607,9 +607,9 @@ int npd_oracle_policy_lag(int64_t T, int32_t S, const double *kl_tok, const uint
   for (int32_t i = 0; i < S; ++i) {
     double acc = 0.0;
     int32_t n = 0;
-    for (int64_t p = cu[i]; p < cu[i + 1]; ++p) {
-      if (mask[p]) {
-        acc += kl_tok[p];
+    for (int64_t q = cu[i]; q < cu[i + 1]; ++q) {
+      if (mask[q]) {
+        acc += kl_tok[q];
         n += 1;
       }
     }

@@ -34,7 +34,7 @@ MUTANTS = [
     ("ppl_without_exp", "ppl[i] = seg_count[i] > 0 ? exp(mean_nll[i]) : 0.0;", "ppl[i] = seg_count[i] > 0 ? mean_nll[i] : 0.0;", "perplexity"),
     ("policy_lag_mean_of_means", "const double mean = n_total > 0 ? total / (double)n_total : 0.0;", "double mm = 0.0; int32_t ns = 0; for (int32_t i = 0; i < S; ++i) if (seg_count[i] > 0) { mm += seg_mean[i]; ns += 1; }\n  const double mean = ns > 0 ? mm / ns : 0.0;", "policy_lag"),
     ("policy_lag_open_bound", "return !((float)mean <= (float)epsilon);", "return !((float)mean < (float)epsilon);", "policy_lag"),
-    ("policy_lag_counts_unscored", "      if (mask[p]) {\n        acc += kl_tok[p];", "      if (1) {\n        acc += kl_tok[p];", "policy_lag"),
+    ("policy_lag_counts_unscored", "      if (mask[q]) {\n        acc += kl_tok[q];", "      if (1) {\n        acc += kl_tok[q];", "policy_lag"),
     ("teacher_topk_tie_rule", "(best < 0 || row[c] > row[best])", "(best < 0 || row[c] >= row[best])", "teacher_topk"),
     ("reverse_kl_swapped", "if (p_s > 0.0) acc += p_s * (logp_s - logp_t);\n      u[c] = p_s > 0.0 ? logp_s - logp_t + 1.0 : 0.0;", "if (p_s > 0.0) acc += p_s * (logp_t - logp_s);\n      u[c] = p_s > 0.0 ? logp_t - logp_s + 1.0 : 0.0;", "divergence"),
     ("reverse_kl_zero_probability_entry", "u[c] = p_s > 0.0 ? logp_s - logp_t + 1.0 : 0.0;", "u[c] = logp_s - logp_t + 1.0;", "minus_infinity"),
