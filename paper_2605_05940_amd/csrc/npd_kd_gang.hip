@@ -37,8 +37,11 @@ size_t gang_workspace_bytes(int64_t T, int32_t V, bool lse1) {
 template <bool LSE1, int DIVK>
 static hipError_t launch_gang(const KdArgs& a, hipStream_t stream) {
   const size_t words = (size_t)a.T * a.gang * gang_words(LSE1 ? 4 : 2);
-  const hipError_t e =
-      launch_kernel(gang_clear_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream, a.ws, words);
+  const int pieces = (a.nvec_s + kPieceGroups - 1) / kPieceGroups;
+  const int64_t want = a.T * pieces;
+  const int64_t fill_grid = want < 8 * (int64_t)compute_units() ? want : 8 * (int64_t)compute_units();
+  const hipError_t e = launch_kernel(gang_prepare_kernel, dim3((unsigned)fill_grid), dim3(256), 0, stream, a.ws, words, a.g,
+                                     a.mask, a.T, a.s_stride, a.nvec_s, pieces);
   if (e != hipSuccess) return e;
   return launch_kernel(kd_gang_kernel<kGangK, kDense, LSE1, DIVK>, dim3((unsigned)(a.T * a.gang)), dim3(kGangThreads), 0,
                        stream, a);

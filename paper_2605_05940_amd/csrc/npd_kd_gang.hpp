@@ -30,6 +30,58 @@ constexpr int kGangMax = 32;                      // slices per row at most
 constexpr uint32_t kGangEmpty = 0xffffffffu;      // scratch word not posted yet (a NaN pattern no partial is stored as)
 constexpr int kGangSpinLimitDefault = 1 << 20;    // polls before a workgroup gives up (seconds; never reached in a healthy run)
 
+// ---- merging partial log-sum-exps: largest reference first, every partial rescaled to it once, then plain sums.
+// Cross-lane steps are DPP operands of the adds (no LDS traffic, no address arithmetic); the order of operations is
+// fixed, so results are bitwise reproducible and two streams fed the same data stay bitwise identical.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_move(float old, float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, old), __builtin_bit_cast(int, x),
+                                                               CTRL, ROW_MASK, 0xf, false));
+}
+__device__ __forceinline__ float lane63(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
+}
+// sum over the 64 lanes, every lane gets the total: pairs, quads, half rows, rows of 16, then lane 15 of rows 0 / 2
+// into rows 1 / 3 and lane 31 into rows 2 and 3, so that lane 63 holds everything
+__device__ __forceinline__ float wave_sum_dpp(float x) {
+  x += dpp_move<0xb1, 0xf>(0.0f, x);   // quad_perm [1, 0, 3, 2]
+  x += dpp_move<0x4e, 0xf>(0.0f, x);   // quad_perm [2, 3, 0, 1]
+  x += dpp_move<0x141, 0xf>(0.0f, x);  // row_half_mirror
+  x += dpp_move<0x140, 0xf>(0.0f, x);  // row_mirror
+  x += dpp_move<0x142, 0xa>(0.0f, x);  // row_bcast:15 into rows 1 and 3
+  x += dpp_move<0x143, 0xc>(0.0f, x);  // row_bcast:31 into rows 2 and 3
+  return lane63(x);
+}
+__device__ __forceinline__ float wave_max_dpp(float x) {
+  x = __builtin_fmaxf(x, dpp_move<0xb1, 0xf>(x, x));
+  x = __builtin_fmaxf(x, dpp_move<0x4e, 0xf>(x, x));
+  x = __builtin_fmaxf(x, dpp_move<0x141, 0xf>(x, x));
+  x = __builtin_fmaxf(x, dpp_move<0x140, 0xf>(x, x));
+  x = __builtin_fmaxf(x, dpp_move<0x142, 0xa>(x, x));
+  x = __builtin_fmaxf(x, dpp_move<0x143, 0xc>(x, x));
+  return lane63(x);
+}
+// merges the 64 lanes' partials (sum = z 2^r, cross term a 2^r); every lane returns with the total
+template <bool CROSS>
+__device__ __forceinline__ void wave_merge_rescaled(Lse& v) {
+  const float R = wave_max_dpp(v.r);
+  const float f = exp2_fast(v.r - R);  // exactly 1 where r == R; 0 for empty partials far below
+  v.z = wave_sum_dpp(__fmul_rn(v.z, f));
+  if constexpr (CROSS) v.a = wave_sum_dpp(__fmul_rn(v.a, f));
+  v.r = R;
+}
+// a lane's partial with its sum brought into [1, 2): r takes up the exponent of z, so that later rescaling to a
+// larger reference can only shrink values (z may be anywhere below 2^100 when the reference was a guess)
+__device__ __forceinline__ void normalise(Lse& v) {
+  const int e = (int)((__builtin_bit_cast(uint32_t, v.z) >> 23) & 0xffu) - 127;
+  if (v.z > 0.0f && e > -127 && e < 128) {  // normal, positive (zero, NaN and infinity stay as they are)
+    const float down = __builtin_bit_cast(float, (uint32_t)(127 - e) << 23);  // 2^-e
+    v.z = __fmul_rn(v.z, down);
+    v.a = __fmul_rn(v.a, down);
+    v.r += (float)e;
+  }
+}
+
 __device__ __forceinline__ void gang_post(uint32_t* p, float v) {
   uint32_t w = __builtin_bit_cast(uint32_t, v);
   if (w == kGangEmpty) w = 0x7fc00000u;  // another NaN
@@ -39,9 +91,41 @@ __device__ __forceinline__ void gang_post(uint32_t* p, float v) {
 // words of scratch per slice: 3 per partial log-sum-exp, rounded up to a power of two
 __host__ __device__ constexpr int gang_words(int ns) { return ns == 2 ? 8 : 16; }
 
-__global__ __launch_bounds__(256) void gang_clear_kernel(uint32_t* p, size_t n) {
-  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i < n) p[i] = kGangEmpty;
+// Runs in front of every launch of the row-gang kernel: clears the scratch record, and zero-fills the gradient rows of
+// the positions that are not scored.  The loss kernel has 127 registers per thread, four workgroups per CU: as a
+// zero-filler it reaches 4.6 TB/s; this one -- a few registers, workgroups that walk the gradient front to back in
+// pieces of 16 KB -- writes at the rate of a plain fill (6.5 .. 6.9 TB/s), and the loss kernel's workgroups of such rows
+// end at once (1,500 workgroups per microsecond).
+constexpr int kPieceGroups = 1024;  // 128-bit groups per piece: four stores per thread
+
+__global__ __launch_bounds__(256) void gang_prepare_kernel(uint32_t* ws, size_t words, uint16_t* g,
+                                                           const uint8_t* __restrict__ mask, int64_t T,
+                                                           int64_t stride, int nvec, int pieces) {
+  const int tid = threadIdx.x;
+  for (size_t i = (size_t)blockIdx.x * 256 + tid; i < words; i += (size_t)gridDim.x * 256) ws[i] = kGangEmpty;
+  // piece c = blockIdx.x + i * gridDim.x, i = 0, 1, ...: the chip walks the gradient front to back.  The mask bytes of 64
+  // pieces ahead are fetched by the 64 lanes at once, so that a workgroup does not wait for memory once per piece.
+  const uint64_t n = (uint64_t)T * (uint64_t)pieces;
+  const u32x4 z = {0, 0, 0, 0};
+  const int lane = tid & 63;
+  for (uint64_t c0 = blockIdx.x; c0 < n; c0 += 64ull * gridDim.x) {
+    const uint64_t c = c0 + (uint64_t)lane * gridDim.x;
+    const uint64_t row = c / (uint64_t)pieces;
+    const bool fill = c < n && mask[row] == 0;
+    uint64_t todo = __builtin_amdgcn_ballot_w64(fill);  // the same in every wave of the workgroup
+    while (todo) {
+      const int i = __builtin_ctzll(todo);
+      todo &= todo - 1;
+      const uint64_t ci = c0 + (uint64_t)i * gridDim.x;
+      const uint64_t ri = ci / (uint64_t)pieces;
+      const int piece = (int)(ci - ri * (uint64_t)pieces);
+      u32x4* p = reinterpret_cast<u32x4*>(g + ri * stride) + (size_t)piece * kPieceGroups;
+      const int left = nvec - piece * kPieceGroups;
+#pragma unroll
+      for (int j = 0; j < kPieceGroups / 256; ++j)
+        if (j * 256 + tid < left) p[j * 256 + tid] = z;
+    }
+  }
 }
 
 // K: groups per thread and tensor a slice may have (the slice of a launch has a.gang_groups <= K * 256 groups).
@@ -70,17 +154,13 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
   const int ng = g1 > g0 ? g1 - g0 : 0;
   uint16_t* grow = a.g + row * a.s_stride;
 
-  if (!a.mask[row]) {  // not scored: scalars 0, gradient slice zero-filled, logits never read
-    if (slice == 0 && tid == 0) {
+  if (!a.mask[row]) {  // not scored: scalars 0, logits never read; gang_prepare_kernel has zero-filled the row's
+    if (slice == 0 && tid == 0) {  // 128-bit groups, the sub-group tail is left to the last slice
       if (a.kd) a.kd[row] = 0.0f;
       if (a.nll) a.nll[row] = 0.0f;
       if (a.tnll) a.tnll[row] = 0.0f;
       if (a.lse) a.lse[row] = 0.0f;
     }
-    const uint4 z = make_uint4(0, 0, 0, 0);
-#pragma unroll
-    for (int k = 0; k < K; ++k)
-      if (k * TH + tid < ng) st16_stream(grow, g0 + k * TH + tid, z);
     if (last)
       for (int e = nvec * 8 + tid; e < V; e += TH) grow[e] = 0;
     return;
@@ -125,11 +205,61 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
   for (int i = 0; i < NS; ++i) acc[i].init();
   __builtin_amdgcn_sched_barrier(0);
 
-  // ---- sweep 1 over the slice
+  // ---- sweep 1 over the slice.  Fast form: a thread's reference exponents are fixed by its first group and no
+  // element is inspected again -- right unless a later logit lies 2^100 above them or a logit is -inf (a masked
+  // vocabulary entry: 0 * -inf in the cross term), which shows in the sums; a wave that sees such a sum takes the
+  // careful form below (references that follow the data, guarded differences) over the same registers.
+  if (ng > tid) {  // (threads without a group keep their empty partials)
+    float x0[8];
+    unpack8(sreg[0], x0);
+    const float ms = max8(x0);
+    unpack8(treg[0], x0);
+    const float mt = max8(x0);
+    acc[0].r = __builtin_fmaxf(ms * c, -1.0e30f);
+    acc[1].r = __builtin_fmaxf(mt * c, -1.0e30f);
+    if constexpr (LSE1) {
+      acc[2].r = __builtin_fmaxf(ms * kLog2e, -1.0e30f);
+      acc[3].r = __builtin_fmaxf(mt * kLog2e, -1.0e30f);
+    }
+  }
 #pragma unroll
   for (int k = 0; k < K; ++k) {
-    if (k * TH + tid < ng) accum8<kDense, LSE1, REV>(sreg[k], treg[k], c, lse1_t, acc);
+    if (k * TH + tid < ng) {
+      float xs[8], xt[8];
+      unpack8(sreg[k], xs);
+      unpack8(treg[k], xt);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float es = exp2_fast(__builtin_fmaf(xs[j], c, -acc[0].r));
+        const float et = exp2_fast(__builtin_fmaf(xt[j], c, -acc[1].r));
+        acc[0].z += es;
+        acc[1].z += et;
+        if constexpr (REV)
+          acc[0].a = __builtin_fmaf(es, xs[j] - xt[j], acc[0].a);
+        else
+          acc[1].a = __builtin_fmaf(et, xt[j] - xs[j], acc[1].a);
+        if constexpr (LSE1) {
+          acc[2].z += exp2_fast(__builtin_fmaf(xs[j], kLog2e, -acc[2].r));
+          if (lse1_t) acc[3].z += exp2_fast(__builtin_fmaf(xt[j], kLog2e, -acc[3].r));
+        }
+      }
+    }
     __builtin_amdgcn_sched_barrier(0);
+  }
+  {
+    constexpr float kBig = 1.2676506e30f;  // 2^100
+    bool odd = false;
+#pragma unroll
+    for (int i = 0; i < NS; ++i) odd = odd || !(acc[i].z < kBig) || !(fabsf(acc[i].a) < kBig);
+    if (__builtin_amdgcn_ballot_w64(odd) != 0) {  // wave-uniform
+#pragma unroll
+      for (int i = 0; i < NS; ++i) acc[i].init();
+#pragma unroll
+      for (int k = 0; k < K; ++k) {
+        if (k * TH + tid < ng) accum8<kDense, LSE1, REV>(sreg[k], treg[k], c, lse1_t, acc);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
   }
   if (last) {
     for (int e = nvec * 8 + tid; e < V; e += TH) {
@@ -148,9 +278,41 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
       }
     }
   }
-  block_merge<TH, NS>(acc, red);
 
-  // ---- post this slice's partials, wait for the row's, merge them in one fixed tree
+  // ---- wave totals, workgroup totals (through LDS), post, wait for the row's, row totals: the same merge each time
+  const int lane = tid & (kWave - 1), wid = tid / kWave;
+  constexpr int NWV = TH / kWave;
+#pragma unroll
+  for (int i = 0; i < NS; ++i) {
+    normalise(acc[i]);
+    if (i < 2)
+      wave_merge_rescaled<true>(acc[i]);
+    else
+      wave_merge_rescaled<false>(acc[i]);
+  }
+  if (lane == 0) {
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+      red[(i * 3 + 0) * NWV + wid] = acc[i].r;
+      red[(i * 3 + 1) * NWV + wid] = acc[i].z;
+      red[(i * 3 + 2) * NWV + wid] = acc[i].a;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < NS; ++i) {
+    acc[i].init();
+    if (lane < NWV) {
+      acc[i].r = red[(i * 3 + 0) * NWV + lane];
+      acc[i].z = red[(i * 3 + 1) * NWV + lane];
+      acc[i].a = red[(i * 3 + 2) * NWV + lane];
+    }
+    if (i < 2)
+      wave_merge_rescaled<true>(acc[i]);
+    else
+      wave_merge_rescaled<false>(acc[i]);
+  }
+
   uint32_t* rec = a.ws + (size_t)blockIdx.x * W;  // scratch[row][slice]
   if (tid < NW3) {
     float v = acc[0].r;
@@ -183,32 +345,18 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
   }
   __syncthreads();
   const bool timeout = gave_up != 0;  // uniform
-  {
-    // lane l starts from slice l mod NG (NG = G rounded up to a power of two; slices past G are empty partials), a
-    // butterfly over log2(NG) steps merges them, and lane 0's result is what every lane of every workgroup of the row
-    // keeps: one fixed order of operations
-    const int NG = a.gang_pow2;
-    const int lane = tid & (kWave - 1);
-    const int s = lane & (NG - 1);
 #pragma unroll
-    for (int i = 0; i < NS; ++i) {
-      Lse t;
-      t.init();
-      if (s < G) {
-        t.r = __builtin_bit_cast(float, xch[s * W + i * 3 + 0]);
-        t.z = __builtin_bit_cast(float, xch[s * W + i * 3 + 1]);
-        t.a = __builtin_bit_cast(float, xch[s * W + i * 3 + 2]);
-      }
-      for (int off = NG >> 1; off > 0; off >>= 1) {
-        const float r2 = __shfl_xor(t.r, off, kWave);
-        const float z2 = __shfl_xor(t.z, off, kWave);
-        const float a2 = __shfl_xor(t.a, off, kWave);
-        t.merge(r2, z2, a2);
-      }
-      acc[i].r = __shfl(t.r, 0, kWave);
-      acc[i].z = __shfl(t.z, 0, kWave);
-      acc[i].a = __shfl(t.a, 0, kWave);
+  for (int i = 0; i < NS; ++i) {  // lane s < G takes slice s: every wave of every workgroup of the row computes the
+    acc[i].init();                // same totals in the same order
+    if (lane < G) {
+      acc[i].r = __builtin_bit_cast(float, xch[lane * W + i * 3 + 0]);
+      acc[i].z = __builtin_bit_cast(float, xch[lane * W + i * 3 + 1]);
+      acc[i].a = __builtin_bit_cast(float, xch[lane * W + i * 3 + 2]);
     }
+    if (i < 2)
+      wave_merge_rescaled<true>(acc[i]);
+    else
+      wave_merge_rescaled<false>(acc[i]);
   }
 
   const float Ls = acc[0].log2_sum();
@@ -252,40 +400,57 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
   }
 
   // ---- sweep 2: the gradient of the slice, from the registers, last group first
+  uint8_t* gslice = reinterpret_cast<uint8_t*>(grow) + (size_t)g0 * 16;
+  auto store = [&](int k, const uint4& o) {
+    const u32x4 w = {o.x, o.y, o.z, o.w};
+    __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(gslice + (uint32_t)(voff + k * GB)));
+  };
   if (timeout || (ce && bad_label)) {  // uniform: the row cannot be differentiated
     const uint4 q = make_uint4(0x7fc07fc0u, 0x7fc07fc0u, 0x7fc07fc0u, 0x7fc07fc0u);
 #pragma unroll
     for (int k = 0; k < K; ++k)
-      if (k * TH + tid < ng) st16_stream(grow, g0 + k * TH + tid, q);
+      if (k * TH + tid < ng) store(k, q);
     if (last)
       for (int e = nvec * 8 + tid; e < V; e += TH) grow[e] = 0x7fc0;
     return;
   }
-  // the label position of the composite loss (Eq. 1): its final value, from fp32, rounded once
-  uint32_t y_bits = 0;
-  const int y_group = (ce && own_y) ? (y >> 3) - g0 : -1;  // group of the slice that holds the label (this thread's if
-  const bool y_mine = y_group >= 0 && (y >> 3) < nvec && (y_group % TH) == tid;  // y_group = k * TH + tid)
-  if (ce && own_y) {
+  // The label position of the composite loss (Eq. 1) gets its final value from fp32, rounded once: the group that
+  // holds it is the same for every thread (k_y, uniform), the thread that owns it keeps a mask and the bits.
+  int k_y = -1;
+  uint4 y_keep = make_uint4(~0u, ~0u, ~0u, ~0u), y_bits = make_uint4(0, 0, 0, 0);
+  uint16_t y_tail = 0;
+  if (ce && own_y) {  // uniform
     float gy;
     if constexpr (REV)
       gy = grad_reverse_elem(s_y, t_y, kf);
     else
       gy = grad_dense_elem(s_y, t_y, kf.p);
-    y_bits = one_bf16(gy - a.cscale);
+    const uint32_t b16 = one_bf16(gy - a.cscale);
+    y_tail = (uint16_t)b16;
+    if ((y >> 3) < nvec) {
+      const int yg = (y >> 3) - g0;  // group of the slice
+      k_y = yg / TH;
+      if (yg - k_y * TH == tid) {
+        const int j = y & 7;
+        const uint32_t keep = (j & 1) ? 0x0000ffffu : 0xffff0000u, bits = (j & 1) ? b16 << 16 : b16;
+        if ((j >> 1) == 0) { y_keep.x = keep; y_bits.x = bits; }
+        if ((j >> 1) == 1) { y_keep.y = keep; y_bits.y = bits; }
+        if ((j >> 1) == 2) { y_keep.z = keep; y_bits.z = bits; }
+        if ((j >> 1) == 3) { y_keep.w = keep; y_bits.w = bits; }
+      }
+    }
   }
-  auto patch_label = [&](uint4& o) {
-    const int j = y & 7;
-    const uint32_t m = (j & 1) ? 0x0000ffffu : 0xffff0000u, b = (j & 1) ? y_bits << 16 : y_bits;
-    if ((j >> 1) == 0) o.x = (o.x & m) | b;
-    if ((j >> 1) == 1) o.y = (o.y & m) | b;
-    if ((j >> 1) == 2) o.z = (o.z & m) | b;
-    if ((j >> 1) == 3) o.w = (o.w & m) | b;
+  auto patch_label = [&](uint4& o) {  // a no-op in every thread but the one that owns the label
+    o.x = (o.x & y_keep.x) | y_bits.x;
+    o.y = (o.y & y_keep.y) | y_bits.y;
+    o.z = (o.z & y_keep.z) | y_bits.z;
+    o.w = (o.w & y_keep.w) | y_bits.w;
   };
   if (last) {
     for (int e = nvec * 8 + tid; e < V; e += TH) {
       const float xs = bf16_one(srow[e]), xt = bf16_one(trow[e]);
       uint16_t o = one_bf16(REV ? grad_reverse_elem(xs, xt, kf) : grad_dense_elem(xs, xt, kf.p));
-      if (ce && own_y && e == y) o = (uint16_t)y_bits;
+      if (ce && own_y && e == y) o = y_tail;
       grow[e] = o;
     }
   }
@@ -294,8 +459,8 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
     for (int k = K - 1; k >= 0; --k) {
       opaque(sreg[k]);
       uint4 o = grad8<kDense, true, DIVK>(sreg[k], treg[k], kf);
-      if (y_mine && y_group == k * TH + tid) patch_label(o);
-      if (k * TH + tid < ng) st16_stream(grow, g0 + k * TH + tid, o);
+      if (k == k_y) patch_label(o);  // uniform
+      if (k * TH + tid < ng) store(k, o);
       __builtin_amdgcn_sched_barrier(0);
     }
   } else {  // rows whose reference exponents are in the thousands: precise form
@@ -303,8 +468,8 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
     for (int k = K - 1; k >= 0; --k) {
       opaque(sreg[k]);
       uint4 o = grad8<kDense, false, DIVK>(sreg[k], treg[k], kf);
-      if (y_mine && y_group == k * TH + tid) patch_label(o);
-      if (k * TH + tid < ng) st16_stream(grow, g0 + k * TH + tid, o);
+      if (k == k_y) patch_label(o);  // uniform
+      if (k * TH + tid < ng) store(k, o);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
