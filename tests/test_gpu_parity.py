@@ -47,7 +47,7 @@ def test_cfg0_tiny_dense_full(oracle):
     gpu = run_gpu_kd(s, mask, t=t, labels=labels, tau=w.tau)
     ref = oracle.kd_dense(_bits(s), _bits(t), lay.labels, lay.loss_mask, tau=w.tau)
     assert gpu["status"] == 0
-    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle)
+    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle, folded=False)
     # rows of the bf16 gradient sum to ~0 (each element carries up to half a bf16 step)
     assert np.abs(gpu["grad"].sum(1)).max() < 1e-2
 
@@ -85,7 +85,9 @@ def test_dense_shapes(oracle, V, stride, tau, scale, no_workspace):
     ref = oracle.kd_dense(_bits(s.contiguous()), _bits(t.contiguous()), lay.labels, lay.loss_mask, tau=tau,
                           grad_scale=scale)
     assert gpu["status"] == 0
-    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle, grad_scale=scale, tau=tau)
+    # rows shorter than 8,192 entries or not 16-byte aligned run the streaming kernel: always the precise gradient form
+    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle, grad_scale=scale, tau=tau,
+               folded=V >= 8192 and stride % 8 == 0)
 
 
 def test_dense_forward_only_and_tau_not_one_nll(oracle):
@@ -1202,7 +1204,8 @@ def test_seeded_random_shapes(oracle, i):
     _say(f"random case {i}: {c}")
     lay, s, t, mask, labels = _inputs(w, c["stride"], dense_teacher=c["kind"] == "dense")
     sb = _bits(s.contiguous())
-    tol = dict(grad_scale=c["scale"], tau=c["tau"], amp_from_ref=c["div"] != "forward" or c["ce"] != 0.0)
+    tol = dict(grad_scale=c["scale"], tau=c["tau"], amp_from_ref=c["div"] != "forward" or c["ce"] != 0.0,
+               folded=not (c["div"] == "forward" and (V < 8192 or c["stride"] % 8 != 0)))
     want_grad = not c["fwd_only"]
     if c["kind"] == "dense":
         tb = _bits(t.contiguous())
