@@ -369,6 +369,8 @@ def bench_teacher_topk(args, binding, synth, dev):
     n_scored = int(lay.loss_mask.sum())
     alg_bytes = n_scored * (2 * V) + T * k * 8          # scored rows read once; every row's record written
     achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
+    topk_traffic, topk_traffic_source = counted_traffic(f"{w.name}/teacher_topk_k{k}", "teacher_topk_stream_kernel",
+                                                        binding.version())
     out = {
         "metric": "teacher_topk_tokens_per_sec", "value": T * args.steps / elapsed, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / args.steps,
@@ -377,8 +379,9 @@ def bench_teacher_topk(args, binding, synth, dev):
                    "tokens": T, "scored_tokens": n_scored},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TOPK_TRAFFIC_BYTES.get(k) if args.config == 1 else None,
-                     "kernel": "npd::teacher_topk_stream_kernel", "kernel_ms": kernel_ms,
+                     "traffic": topk_traffic, "traffic_source": topk_traffic_source,
+                     "kernel": "npd::teacher_topk_stream_kernel", "npd_version": binding.version(),
+                     "kernel_ms": kernel_ms,
                      "algorithmic_bytes_per_launch": alg_bytes},
     }
     if not args.no_cpu_baseline:

@@ -82,6 +82,21 @@ __device__ __forceinline__ void normalise(Lse& v) {
   }
 }
 
+// Largest of the eight bf16 values packed in a group, as a float -- by packed 16-bit integer maxima on the bit
+// patterns, which order non-negative values correctly and put every negative value below them.  Among negative
+// values alone the integer order is the reverse of the value order, so for a group whose logits are all negative the
+// result is its smallest logit: still a usable reference exponent (lower by the spread of the group), and the
+// caller's check of the sums catches the case where that is not enough.
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pk_max_i16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2, a), __builtin_bit_cast(s16x2, b)));
+}
+__device__ __forceinline__ uint32_t pk_max_group(const uint4& v) { return pk_max_i16(pk_max_i16(v.x, v.y), pk_max_i16(v.z, v.w)); }
+__device__ __forceinline__ float pk_max_value(uint32_t m) {
+  const int lo = (int)(short)(m & 0xffffu), hi = (int)(short)(m >> 16);
+  return bf16_one((uint16_t)(lo > hi ? lo : hi));
+}
+
 __device__ __forceinline__ void gang_post(uint32_t* p, float v) {
   uint32_t w = __builtin_bit_cast(uint32_t, v);
   if (w == kGangEmpty) w = 0x7fc00000u;  // another NaN
@@ -172,10 +187,13 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
   const bool lse1_t = LSE1 && a.tnll != nullptr;
   if (tid == 0) gave_up = 0;  // ordered before its use by the barriers of block_merge
 
-  // the slice as a buffer: groups past its end read as zero and are never used
+  // The slice as a buffer: all of a thread's groups are requested at once, unconditionally (a predicate around a load
+  // makes the compiler wait for it on the spot); groups past the slice's end read as zero and are never used.  Groups
+  // k < q are whole for every thread, group q belongs to the first `part` threads.
   const __amdgpu_buffer_rsrc_t rs = row_rsrc(srow + (size_t)g0 * 8, ng);
   const __amdgpu_buffer_rsrc_t rt = row_rsrc(trow + (size_t)g0 * 8, ng);
   const int voff = tid * 16;
+  const int q = ng / TH, part = ng - q * TH;  // uniform
   uint4 sreg[K], treg[K];
 #pragma unroll
   for (int k = 0; k < K; ++k) {
@@ -205,26 +223,27 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
   for (int i = 0; i < NS; ++i) acc[i].init();
   __builtin_amdgcn_sched_barrier(0);
 
-  // ---- sweep 1 over the slice.  Fast form: a thread's reference exponents are fixed by its first group and no
-  // element is inspected again -- right unless a later logit lies 2^100 above them or a logit is -inf (a masked
-  // vocabulary entry: 0 * -inf in the cross term), which shows in the sums; a wave that sees such a sum takes the
-  // careful form below (references that follow the data, guarded differences) over the same registers.
+  // ---- sweep 1 over the slice.  Fast form: a thread's reference exponents are fixed by its first group -- the
+  // largest of its eight logits (integer maxima on the packed bit patterns, see pk_max_i16) plus kRefBias bits of
+  // head room -- before the other groups have arrived, and no element is inspected again.  Terms are then 2^-100 and
+  // below, sums stay far inside the fp32 range while no later logit exceeds the first group's by 2^200 (139 nats at
+  // tau = 1), and a term that matters (within 2^-24 of the row's largest) cannot underflow.  What this form cannot take
+  // -- a wider excursion, a logit of -inf (a masked vocabulary entry: 0 * -inf in the cross term) -- shows in the sums;
+  // a wave that sees such a sum takes the careful form below (references that follow the data, guarded differences)
+  // over the same registers.
+  constexpr float kRefBias = 100.0f;
   if (ng > tid) {  // (threads without a group keep their empty partials)
-    float x0[8];
-    unpack8(sreg[0], x0);
-    const float ms = max8(x0);
-    unpack8(treg[0], x0);
-    const float mt = max8(x0);
-    acc[0].r = __builtin_fmaxf(ms * c, -1.0e30f);
-    acc[1].r = __builtin_fmaxf(mt * c, -1.0e30f);
+    const float fs = pk_max_value(pk_max_group(sreg[0])), ft = pk_max_value(pk_max_group(treg[0]));
+    acc[0].r = __builtin_fmaxf(__builtin_fmaf(fs, c, kRefBias), -1.0e30f);
+    acc[1].r = __builtin_fmaxf(__builtin_fmaf(ft, c, kRefBias), -1.0e30f);
     if constexpr (LSE1) {
-      acc[2].r = __builtin_fmaxf(ms * kLog2e, -1.0e30f);
-      acc[3].r = __builtin_fmaxf(mt * kLog2e, -1.0e30f);
+      acc[2].r = __builtin_fmaxf(__builtin_fmaf(fs, kLog2e, kRefBias), -1.0e30f);
+      acc[3].r = __builtin_fmaxf(__builtin_fmaf(ft, kLog2e, kRefBias), -1.0e30f);
     }
   }
 #pragma unroll
   for (int k = 0; k < K; ++k) {
-    if (k * TH + tid < ng) {
+    if (k < q || (k == q && tid < part)) {
       float xs[8], xt[8];
       unpack8(sreg[k], xs);
       unpack8(treg[k], xt);
@@ -256,7 +275,7 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
       for (int i = 0; i < NS; ++i) acc[i].init();
 #pragma unroll
       for (int k = 0; k < K; ++k) {
-        if (k * TH + tid < ng) accum8<kDense, LSE1, REV>(sreg[k], treg[k], c, lse1_t, acc);
+        if (k < q || (k == q && tid < part)) accum8<kDense, LSE1, REV>(sreg[k], treg[k], c, lse1_t, acc);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -401,15 +420,15 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
 
   // ---- sweep 2: the gradient of the slice, from the registers, last group first
   uint8_t* gslice = reinterpret_cast<uint8_t*>(grow) + (size_t)g0 * 16;
-  auto store = [&](int k, const uint4& o) {
+  auto store = [&](int k, const uint4& o) {  // the group's base is uniform, the thread adds tid * 16
     const u32x4 w = {o.x, o.y, o.z, o.w};
-    __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(gslice + (uint32_t)(voff + k * GB)));
+    __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(gslice + (size_t)k * GB) + tid);
   };
   if (timeout || (ce && bad_label)) {  // uniform: the row cannot be differentiated
-    const uint4 q = make_uint4(0x7fc07fc0u, 0x7fc07fc0u, 0x7fc07fc0u, 0x7fc07fc0u);
+    const uint4 qnan = make_uint4(0x7fc07fc0u, 0x7fc07fc0u, 0x7fc07fc0u, 0x7fc07fc0u);
 #pragma unroll
     for (int k = 0; k < K; ++k)
-      if (k * TH + tid < ng) store(k, q);
+      if (k < q || (k == q && tid < part)) store(k, qnan);
     if (last)
       for (int e = nvec * 8 + tid; e < V; e += TH) grow[e] = 0x7fc0;
     return;
@@ -457,19 +476,21 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
   if (kf.folded) {  // uniform
 #pragma unroll
     for (int k = K - 1; k >= 0; --k) {
-      opaque(sreg[k]);
+      opaque(sreg[k]);  // sweep 2 unpacks the registers again instead of keeping sweep 1's floats alive
+      opaque(treg[k]);
       uint4 o = grad8<kDense, true, DIVK>(sreg[k], treg[k], kf);
       if (k == k_y) patch_label(o);  // uniform
-      if (k * TH + tid < ng) store(k, o);
+      if (k < q || (k == q && tid < part)) store(k, o);
       __builtin_amdgcn_sched_barrier(0);
     }
   } else {  // rows whose reference exponents are in the thousands: precise form
 #pragma unroll
     for (int k = K - 1; k >= 0; --k) {
       opaque(sreg[k]);
+      opaque(treg[k]);
       uint4 o = grad8<kDense, false, DIVK>(sreg[k], treg[k], kf);
       if (k == k_y) patch_label(o);  // uniform
-      if (k * TH + tid < ng) store(k, o);
+      if (k < q || (k == q && tid < part)) store(k, o);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
