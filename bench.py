@@ -153,7 +153,8 @@ def main():
                                         grad_out=g, kd_tok=kd, nll_tok=nll, teacher_nll_tok=tnll, dev_status=status)
         else:
             binding.npd_kd_loss_fwd_bwd(s, mask, teacher_idx=idx, teacher_val=val, labels=labels, tau=w.tau,
-                                        grad_scale=1.0, grad_out=g, kd_tok=kd, nll_tok=nll, dev_status=status)
+                                        grad_scale=1.0, no_workspace=args.no_workspace, grad_out=g, kd_tok=kd,
+                                        nll_tok=nll, dev_status=status)
         if record:
             e1.record()
             kernel_events.append((e0, e1))
@@ -224,7 +225,8 @@ def main():
                                             teacher_nll_tok=tnll, dev_status=status)
             else:
                 binding.npd_kd_loss_fwd_bwd(s, mask, teacher_idx=idx, teacher_val=val, labels=labels, tau=w.tau,
-                                            grad_out=g, kd_tok=kd, nll_tok=nll, dev_status=status)
+                                            no_workspace=args.no_workspace, grad_out=g, kd_tok=kd, nll_tok=nll,
+                                            dev_status=status)
             if i >= 2:
                 e1.record()
                 all_scored_events.append((e0, e1))

@@ -104,12 +104,14 @@ void* noalloc_scratch_address(hipError_t* err) {
 
 // workspace bytes of a call with a valid descriptor
 size_t workspace_bytes_of(const npd_kd_desc& d) {
-  // only the row-gang kernels (long rows, dense teacher, gradient, forward or reverse KL) exchange partial sums
+  // only the row-gang kernels (long rows, gradient; dense teacher with the forward or reverse KL, top-k teacher) exchange partial sums
   // through device memory; every other kernel keeps them in registers and LDS
   if (d.flags & (NPD_FLAG_FWD_ONLY | NPD_FLAG_NO_WORKSPACE)) return 0;
+  if (d.ce_grad_scale != 0.0f && d.tau != 1.0f) return 0;
+  if (d.teacher_kind == NPD_TEACHER_TOPK)  // (forward KL only: checked with the descriptor)
+    return npd::gang_workspace_bytes(d.n_tokens, d.vocab, false);
   if (d.teacher_kind != NPD_TEACHER_DENSE_BF16) return 0;
   if (d.divergence != NPD_DIV_FORWARD_KL && d.divergence != NPD_DIV_REVERSE_KL) return 0;
-  if (d.ce_grad_scale != 0.0f && d.tau != 1.0f) return 0;
   return npd::gang_workspace_bytes(d.n_tokens, d.vocab, d.tau != 1.0f);
 }
 
@@ -240,7 +242,7 @@ npd_status check_kd_call(const npd_kd_desc* desc, const void* student_logits, co
 
 extern "C" {
 
-int npd_version(void) { return 107; }
+int npd_version(void) { return 108; }
 
 const char* npd_status_string(npd_status st) {
   switch (st) {

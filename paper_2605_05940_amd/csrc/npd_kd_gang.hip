@@ -2,6 +2,7 @@
 #include <atomic>
 
 #include "npd_kd_gang.hpp"
+#include "npd_kd_gang_topk.hpp"
 
 namespace npd {
 
@@ -11,17 +12,19 @@ int set_gang_spin_limit(int polls) {
   return g_spin_limit.exchange(polls > 0 ? polls : kGangSpinLimitDefault, std::memory_order_relaxed);
 }
 
-constexpr int kGangK = 10;  // 128-bit groups per thread and tensor: 80 of a thread's 128 registers hold its slice
+constexpr int kGangK = 10;      // 128-bit groups per thread and tensor: 80 of a thread's 128 registers hold its slice
+constexpr int kGangTopkK = 10;  // top-k teacher: groups per thread of the student row alone
 
 // slices per row: a slice has at most kGangK * 256 groups (20,480 logits)
-static int gang_size(int nvec) { return (nvec + kGangK * kGangThreads - 1) / (kGangK * kGangThreads); }
+static int gang_size(int nvec, int k = kGangK) { return (nvec + k * kGangThreads - 1) / (k * kGangThreads); }
 
-// Dense teacher with gradient, forward or reverse KL, 16-byte aligned rows that span at least two slices.  (The CE
+// Gradient calls with a dense teacher (forward or reverse KL) or a top-k teacher (forward KL), 16-byte aligned rows
+// that span at least two slices.  (The CE
 // softmax of the composite loss has no temperature; this path covers it at tau = 1, where it shares the student's
 // exponentials.)
 bool gang_path_applies(const KdArgs& a, int teacher_kind, bool want_grad) {
-  if (teacher_kind != kDense || !want_grad) return false;
-  if (a.divergence != kForwardKl && a.divergence != kReverseKl) return false;
+  if ((teacher_kind != kDense && teacher_kind != kTopk) || !want_grad) return false;
+  if (a.divergence != kForwardKl && !(a.divergence == kReverseKl && teacher_kind == kDense)) return false;
   if (a.cscale != 0.0f && a.need_lse1) return false;
   const int g = gang_size(a.nvec_s);
   if (g < 2 || g > kGangMax) return false;
@@ -34,26 +37,34 @@ size_t gang_workspace_bytes(int64_t T, int32_t V, bool lse1) {
   return (size_t)T * g * gang_words(lse1 ? 4 : 2) * sizeof(uint32_t);
 }
 
-template <bool LSE1, int DIVK>
-static hipError_t launch_gang(const KdArgs& a, hipStream_t stream) {
-  const size_t words = (size_t)a.T * a.gang * gang_words(LSE1 ? 4 : 2);
+template <class Kernel>
+static hipError_t launch_gang_kernel(const KdArgs& a, int words_per_slice, Kernel kernel, hipStream_t stream) {
+  const size_t words = (size_t)a.T * a.gang * words_per_slice;
   const int pieces = (a.nvec_s + kPieceGroups - 1) / kPieceGroups;
   const int64_t want = a.T * pieces;
   const int64_t fill_grid = want < 8 * (int64_t)compute_units() ? want : 8 * (int64_t)compute_units();
   const hipError_t e = launch_kernel(gang_prepare_kernel, dim3((unsigned)fill_grid), dim3(256), 0, stream, a.ws, words, a.g,
                                      a.mask, a.T, a.s_stride, a.nvec_s, pieces);
   if (e != hipSuccess) return e;
-  return launch_kernel(kd_gang_kernel<kGangK, kDense, LSE1, DIVK>, dim3((unsigned)(a.T * a.gang)), dim3(kGangThreads), 0,
-                       stream, a);
+  return launch_kernel(kernel, dim3((unsigned)(a.T * a.gang)), dim3(kGangThreads), 0, stream, a);
 }
 
-hipError_t launch_kd_gang(const KdArgs& a0, hipStream_t stream) {
+template <bool LSE1, int DIVK>
+static hipError_t launch_gang(const KdArgs& a, hipStream_t stream) {
+  return launch_gang_kernel(a, gang_words(LSE1 ? 4 : 2), kd_gang_kernel<kGangK, kDense, LSE1, DIVK>, stream);
+}
+
+hipError_t launch_kd_gang(const KdArgs& a0, int teacher_kind, hipStream_t stream) {
   KdArgs a = a0;
-  a.gang = gang_size(a.nvec_s);
+  a.gang = gang_size(a.nvec_s, teacher_kind == kTopk ? kGangTopkK : kGangK);
   a.gang_groups = (a.nvec_s + a.gang - 1) / a.gang;
   a.gang_pow2 = 1;
   while (a.gang_pow2 < a.gang) a.gang_pow2 *= 2;
   a.spin_limit = g_spin_limit.load(std::memory_order_relaxed);
+  if (teacher_kind == kTopk) {
+    if (a.need_lse1) return launch_gang_kernel(a, 8, kd_gang_topk_kernel<kGangTopkK, true>, stream);
+    return launch_gang_kernel(a, 8, kd_gang_topk_kernel<kGangTopkK, false>, stream);
+  }
   if (a.divergence == kReverseKl)
     return a.need_lse1 ? launch_gang<true, kReverseKl>(a, stream) : launch_gang<false, kReverseKl>(a, stream);
   return a.need_lse1 ? launch_gang<true, kForwardKl>(a, stream) : launch_gang<false, kForwardKl>(a, stream);

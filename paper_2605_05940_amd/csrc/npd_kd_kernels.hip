@@ -230,7 +230,7 @@ const char* kd_kernel_name(const KdArgs& a, int teacher_kind, bool want_grad) {
 }
 
 hipError_t launch_kd(const KdArgs& a, int teacher_kind, bool want_grad, hipStream_t stream) {
-  if (a.ws && gang_path_applies(a, teacher_kind, want_grad)) return launch_kd_gang(a, stream);
+  if (a.ws && gang_path_applies(a, teacher_kind, want_grad)) return launch_kd_gang(a, teacher_kind, stream);
   if (cached_path_applies(a, teacher_kind, want_grad)) return launch_kd_cached(a, teacher_kind, want_grad, stream);
   if (a.divergence != kForwardKl) return launch_div(a, want_grad, stream);  // dense teacher (checked by the API)
   switch (teacher_kind) {

@@ -194,10 +194,11 @@ def test_topk_shapes(oracle, V, k, tau, scale, inplace):
     ref = oracle.kd_topk(_bits(s), idx.cpu().numpy(), val.cpu().numpy(), lay.labels, lay.loss_mask, tau=tau,
                          grad_scale=scale)
     assert ref["bad_index_rows"] == 0
-    gpu = run_gpu_kd(s.clone() if inplace else s, mask, idx=idx, val=val, labels=labels, tau=tau, grad_scale=scale,
-                     inplace=inplace)
-    assert gpu["status"] == 0
-    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle, grad_scale=scale, tau=tau)
+    for no_workspace in (False, True):     # row-gang kernel where it applies | one workgroup per row
+        gpu = run_gpu_kd(s.clone() if inplace else s, mask, idx=idx, val=val, labels=labels, tau=tau, grad_scale=scale,
+                         inplace=inplace, no_workspace=no_workspace)
+        assert gpu["status"] == 0
+        compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle, grad_scale=scale, tau=tau)
 
 
 def test_topk_uniform_closed_form_on_gpu():
@@ -210,8 +211,9 @@ def test_topk_uniform_closed_form_on_gpu():
     np.testing.assert_allclose(gpu["kd"], np.log(V / k), rtol=1e-5)
 
 
-def test_topk_bad_index_is_flagged():
-    V, k = 1000, 8
+@pytest.mark.parametrize("V", [1000, 151936])
+def test_topk_bad_index_is_flagged(V):
+    k = 8
     s = torch.randn((3, V), device=dev()).to(torch.bfloat16)
     idx = torch.arange(k, dtype=torch.int32, device=dev()).repeat(3, 1).contiguous()
     idx[1, 3] = V
@@ -641,6 +643,42 @@ def test_gang_slices_with_labels_on_their_edges(oracle, V, stride, tau, div):
                    amp_from_ref=div != "forward")
 
 
+@pytest.mark.parametrize("V,stride,tau", [(8 * 5121 + 5, 8 * 5122, 1.0), (151936, 151936, 2.0), (151936, 151936, 1.0)])
+def test_gang_topk_support_and_labels_on_slice_edges(oracle, V, stride, tau):
+    """Top-k teacher on rows shared by several workgroups: support positions and labels on the first and last element
+    of slices and in the sub-group tail, labels inside and outside the support; out of place and in place."""
+    assert binding.npd_workspace_bytes(4, V, teacher_kind=binding.NPD_TEACHER_TOPK, topk=24) > 0
+    nvec = V // 8
+    gang = -(-nvec // 2560)
+    per = -(-nvec // gang)
+    edges = sorted({0, 7, 8 * per - 1, 8 * per, 8 * per + 1, 8 * (gang - 1) * per - 1, 8 * (gang - 1) * per,
+                    8 * nvec - 1, V - 1, V // 2})
+    T, k = 2 * len(edges), 24
+    w = synth.scaled(synth.config(2), n_rows=1, row_len=T, vocab=V, length_lo=4, length_hi=9, topk=k)
+    lay, s, _, mask, _ = _inputs(w, stride, dense_teacher=False)
+    idx, val = synth.make_topk_teacher(w, s)
+    lab = np.array([edges[i % len(edges)] for i in range(T)], np.int32)
+    idx_np = idx.cpu().numpy().copy()
+    for r in range(T):
+        # the first entries of the support sit on slice edges (kept unique); in even rows the label is one of them
+        want = [e for e in edges if r % 2 == 0 or e != lab[r]][:10]
+        rest = [int(v) for v in idx_np[r] if int(v) not in want][:k - len(want)]
+        idx_np[r] = np.array(want + rest, np.int32)
+        assert len(set(idx_np[r].tolist())) == k
+    idx = torch.from_numpy(idx_np).to(dev())
+    labels = torch.from_numpy(lab).to(dev())
+    ce = 0.25 if tau == 1.0 else 0.0
+    _say(f"gang top-k V={V} stride={stride} gang={gang} tau={tau}")
+    ref = oracle.kd_topk(_bits(s.contiguous()), idx_np, val.cpu().numpy(), lab, lay.loss_mask, tau=tau, grad_scale=0.75,
+                         ce_grad_scale=ce)
+    assert ref["bad_index_rows"] == 0
+    for inplace in (False, True):
+        gpu = run_gpu_kd(s.clone() if inplace else s, mask, idx=idx, val=val, labels=labels, tau=tau, grad_scale=0.75,
+                         ce_grad_scale=ce, inplace=inplace)
+        assert gpu["status"] == 0
+        compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle, grad_scale=0.75 + ce, tau=tau)
+
+
 def test_gang_wait_is_bounded(oracle):
     """A workgroup of a row gang that does not see the rest of its row within its poll limit gives up, marks what it
     writes NaN and sets NPD_DEV_GANG_TIMEOUT: forced here with a limit of one poll (the kernel still ends normally);
@@ -761,10 +799,11 @@ def test_composite_gradient_topk(oracle, V, k, tau, inplace):
             idx[r, r % k] = int(lay.labels[r])
     ref = oracle.kd_topk(_bits(s), idx.cpu().numpy(), val.cpu().numpy(), lay.labels, lay.loss_mask, tau=tau,
                          grad_scale=0.9, ce_grad_scale=0.1)
-    gpu = run_gpu_kd(s.clone() if inplace else s, mask, idx=idx, val=val, labels=labels, tau=tau, grad_scale=0.9,
-                     ce_grad_scale=0.1, inplace=inplace)
-    assert gpu["status"] == 0 and ref["bad_index_rows"] == 0
-    compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle, grad_scale=0.9 + 0.1 * tau, tau=tau)
+    for no_workspace in (False, True):
+        gpu = run_gpu_kd(s.clone() if inplace else s, mask, idx=idx, val=val, labels=labels, tau=tau, grad_scale=0.9,
+                         ce_grad_scale=0.1, inplace=inplace, no_workspace=no_workspace)
+        assert gpu["status"] == 0 and ref["bad_index_rows"] == 0
+        compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle, grad_scale=0.9 + 0.1 * tau, tau=tau)
 
 
 def test_composite_gradient_bad_label_poisons_row():
@@ -1227,7 +1266,8 @@ def test_seeded_random_shapes(oracle, i):
                              grad_scale=c["scale"], ce_grad_scale=c["ce"], want_grad=want_grad)
         assert ref["bad_index_rows"] == 0
         gpu = run_gpu_kd(s.clone() if c["inplace"] else s, mask, idx=idx, val=val, labels=labels, tau=c["tau"],
-                         grad_scale=c["scale"], ce_grad_scale=c["ce"], want_grad=want_grad, inplace=c["inplace"])
+                         grad_scale=c["scale"], ce_grad_scale=c["ce"], want_grad=want_grad, inplace=c["inplace"],
+                         no_workspace=i % 2 == 1)
     else:
         nl = oracle.nll(sb, lay.labels, lay.loss_mask)
         ref = dict(nll_s=nl["nll"], lse_s=nl["lse"])
