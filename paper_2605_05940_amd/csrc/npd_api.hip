@@ -104,15 +104,14 @@ void* noalloc_scratch_address(hipError_t* err) {
 
 // workspace bytes of a call with a valid descriptor
 size_t workspace_bytes_of(const npd_kd_desc& d) {
-  // only the row-gang kernels (long rows, gradient; dense teacher with the forward or reverse KL, top-k teacher) exchange partial sums
-  // through device memory; every other kernel keeps them in registers and LDS
+  // only the row-gang kernels (gradient calls on long rows) exchange partial sums through device memory; every other
+  // kernel keeps them in registers and LDS
   if (d.flags & (NPD_FLAG_FWD_ONLY | NPD_FLAG_NO_WORKSPACE)) return 0;
   if (d.ce_grad_scale != 0.0f && d.tau != 1.0f) return 0;
   if (d.teacher_kind == NPD_TEACHER_TOPK)  // (forward KL only: checked with the descriptor)
-    return npd::gang_workspace_bytes(d.n_tokens, d.vocab, false);
+    return npd::gang_workspace_bytes(d.n_tokens, d.vocab, npd::kTopk, npd::kForwardKl, false);
   if (d.teacher_kind != NPD_TEACHER_DENSE_BF16) return 0;
-  if (d.divergence != NPD_DIV_FORWARD_KL && d.divergence != NPD_DIV_REVERSE_KL) return 0;
-  return npd::gang_workspace_bytes(d.n_tokens, d.vocab, d.tau != 1.0f);
+  return npd::gang_workspace_bytes(d.n_tokens, d.vocab, npd::kDense, d.divergence, d.tau != 1.0f);
 }
 
 // Every input and output buffer of a KD call as a byte range (empty for arguments that are absent).

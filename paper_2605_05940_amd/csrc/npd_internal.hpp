@@ -68,7 +68,7 @@ hipError_t launch_kd_cached(const KdArgs& a, int teacher_kind, bool want_grad, h
 
 // row-gang kernels for long rows with a dense teacher (npd_kd_gang.hip); `lse1`: tau != 1 and a tau = 1 quantity wanted
 bool gang_path_applies(const KdArgs& a, int teacher_kind, bool want_grad);
-size_t gang_workspace_bytes(int64_t T, int32_t V, bool lse1);
+size_t gang_workspace_bytes(int64_t T, int32_t V, int teacher_kind, int divergence, bool lse1);
 hipError_t launch_kd_gang(const KdArgs& a, int teacher_kind, hipStream_t stream);
 int set_gang_spin_limit(int polls);  // returns the previous limit; <= 0 restores the default
 

@@ -14,6 +14,12 @@ int set_gang_spin_limit(int polls) {
 
 constexpr int kGangK = 10;      // 128-bit groups per thread and tensor: 80 of a thread's 128 registers hold its slice
 constexpr int kGangTopkK = 10;  // top-k teacher: groups per thread of the student row alone
+constexpr int kGangSkewK = 5;   // skew forms: the slice is kept as two fp32 values per element from sweep 2 on
+
+static int gang_k(int teacher_kind, int divergence) {
+  if (teacher_kind == kTopk) return kGangTopkK;
+  return divergence == kSkewKl || divergence == kSkewReverseKl ? kGangSkewK : kGangK;
+}
 
 // slices per row: a slice has at most kGangK * 256 groups (20,480 logits)
 static int gang_size(int nvec, int k = kGangK) { return (nvec + k * kGangThreads - 1) / (k * kGangThreads); }
@@ -24,15 +30,15 @@ static int gang_size(int nvec, int k = kGangK) { return (nvec + k * kGangThreads
 // exponentials.)
 bool gang_path_applies(const KdArgs& a, int teacher_kind, bool want_grad) {
   if ((teacher_kind != kDense && teacher_kind != kTopk) || !want_grad) return false;
-  if (a.divergence != kForwardKl && !(a.divergence == kReverseKl && teacher_kind == kDense)) return false;
+  if (a.divergence != kForwardKl && teacher_kind != kDense) return false;
   if (a.cscale != 0.0f && a.need_lse1) return false;
-  const int g = gang_size(a.nvec_s);
+  const int g = gang_size(a.nvec_s, gang_k(teacher_kind, a.divergence));
   if (g < 2 || g > kGangMax) return false;
   return a.T * (int64_t)g <= 0x7fffffffLL;  // one workgroup per slice, 1-D grid
 }
 
-size_t gang_workspace_bytes(int64_t T, int32_t V, bool lse1) {
-  const int g = gang_size(V / 8);
+size_t gang_workspace_bytes(int64_t T, int32_t V, int teacher_kind, int divergence, bool lse1) {
+  const int g = gang_size(V / 8, gang_k(teacher_kind, divergence));
   if (g < 2 || g > kGangMax || T * (int64_t)g > 0x7fffffffLL) return 0;
   return (size_t)T * g * gang_words(lse1 ? 4 : 2) * sizeof(uint32_t);
 }
@@ -51,12 +57,13 @@ static hipError_t launch_gang_kernel(const KdArgs& a, int words_per_slice, Kerne
 
 template <bool LSE1, int DIVK>
 static hipError_t launch_gang(const KdArgs& a, hipStream_t stream) {
-  return launch_gang_kernel(a, gang_words(LSE1 ? 4 : 2), kd_gang_kernel<kGangK, kDense, LSE1, DIVK>, stream);
+  constexpr int K = DIVK == kSkewKl || DIVK == kSkewReverseKl ? kGangSkewK : kGangK;
+  return launch_gang_kernel(a, gang_words(LSE1 ? 4 : 2), kd_gang_kernel<K, kDense, LSE1, DIVK>, stream);
 }
 
 hipError_t launch_kd_gang(const KdArgs& a0, int teacher_kind, hipStream_t stream) {
   KdArgs a = a0;
-  a.gang = gang_size(a.nvec_s, teacher_kind == kTopk ? kGangTopkK : kGangK);
+  a.gang = gang_size(a.nvec_s, gang_k(teacher_kind, a.divergence));
   a.gang_groups = (a.nvec_s + a.gang - 1) / a.gang;
   a.gang_pow2 = 1;
   while (a.gang_pow2 < a.gang) a.gang_pow2 *= 2;
@@ -67,6 +74,10 @@ hipError_t launch_kd_gang(const KdArgs& a0, int teacher_kind, hipStream_t stream
   }
   if (a.divergence == kReverseKl)
     return a.need_lse1 ? launch_gang<true, kReverseKl>(a, stream) : launch_gang<false, kReverseKl>(a, stream);
+  if (a.divergence == kSkewKl)
+    return a.need_lse1 ? launch_gang<true, kSkewKl>(a, stream) : launch_gang<false, kSkewKl>(a, stream);
+  if (a.divergence == kSkewReverseKl)
+    return a.need_lse1 ? launch_gang<true, kSkewReverseKl>(a, stream) : launch_gang<false, kSkewReverseKl>(a, stream);
   return a.need_lse1 ? launch_gang<true, kForwardKl>(a, stream) : launch_gang<false, kForwardKl>(a, stream);
 }
 

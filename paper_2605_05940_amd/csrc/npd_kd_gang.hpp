@@ -31,34 +31,30 @@ constexpr uint32_t kGangEmpty = 0xffffffffu;      // scratch word not posted yet
 constexpr int kGangSpinLimitDefault = 1 << 20;    // polls before a workgroup gives up (seconds; never reached in a healthy run)
 
 // ---- merging partial log-sum-exps: largest reference first, every partial rescaled to it once, then plain sums.
-// Cross-lane steps are DPP operands of the adds (no LDS traffic, no address arithmetic); the order of operations is
+// Cross-lane steps are DPP operands of the adds and maxima (no LDS traffic, no address arithmetic); the order of operations is
 // fixed, so results are bitwise reproducible and two streams fed the same data stay bitwise identical.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_move(float old, float x) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, old), __builtin_bit_cast(int, x),
-                                                               CTRL, ROW_MASK, 0xf, false));
-}
 __device__ __forceinline__ float lane63(float x) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
 }
-// sum over the 64 lanes, every lane gets the total: pairs, quads, half rows, rows of 16, then lane 15 of rows 0 / 2
-// into rows 1 / 3 and lane 31 into rows 2 and 3, so that lane 63 holds everything
+// Sum / maximum over the 64 lanes, every lane gets the result: pairs, quads, half rows, rows of 16, then lane 15 of
+// rows 0 / 2 into rows 1 / 3 and lane 31 into rows 2 and 3, so that lane 63 holds everything.  Each step is one
+// instruction whose first operand is read through DPP (lanes that a row mask leaves out keep their value); written out
+// because the compiler spends four instructions per step on the maximum.  A DPP operand must not be read within two
+// wait states of the instruction that wrote it: hence the s_nop in front of every step.
+#define NPD_DPP_REDUCE(op)                                                  \
+  "s_nop 4\n" op " %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n" \
+  "s_nop 1\n" op " %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n" \
+  "s_nop 1\n" op " %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n"     \
+  "s_nop 1\n" op " %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n"          \
+  "s_nop 1\n" op " %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n"        \
+  "s_nop 1\n" op " %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n"        \
+  "s_nop 1\n"
 __device__ __forceinline__ float wave_sum_dpp(float x) {
-  x += dpp_move<0xb1, 0xf>(0.0f, x);   // quad_perm [1, 0, 3, 2]
-  x += dpp_move<0x4e, 0xf>(0.0f, x);   // quad_perm [2, 3, 0, 1]
-  x += dpp_move<0x141, 0xf>(0.0f, x);  // row_half_mirror
-  x += dpp_move<0x140, 0xf>(0.0f, x);  // row_mirror
-  x += dpp_move<0x142, 0xa>(0.0f, x);  // row_bcast:15 into rows 1 and 3
-  x += dpp_move<0x143, 0xc>(0.0f, x);  // row_bcast:31 into rows 2 and 3
+  asm volatile(NPD_DPP_REDUCE("v_add_f32_dpp") : "+v"(x));
   return lane63(x);
 }
 __device__ __forceinline__ float wave_max_dpp(float x) {
-  x = __builtin_fmaxf(x, dpp_move<0xb1, 0xf>(x, x));
-  x = __builtin_fmaxf(x, dpp_move<0x4e, 0xf>(x, x));
-  x = __builtin_fmaxf(x, dpp_move<0x141, 0xf>(x, x));
-  x = __builtin_fmaxf(x, dpp_move<0x140, 0xf>(x, x));
-  x = __builtin_fmaxf(x, dpp_move<0x142, 0xa>(x, x));
-  x = __builtin_fmaxf(x, dpp_move<0x143, 0xc>(x, x));
+  asm volatile(NPD_DPP_REDUCE("v_max_f32_dpp") : "+v"(x));
   return lane63(x);
 }
 // merges the 64 lanes' partials (sum = z 2^r, cross term a 2^r); every lane returns with the total
@@ -143,19 +139,80 @@ __global__ __launch_bounds__(256) void gang_prepare_kernel(uint32_t* ws, size_t 
   }
 }
 
+// ---- the skew divergences (three sweeps): sums and gradient on normalised log2-probabilities.
+//   skew KL          D = KL(p_T || m),  m = alpha p_T + (1 - alpha) p_S,  u = (alpha - 1) p_T / m
+//   skew reverse KL  D = KL(p_S || m),  m = (1 - alpha) p_T + alpha p_S,  u = ln(p_S / m) + 1 - alpha p_S / m
+// gradient = grad_scale / tau * p_S (u - ubar) with ubar = sum p_S u (+ ce_grad_scale p_S from the CE term at tau = 1).
+// Entries of probability 0 (logits of -inf, underflow) contribute nothing: m has a floor, log ratios are kept finite.
+struct SkewCoef {
+  float c, Ls, Lt;     // log2 p = x c - L
+  float alpha, beta;   // beta = 1 - alpha
+  float A, B, Cl;      // gradient coefficients, see skew_grad
+  float Av;            // coefficient of the cached v, see skew_cache
+};
+constexpr float kSkewTiny = 1.0e-37f;
+constexpr float kSkewLogFloor = -1.0e30f;
+
+// skew KL:          p_S (A p_T / m + B),                         A = (alpha - 1) g,  B = ce - g ubar
+// skew reverse KL:  p_S (Cl log2(p_S / m) + A p_S / m + B),      Cl = g ln 2,  A = -alpha g,  B = g (1 - ubar) + ce
+// with g = grad_scale / tau, ce = ce_grad_scale
+template <int DIVK>
+__device__ __forceinline__ float skew_grad(float xs, float xt, const SkewCoef& k) {
+  const float lps = __builtin_fmaf(xs, k.c, -k.Ls), lpt = __builtin_fmaf(xt, k.c, -k.Lt);
+  const float ps = exp2_fast(lps), pt = exp2_fast(lpt);
+  if constexpr (DIVK == kSkewKl) {
+    const float m = __builtin_fmaxf(__builtin_fmaf(k.alpha, pt, k.beta * ps), kSkewTiny);
+    return ps * __builtin_fmaf(pt * __builtin_amdgcn_rcpf(m), k.A, k.B);
+  } else {
+    const float m = __builtin_fmaxf(__builtin_fmaf(k.beta, pt, k.alpha * ps), kSkewTiny);
+    const float l = __builtin_fmaxf(lps - __log2f(m), kSkewLogFloor);
+    return ps * __builtin_fmaf(l, k.Cl, __builtin_fmaf(ps * __builtin_amdgcn_rcpf(m), k.A, k.B));
+  }
+}
+// Sweep 2 of an element whose gradient is finished from two cached fp32 values, p = p_S and v:
+//   skew KL          v = p_S p_T / m,                                 gradient = A v + B p  (A, B as in skew_grad)
+//   skew reverse KL  v = p_S (ln(p_S / m) - alpha p_S / m) = p_S (u - 1),   gradient = g v + B p
+// dsum: D in log2 units; usum = sum v.
+template <int DIVK>
+__device__ __forceinline__ void skew_cache(float xs, float xt, const SkewCoef& k, float& dsum, float& usum, float& p,
+                                           float& v) {
+  const float lps = __builtin_fmaf(xs, k.c, -k.Ls), lpt = __builtin_fmaf(xt, k.c, -k.Lt);
+  const float ps = exp2_fast(lps), pt = exp2_fast(lpt);
+  p = ps;
+  // The floors are additive here (one fused operation each instead of a maximum): kSkewTiny changes nothing above
+  // 2e-30, and below that the element's terms are far under one rounding step of the sums.  The log ratio is taken of
+  // the quotient itself, which sweep 2 needs anyway.
+  if constexpr (DIVK == kSkewKl) {
+    const float m = __builtin_fmaf(k.alpha, pt, __builtin_fmaf(k.beta, ps, kSkewTiny));
+    const float w = __builtin_fmaf(pt, __builtin_amdgcn_rcpf(m), kSkewTiny);  // p_T / m
+    dsum = __builtin_fmaf(pt, __log2f(w), dsum);
+    v = ps * w;
+  } else {
+    const float m = __builtin_fmaf(k.beta, pt, __builtin_fmaf(k.alpha, ps, kSkewTiny));
+    const float t = __builtin_fmaf(ps, __builtin_amdgcn_rcpf(m), kSkewTiny);  // p_S / m
+    const float l = __log2f(t);
+    dsum = __builtin_fmaf(ps, l, dsum);
+    v = ps * __builtin_fmaf(l, kLn2, t * -k.alpha);
+  }
+  usum += v;
+}
+
 // K: groups per thread and tensor a slice may have (the slice of a launch has a.gang_groups <= K * 256 groups).
 template <int K, int TEACHER, bool LSE1, int DIVK = kForwardKl>
 __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a) {
   static_assert(TEACHER == kDense, "dense teacher");
-  static_assert(DIVK == kForwardKl || DIVK == kReverseKl, "two-sweep divergences");
   constexpr int TH = kGangThreads;
   constexpr int GB = TH * 16;
   constexpr int NS = LSE1 ? 4 : 2;  // 0 student / tau, 1 teacher / tau (+ cross), 2 student tau = 1, 3 teacher tau = 1
   constexpr int NW3 = NS * 3;
   constexpr int W = gang_words(NS);
   constexpr bool REV = DIVK == kReverseKl;
+  // the skew forms take three sweeps over the registers and a second exchange: normalisers; D and ubar; gradient
+  constexpr bool SKEW = DIVK == kSkewKl || DIVK == kSkewReverseKl;
+  static_assert(NW3 + 2 <= W, "the second exchange of the skew forms uses two spare words of a slice's record");
   __shared__ float red[4 * 3 * (TH / kWave)];
   __shared__ uint32_t xch[kGangMax * W];
+  __shared__ uint32_t xch2[SKEW ? kGangMax * 2 : 1];
   __shared__ int gave_up;
 
   const int G = a.gang;
@@ -255,7 +312,7 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
         acc[1].z += et;
         if constexpr (REV)
           acc[0].a = __builtin_fmaf(es, xs[j] - xt[j], acc[0].a);
-        else
+        else if constexpr (!SKEW)
           acc[1].a = __builtin_fmaf(et, xt[j] - xs[j], acc[1].a);
         if constexpr (LSE1) {
           acc[2].z += exp2_fast(__builtin_fmaf(xs[j], kLog2e, -acc[2].r));
@@ -304,7 +361,7 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
 #pragma unroll
   for (int i = 0; i < NS; ++i) {
     normalise(acc[i]);
-    if (i < 2)
+    if (i == (REV ? 0 : 1) && !SKEW)  // the stream that carries the cross term
       wave_merge_rescaled<true>(acc[i]);
     else
       wave_merge_rescaled<false>(acc[i]);
@@ -326,7 +383,7 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
       acc[i].z = red[(i * 3 + 1) * NWV + lane];
       acc[i].a = red[(i * 3 + 2) * NWV + lane];
     }
-    if (i < 2)
+    if (i == (REV ? 0 : 1) && !SKEW)  // the stream that carries the cross term
       wave_merge_rescaled<true>(acc[i]);
     else
       wave_merge_rescaled<false>(acc[i]);
@@ -363,7 +420,7 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
     }
   }
   __syncthreads();
-  const bool timeout = gave_up != 0;  // uniform
+  bool timeout = gave_up != 0;  // uniform
 #pragma unroll
   for (int i = 0; i < NS; ++i) {  // lane s < G takes slice s: every wave of every workgroup of the row computes the
     acc[i].init();                // same totals in the same order
@@ -372,7 +429,7 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
       acc[i].z = __builtin_bit_cast(float, xch[lane * W + i * 3 + 1]);
       acc[i].a = __builtin_bit_cast(float, xch[lane * W + i * 3 + 2]);
     }
-    if (i < 2)
+    if (i == (REV ? 0 : 1) && !SKEW)  // the stream that carries the cross term
       wave_merge_rescaled<true>(acc[i]);
     else
       wave_merge_rescaled<false>(acc[i]);
@@ -383,9 +440,89 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
   const float lse1_s = __fmul_rn(LSE1 ? acc[NS - 2].log2_sum() : Ls, kLn2);
   const float lse_diff = ((acc[0].r - acc[1].r) + (acc[0].log2_z() - acc[1].log2_z())) * kLn2;  // lse_S - lse_T at tau
   float kd = REV ? (acc[0].a / acc[0].z) * a.inv_tau - lse_diff : (acc[1].a / acc[1].z) * a.inv_tau + lse_diff;
-  kd = kd < 0.0f ? 0.0f : kd;
+  kd = kd < 0.0f ? 0.0f : kd;  // (the skew forms replace it below)
   const bool ce = a.cscale != 0.0f;  // uniform (tau = 1 here whenever it is set)
   Sweep2Coef kf = sweep2_coef(acc[0], acc[1], c, a.gscale, a.cscale, true, true);
+  SkewCoef ks;
+  // the skew forms keep p_S and p_S u of the slice as fp32 from sweep 2 on (twice the registers of the packed logits,
+  // which are dead by then -- hence the smaller K of these instances): the gradient sweep is one multiply-add each
+  float cp[SKEW ? K : 1][8], cv[SKEW ? K : 1][8];
+  if constexpr (SKEW) {
+    // ---- sweep 2 of the skew forms over the registers: D and ubar need the row's normalisers in every term
+    ks.c = c;
+    ks.Ls = Ls;
+    ks.Lt = Lt;
+    ks.alpha = a.alpha;
+    ks.beta = 1.0f - a.alpha;
+    float dsum = 0.0f, usum = 0.0f;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      if (k < q || (k == q && tid < part)) {
+        opaque(sreg[k]);  // unpacked again, not kept from sweep 1
+        opaque(treg[k]);
+        float xs[8], xt[8];
+        unpack8(sreg[k], xs);
+        unpack8(treg[k], xt);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) skew_cache<DIVK>(xs[j], xt[j], ks, dsum, usum, cp[k][j], cv[k][j]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (last)
+      for (int e = nvec * 8 + tid; e < V; e += TH) {
+        float p, v;
+        skew_cache<DIVK>(bf16_one(srow[e]), bf16_one(trow[e]), ks, dsum, usum, p, v);
+      }
+    // workgroup totals, second post / wait, row totals -- plain sums in a fixed order
+    dsum = wave_sum_dpp(dsum);
+    usum = wave_sum_dpp(usum);
+    if (lane == 0) {
+      red[wid] = dsum;
+      red[NWV + wid] = usum;
+    }
+    __syncthreads();
+    dsum = wave_sum_dpp(lane < NWV ? red[lane] : 0.0f);
+    usum = wave_sum_dpp(lane < NWV ? red[NWV + lane] : 0.0f);
+    if (tid < 2) gang_post(rec + NW3 + tid, tid == 0 ? dsum : usum);
+    {
+      const uint32_t* rrow = a.ws + (size_t)row * G * W;
+      for (int w = tid; w < 2 * G; w += TH) {
+        const int s = w >> 1, f = w & 1;
+        uint32_t v;
+        int spins = 0;
+        while (true) {
+          v = __hip_atomic_load(rrow + s * W + NW3 + f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (v != kGangEmpty) break;
+          if (++spins > a.spin_limit) {
+            gave_up = 1;
+            break;
+          }
+          __builtin_amdgcn_s_sleep(8);
+        }
+        xch2[w] = v;
+      }
+    }
+    __syncthreads();
+    timeout = gave_up != 0;
+    dsum = wave_sum_dpp(lane < G ? __builtin_bit_cast(float, xch2[2 * lane]) : 0.0f);
+    usum = wave_sum_dpp(lane < G ? __builtin_bit_cast(float, xch2[2 * lane + 1]) : 0.0f);
+    kd = dsum * kLn2;
+    kd = kd < 0.0f ? 0.0f : kd;
+    const float g = a.gscale;  // (grad_scale / tau)
+    if constexpr (DIVK == kSkewKl) {
+      const float ubar = (a.alpha - 1.0f) * usum;
+      ks.A = (a.alpha - 1.0f) * g;
+      ks.B = a.cscale - g * ubar;
+      ks.Cl = 0.0f;
+      ks.Av = ks.A;
+    } else {
+      const float ubar = usum + 1.0f;
+      ks.A = -a.alpha * g;
+      ks.B = __builtin_fmaf(g, 1.0f - ubar, a.cscale);
+      ks.Cl = g * kLn2;
+      ks.Av = g;
+    }
+  }
   if constexpr (REV) {
     const float inv_z = 1.0f / acc[0].z;
     kf.ra = a.gscale * a.inv_tau * inv_z;
@@ -442,6 +579,8 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
     float gy;
     if constexpr (REV)
       gy = grad_reverse_elem(s_y, t_y, kf);
+    else if constexpr (SKEW)
+      gy = skew_grad<DIVK>(s_y, t_y, ks);
     else
       gy = grad_dense_elem(s_y, t_y, kf.p);
     const uint32_t b16 = one_bf16(gy - a.cscale);
@@ -468,12 +607,27 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
   if (last) {
     for (int e = nvec * 8 + tid; e < V; e += TH) {
       const float xs = bf16_one(srow[e]), xt = bf16_one(trow[e]);
-      uint16_t o = one_bf16(REV ? grad_reverse_elem(xs, xt, kf) : grad_dense_elem(xs, xt, kf.p));
+      uint16_t o;
+      if constexpr (SKEW)
+        o = one_bf16(skew_grad<DIVK>(xs, xt, ks));
+      else
+        o = one_bf16(REV ? grad_reverse_elem(xs, xt, kf) : grad_dense_elem(xs, xt, kf.p));
       if (ce && own_y && e == y) o = y_tail;
       grow[e] = o;
     }
   }
-  if (kf.folded) {  // uniform
+  if constexpr (SKEW) {
+#pragma unroll
+    for (int k = K - 1; k >= 0; --k) {
+      float gv[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) gv[j] = __builtin_fmaf(cv[k][j], ks.Av, ks.B * cp[k][j]);
+      uint4 o = make_uint4(pack_bf16(gv[0], gv[1]), pack_bf16(gv[2], gv[3]), pack_bf16(gv[4], gv[5]), pack_bf16(gv[6], gv[7]));
+      if (k == k_y) patch_label(o);  // uniform
+      if (k < q || (k == q && tid < part)) store(k, o);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  } else if (kf.folded) {  // uniform
 #pragma unroll
     for (int k = K - 1; k >= 0; --k) {
       opaque(sreg[k]);  // sweep 2 unpacks the registers again instead of keeping sweep 1's floats alive

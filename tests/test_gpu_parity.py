@@ -609,14 +609,16 @@ def test_cfg4_full_size_inplace(oracle):
     (151936, 151936),              # eight slices of 2,374 groups
     (8 * 2560 * 9 + 8, 8 * 2560 * 9 + 24),   # ten slices, nine of them a single group short of full; padded rows
 ])
-@pytest.mark.parametrize("tau,div", [(1.0, "forward"), (2.0, "forward"), (1.0, "reverse")])
+@pytest.mark.parametrize("tau,div", [(1.0, "forward"), (2.0, "forward"), (1.0, "reverse"), (1.0, "skew"),
+                                     (2.0, "skew"), (1.0, "skew_reverse"), (2.0, "skew_reverse")])
 def test_gang_slices_with_labels_on_their_edges(oracle, V, stride, tau, div):
     """Rows shared by 2 .. 10 workgroups; the labels sit on the first and last element of slices, in the tail and
     next to slice boundaries, so that the label logit, the NLLs and the one-hot term of the composite gradient are
     taken by the right workgroup.  Out of place and in place."""
     assert binding.npd_workspace_bytes(4, V, tau=1.0) > 0
     nvec = V // 8
-    gang = -(-nvec // 2560)
+    width = 1280 if div.startswith("skew") else 2560     # groups a slice holds at most (the skew forms: half)
+    gang = -(-nvec // width)
     per = -(-nvec // gang)
     edges = sorted({0, 7, 8 * per - 1, 8 * per, 8 * per + 1, 8 * (gang - 1) * per - 1, 8 * (gang - 1) * per,
                     8 * nvec - 1, V - 1, V // 2})
@@ -637,7 +639,7 @@ def test_gang_slices_with_labels_on_their_edges(oracle, V, stride, tau, div):
         ref.update(nll_s=nl["nll_s"], nll_t=nl["nll_t"], lse_s=nl["lse_s"])
     for inplace in (False, True):
         gpu = run_gpu_kd(s.clone() if inplace else s, mask, t=t, labels=labels, tau=tau, grad_scale=0.75,
-                         ce_grad_scale=ce, inplace=inplace, divergence=DIVS.get(div, 0))
+                         ce_grad_scale=ce, inplace=inplace, divergence=DIVS.get(div, 0), skew_alpha=0.1)
         assert gpu["status"] == 0
         compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle, grad_scale=0.75 + ce, tau=tau,
                    amp_from_ref=div != "forward")
@@ -1048,6 +1050,7 @@ DIVS = {"reverse": binding.NPD_DIV_REVERSE_KL, "skew": binding.NPD_DIV_SKEW_KL,
         "skew_reverse": binding.NPD_DIV_SKEW_REVERSE_KL}
 
 
+@pytest.mark.parametrize("no_workspace", [False, True])
 @pytest.mark.parametrize("div", sorted(DIVS))
 @pytest.mark.parametrize("V,stride,tau,alpha,scale,inplace", [
     (1024, 1024, 1.0, 0.1, 1.0, False),        # one wave per row
@@ -1057,7 +1060,9 @@ DIVS = {"reverse": binding.NPD_DIV_REVERSE_KL, "skew": binding.NPD_DIV_SKEW_KL,
     (151936, 151936, 3.0, 0.9, -2.0, True),
     (600000, 600000, 1.0, 0.3, 1.0, False),    # 74 groups per thread: most of the row streamed in every sweep
 ])
-def test_divergence_shapes(oracle, div, V, stride, tau, alpha, scale, inplace):
+def test_divergence_shapes(oracle, div, V, stride, tau, alpha, scale, inplace, no_workspace):
+    if no_workspace and V < 8 * 2561:
+        pytest.skip("rows of one slice take the same kernel with and without a workspace")
     T = (12 if V > 500000 else 24) if V > 100000 else 64
     w = synth.scaled(synth.config(1), n_rows=1, row_len=T, vocab=V, length_lo=4, length_hi=16)
     _say(f"divergence {div} V={V} stride={stride} tau={tau} alpha={alpha} scale={scale} inplace={inplace}")
@@ -1067,7 +1072,7 @@ def test_divergence_shapes(oracle, div, V, stride, tau, alpha, scale, inplace):
     nll = oracle.kd_dense(_bits(s), _bits(t), lay.labels, lay.loss_mask, want_grad=False)
     ref.update(nll_s=nll["nll_s"], nll_t=nll["nll_t"], lse_s=nll["lse_s"])
     gpu = run_gpu_kd(s, mask, t=t, labels=labels, tau=tau, grad_scale=scale, inplace=inplace, divergence=DIVS[div],
-                     skew_alpha=alpha)
+                     skew_alpha=alpha, no_workspace=no_workspace)
     assert gpu["status"] == 0
     compare_kd(gpu, ref, lay.loss_mask, lay.cu_seqlens, oracle, grad_scale=scale, tau=tau, amp_from_ref=True)
 
