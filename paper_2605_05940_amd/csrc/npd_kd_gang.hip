@@ -14,7 +14,7 @@ int set_gang_spin_limit(int polls) {
 
 constexpr int kGangK = 10;      // 128-bit groups per thread and tensor: 80 of a thread's 128 registers hold its slice
 constexpr int kGangTopkK = 10;  // top-k teacher: groups per thread of the student row alone
-constexpr int kGangSkewK = 5;   // skew forms: the slice is kept as two fp32 values per element from sweep 2 on
+constexpr int kGangSkewK = 6;   // skew forms: the slice is kept as two fp32 values per element from sweep 2 on
 
 static int gang_k(int teacher_kind, int divergence) {
   if (teacher_kind == kTopk) return kGangTopkK;

@@ -617,7 +617,7 @@ def test_gang_slices_with_labels_on_their_edges(oracle, V, stride, tau, div):
     taken by the right workgroup.  Out of place and in place."""
     assert binding.npd_workspace_bytes(4, V, tau=1.0) > 0
     nvec = V // 8
-    width = 1280 if div.startswith("skew") else 2560     # groups a slice holds at most (the skew forms: half)
+    width = 1536 if div.startswith("skew") else 2560     # groups a slice holds at most (fewer for the skew forms)
     gang = -(-nvec // width)
     per = -(-nvec // gang)
     edges = sorted({0, 7, 8 * per - 1, 8 * per, 8 * per + 1, 8 * (gang - 1) * per - 1, 8 * (gang - 1) * per,
