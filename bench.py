@@ -326,6 +326,9 @@ def bench_memory_system(args, synth, dev):
         gbs = rate(lambda: membench.run_gang(a, b, o, scratch, rows, groups), 3)
         patterns["gang_read_2_then_write_1/rows"] = {"best_gbs": gbs, "best_variant": "256_nt", "frac_of_peak": gbs / HBM_PEAK_GBS,
                                                      "variants_gbs": {"256_nt": gbs}}
+        gbs = rate(lambda: membench.run_gang(a, b, o, scratch, rows, groups, reads=1), 2)
+        patterns["gang_read_1_then_write_1/rows"] = {"best_gbs": gbs, "best_variant": "256_nt", "frac_of_peak": gbs / HBM_PEAK_GBS,
+                                                     "variants_gbs": {"256_nt": gbs}}
     runtime = {"fill_gbs": rate(lambda: o.zero_(), 1), "copy_gbs": rate(lambda: o.copy_(a), 2)}
     print(json.dumps({
         "metric": "memory_system_stream_rate_2_reads_1_write",

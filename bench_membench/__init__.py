@@ -44,7 +44,7 @@ def load() -> ctypes.CDLL:
         lib.npd_membench_gang_scratch_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32]
         lib.npd_membench_gang.restype = ctypes.c_int
         lib.npd_membench_gang.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
-                                          ctypes.c_void_p, ctypes.c_void_p]
+                                          ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p]
         assert lib.npd_membench_patterns() == len(PATTERNS)
         _lib = lib
     return _lib
@@ -70,9 +70,10 @@ def gang_scratch_bytes(rows: int, row_groups: int) -> int:
     return int(load().npd_membench_gang_scratch_bytes(rows, row_groups))
 
 
-def run_gang(a, b, o, scratch, rows: int, row_groups: int) -> None:
-    """One pass of the row-gang pattern (two reads + one write; rows shared by workgroups of 256 threads that read their
-    slices, exchange through ``scratch`` and then write) on torch's current stream."""
+def run_gang(a, b, o, scratch, rows: int, row_groups: int, reads: int = 2) -> None:
+    """One pass of the row-gang pattern (``reads`` = 2: two reads + one write, 1: one read + one write; rows shared by
+    workgroups of 256 threads that read their slices, exchange through ``scratch`` and then write) on torch's current
+    stream."""
     import torch
     for x in (a, b, o):
         if not x.is_cuda or not x.is_contiguous() or x.numel() * x.element_size() < rows * row_groups * 16:
@@ -80,7 +81,7 @@ def run_gang(a, b, o, scratch, rows: int, row_groups: int) -> None:
     need = gang_scratch_bytes(rows, row_groups)
     if need == 0 or not scratch.is_cuda or scratch.numel() * scratch.element_size() < need:
         raise ValueError("scratch too small or shape not supported")
-    rc = load().npd_membench_gang(a.data_ptr(), b.data_ptr(), o.data_ptr(), rows, row_groups, scratch.data_ptr(),
+    rc = load().npd_membench_gang(a.data_ptr(), b.data_ptr(), o.data_ptr(), rows, row_groups, scratch.data_ptr(), reads,
                                   torch.cuda.current_stream().cuda_stream)
     if rc != 0:
         raise RuntimeError(f"npd_membench_gang failed with HIP error {rc}")

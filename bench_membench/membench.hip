@@ -115,8 +115,10 @@ __global__ __launch_bounds__(256) void gang_clear_kernel(uint32_t* p, size_t n) 
   if (i < n) p[i] = kGangEmpty;
 }
 
-template <int K>
-__global__ __launch_bounds__(256, 4) void gang_rows_kernel(const u32x4* __restrict__ a, const u32x4* __restrict__ b,
+// READS = 1: one read + one write (the order of the row-gang kernel for a top-k teacher: array b is not touched, and
+// with half the registers six workgroups run per compute unit instead of four).
+template <int K, int READS>
+__global__ __launch_bounds__(256, READS == 2 ? 4 : 6) void gang_rows_kernel(const u32x4* __restrict__ a, const u32x4* __restrict__ b,
                                                            u32x4* __restrict__ o, int row_groups, int slice_groups,
                                                            int gang, uint32_t* scratch, int spin_limit) {
   __shared__ uint32_t xch[kGangMax * kGangWords];
@@ -125,19 +127,20 @@ __global__ __launch_bounds__(256, 4) void gang_rows_kernel(const u32x4* __restri
   const size_t base = (size_t)row * row_groups;
   const int g0 = slice * slice_groups;
   const int g1 = g0 + slice_groups < row_groups ? g0 + slice_groups : row_groups;
-  u32x4 ra[K], rb[K];
+  u32x4 ra[K], rb[READS == 2 ? K : 1];
 #pragma unroll
   for (int k = 0; k < K; ++k) {
     const int g = g0 + k * 256 + tid;
-    ra[k] = rb[k] = u32x4{0, 0, 0, 0};
+    ra[k] = u32x4{0, 0, 0, 0};
+    if constexpr (READS == 2) rb[k] = u32x4{0, 0, 0, 0};
     if (g < g1) {
       ra[k] = __builtin_nontemporal_load(a + base + g);
-      rb[k] = __builtin_nontemporal_load(b + base + g);
+      if constexpr (READS == 2) rb[k] = __builtin_nontemporal_load(b + base + g);
     }
   }
   uint32_t f = 0;  // something that depends on every load of the thread
 #pragma unroll
-  for (int k = 0; k < K; ++k) f ^= ra[k].x ^ rb[k].y;
+  for (int k = 0; k < K; ++k) f ^= READS == 2 ? ra[k].x ^ rb[k].y : ra[k].x;
   for (int off = 32; off > 0; off >>= 1) f ^= __shfl_xor(f, off, 64);
   if ((tid & 63) == 0) red[tid >> 6] = f;
   __syncthreads();
@@ -162,7 +165,8 @@ __global__ __launch_bounds__(256, 4) void gang_rows_kernel(const u32x4* __restri
 #pragma unroll
   for (int k = K - 1; k >= 0; --k) {
     const int g = g0 + k * 256 + tid;
-    u32x4 v = ra[k] ^ rb[k];
+    u32x4 v = ra[k];
+    if constexpr (READS == 2) v ^= rb[k];
     v.x ^= mix;
     if (g < g1) __builtin_nontemporal_store(v, o + base + g);
   }
@@ -250,13 +254,14 @@ size_t npd_membench_gang_scratch_bytes(int64_t rows, int32_t row_groups) {
   return (size_t)rows * gang * kGangWords * sizeof(uint32_t);
 }
 
-// Enqueues one pass of the row-gang pattern (two reads + one write; see gang_rows_kernel) over `rows` rows of
-// `row_groups` 16-byte groups: device arrays a, b, o as in npd_membench_run, `scratch` a device buffer of
-// npd_membench_gang_scratch_bytes() bytes.  Returns 0 or a hipError_t value (invalid arguments: nothing enqueued).
+// Enqueues one pass of the row-gang pattern (`reads` = 2: two reads + one write; 1: one read + one write, b is not
+// touched; see gang_rows_kernel) over `rows` rows of `row_groups` 16-byte groups: device arrays a, b, o as in
+// npd_membench_run, `scratch` a device buffer of npd_membench_gang_scratch_bytes() bytes.  Returns 0 or a hipError_t
+// value (invalid arguments: nothing enqueued).
 int npd_membench_gang(const void* a, const void* b, void* o, int64_t rows, int32_t row_groups, void* scratch,
-                      void* stream) {
+                      int32_t reads, void* stream) {
   const size_t bytes = npd_membench_gang_scratch_bytes(rows, row_groups);
-  if (!a || !b || !o || !scratch || bytes == 0) return (int)hipErrorInvalidValue;
+  if (!a || !b || !o || !scratch || bytes == 0 || (reads != 1 && reads != 2)) return (int)hipErrorInvalidValue;
   if (((uintptr_t)a | (uintptr_t)b | (uintptr_t)o | (uintptr_t)scratch) & 15u) return (int)hipErrorInvalidValue;
   const int gang = (row_groups + kGangK * 256 - 1) / (kGangK * 256);
   const int slice_groups = (row_groups + gang - 1) / gang;
@@ -264,9 +269,14 @@ int npd_membench_gang(const void* a, const void* b, void* o, int64_t rows, int32
   const size_t words = bytes / sizeof(uint32_t);
   hipLaunchKernelGGL(gang_clear_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, s,
                      static_cast<uint32_t*>(scratch), words);
-  hipLaunchKernelGGL((gang_rows_kernel<kGangK>), dim3((unsigned)(rows * gang)), dim3(256), 0, s,
-                     static_cast<const u32x4*>(a), static_cast<const u32x4*>(b), static_cast<u32x4*>(o), row_groups,
-                     slice_groups, gang, static_cast<uint32_t*>(scratch), 1 << 20);
+  if (reads == 2)
+    hipLaunchKernelGGL((gang_rows_kernel<kGangK, 2>), dim3((unsigned)(rows * gang)), dim3(256), 0, s,
+                       static_cast<const u32x4*>(a), static_cast<const u32x4*>(b), static_cast<u32x4*>(o), row_groups,
+                       slice_groups, gang, static_cast<uint32_t*>(scratch), 1 << 20);
+  else
+    hipLaunchKernelGGL((gang_rows_kernel<kGangK, 1>), dim3((unsigned)(rows * gang)), dim3(256), 0, s,
+                       static_cast<const u32x4*>(a), static_cast<const u32x4*>(b), static_cast<u32x4*>(o), row_groups,
+                       slice_groups, gang, static_cast<uint32_t*>(scratch), 1 << 20);
   return (int)hipGetLastError();
 }
 

@@ -40,12 +40,12 @@ bool gang_path_applies(const KdArgs& a, int teacher_kind, bool want_grad) {
 size_t gang_workspace_bytes(int64_t T, int32_t V, int teacher_kind, int divergence, bool lse1) {
   const int g = gang_size(V / 8, gang_k(teacher_kind, divergence));
   if (g < 2 || g > kGangMax || T * (int64_t)g > 0x7fffffffLL) return 0;
-  return (size_t)T * g * gang_words(lse1 ? 4 : 2) * sizeof(uint32_t);
+  return ((size_t)T * g * gang_words(lse1 ? 4 : 2) + kGangTailWords) * sizeof(uint32_t);
 }
 
 template <class Kernel>
 static hipError_t launch_gang_kernel(const KdArgs& a, int words_per_slice, Kernel kernel, hipStream_t stream) {
-  const size_t words = (size_t)a.T * a.gang * words_per_slice;
+  const size_t words = (size_t)a.T * a.gang * words_per_slice + kGangTailWords;
   const int pieces = (a.nvec_s + kPieceGroups - 1) / kPieceGroups;
   const int64_t want = a.T * pieces;
   const int64_t fill_grid = want < 8 * (int64_t)compute_units() ? want : 8 * (int64_t)compute_units();

@@ -18,8 +18,9 @@
 // and consumers poll those words with atomic loads at device scope.  Forward progress: a workgroup waits only for
 // workgroups of smaller or neighbouring index (the other slices of its own row), a workgroup never waits before it
 // has posted, and workgroups start in index order, so the lowest unfinished row always has all its workgroups
-// resident or next to start.  Every wait is bounded all the same: a workgroup that gives up marks its row NaN and
-// sets NPD_DEV_GANG_TIMEOUT, so a kernel can never hang.
+// resident or next to start.  Every wait is bounded all the same: a workgroup that gives up marks its row NaN, sets
+// NPD_DEV_GANG_TIMEOUT and raises a launch-wide flag that ends every other wait of the launch early, so a kernel can
+// never hang, nor spend one limit per row.
 #pragma once
 #include "npd_kd_cached.hpp"
 
@@ -97,6 +98,30 @@ __device__ __forceinline__ void gang_post(uint32_t* p, float v) {
   uint32_t w = __builtin_bit_cast(uint32_t, v);
   if (w == kGangEmpty) w = 0x7fc00000u;  // another NaN
   __hip_atomic_store(p, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Waits for a posted word.  Gives up after `spin_limit` polls, or -- looked at every 256th poll -- as soon as any
+// workgroup of the launch has given up (the word *abandon, cleared with the record): once one wait has run out, no
+// other workgroup spends its own limit, so a launch whose workgroups cannot see each other ends within seconds
+// however many rows it has.  Returns the word, or kGangEmpty with *gave_up set.
+constexpr int kGangTailWords = 64;  // words behind the record; word 0: a workgroup has given up
+__device__ __forceinline__ uint32_t gang_wait(const uint32_t* p, uint32_t* abandon, int spin_limit, int* gave_up) {
+  int spins = 0;
+  while (true) {
+    const uint32_t v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (v != kGangEmpty) return v;
+    ++spins;
+    if (spins > spin_limit) {
+      __hip_atomic_store(abandon, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      *gave_up = 1;
+      return v;
+    }
+    if ((spins & 255) == 0 && __hip_atomic_load(abandon, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 1u) {
+      *gave_up = 1;
+      return v;
+    }
+    __builtin_amdgcn_s_sleep(8);
+  }
 }
 
 // words of scratch per slice: 3 per partial log-sum-exp, rounded up to a power of two
@@ -390,6 +415,7 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
   }
 
   uint32_t* rec = a.ws + (size_t)blockIdx.x * W;  // scratch[row][slice]
+  uint32_t* abandon = a.ws + (size_t)gridDim.x * W;  // behind the record
   if (tid < NW3) {
     float v = acc[0].r;
 #pragma unroll
@@ -405,18 +431,7 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
     const int nw = G * NW3;
     for (int w = tid; w < nw; w += TH) {
       const int s = w / NW3, f = w - s * NW3;
-      uint32_t v;
-      int spins = 0;
-      while (true) {
-        v = __hip_atomic_load(rrow + s * W + f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (v != kGangEmpty) break;
-        if (++spins > a.spin_limit) {
-          gave_up = 1;
-          break;
-        }
-        __builtin_amdgcn_s_sleep(8);
-      }
-      xch[s * W + f] = v;
+      xch[s * W + f] = gang_wait(rrow + s * W + f, abandon, a.spin_limit, &gave_up);
     }
   }
   __syncthreads();
@@ -488,18 +503,7 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
       const uint32_t* rrow = a.ws + (size_t)row * G * W;
       for (int w = tid; w < 2 * G; w += TH) {
         const int s = w >> 1, f = w & 1;
-        uint32_t v;
-        int spins = 0;
-        while (true) {
-          v = __hip_atomic_load(rrow + s * W + NW3 + f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          if (v != kGangEmpty) break;
-          if (++spins > a.spin_limit) {
-            gave_up = 1;
-            break;
-          }
-          __builtin_amdgcn_s_sleep(8);
-        }
-        xch2[w] = v;
+        xch2[w] = gang_wait(rrow + s * W + NW3 + f, abandon, a.spin_limit, &gave_up);
       }
     }
     __syncthreads();

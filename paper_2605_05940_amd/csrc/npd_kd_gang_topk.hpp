@@ -181,6 +181,7 @@ __global__ __launch_bounds__(kGangThreads, 6) void kd_gang_topk_kernel(const KdA
   bad_index = (red[6 * NWV + 0] + red[6 * NWV + 1] + red[6 * NWV + 2] + red[6 * NWV + 3]) != 0.0f;  // uniform
 
   uint32_t* rec = a.ws + (size_t)blockIdx.x * W;
+  uint32_t* abandon = a.ws + (size_t)gridDim.x * W;  // behind the record
   if (tid < NW3) {
     float v = st[0].r;
 #pragma unroll
@@ -196,18 +197,7 @@ __global__ __launch_bounds__(kGangThreads, 6) void kd_gang_topk_kernel(const KdA
     const int nw = G * NW3;
     for (int w = tid; w < nw; w += TH) {
       const int s = w / NW3, f = w - s * NW3;
-      uint32_t v;
-      int spins = 0;
-      while (true) {
-        v = __hip_atomic_load(rrow + s * W + f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (v != kGangEmpty) break;
-        if (++spins > a.spin_limit) {
-          gave_up = 1;
-          break;
-        }
-        __builtin_amdgcn_s_sleep(8);
-      }
-      xch[s * W + f] = v;
+      xch[s * W + f] = gang_wait(rrow + s * W + f, abandon, a.spin_limit, &gave_up);
     }
   }
   __syncthreads();

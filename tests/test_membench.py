@@ -62,9 +62,10 @@ def test_membench_gang_validates_on_the_host():
     assert membench.gang_scratch_bytes(32768, 18992) == 32768 * 8 * 32      # 8 slices of at most 2,560 groups
     assert membench.gang_scratch_bytes(4, 33 * 2560) == 0                   # more than 32 slices per row
     assert membench.gang_scratch_bytes(0, 100) == 0
-    assert lib.npd_membench_gang(FAKE, FAKE + 0x1000, FAKE + 0x2000, 4, 100, None, None) == HIP_INVALID_VALUE
-    assert lib.npd_membench_gang(FAKE, FAKE + 0x1000, FAKE + 0x2004, 4, 100, FAKE + 0x3000, None) == HIP_INVALID_VALUE
-    assert lib.npd_membench_gang(None, FAKE + 0x1000, FAKE + 0x2000, 4, 100, FAKE + 0x3000, None) == HIP_INVALID_VALUE
+    assert lib.npd_membench_gang(FAKE, FAKE + 0x1000, FAKE + 0x2000, 4, 100, None, 2, None) == HIP_INVALID_VALUE
+    assert lib.npd_membench_gang(FAKE, FAKE + 0x1000, FAKE + 0x2004, 4, 100, FAKE + 0x3000, 2, None) == HIP_INVALID_VALUE
+    assert lib.npd_membench_gang(None, FAKE + 0x1000, FAKE + 0x2000, 4, 100, FAKE + 0x3000, 1, None) == HIP_INVALID_VALUE
+    assert lib.npd_membench_gang(FAKE, FAKE + 0x1000, FAKE + 0x2000, 4, 100, FAKE + 0x3000, 3, None) == HIP_INVALID_VALUE
 
 
 @pytest.mark.gpu
@@ -80,9 +81,9 @@ def test_membench_gang_moves_what_it_says(groups):
     full = torch.full((n + 2 * guard,), 0xA5, dtype=torch.uint8, device=dev)
     o = full[guard:guard + n]
     scratch = torch.zeros(membench.gang_scratch_bytes(rows, groups), dtype=torch.uint8, device=dev)
-    for _ in range(2):                       # the second pass finds the first one's words in the record
+    for reads in (2, 2, 1):                  # the second pass finds the first one's words in the record
         full.fill_(0xA5)
-        membench.run_gang(a, b, o, scratch, rows, groups)
+        membench.run_gang(a, b, o, scratch, rows, groups, reads=reads)
         torch.cuda.synchronize()
-        assert torch.equal(o, a ^ b)
+        assert torch.equal(o, a ^ b if reads == 2 else a)
         assert (full[:guard] == 0xA5).all() and (full[guard + n:] == 0xA5).all()
