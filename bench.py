@@ -145,8 +145,10 @@ def main():
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
         if w.paired:       # scoring pass: forward-only NLL of the student logits, then of the teacher logits
-            binding.npd_kd_loss_fwd_bwd(s, mask, labels=labels, nll_tok=nll, dev_status=status)
-            binding.npd_kd_loss_fwd_bwd(t, mask, labels=labels, nll_tok=tnll, dev_status=status)
+            binding.npd_kd_loss_fwd_bwd(s, mask, labels=labels, nll_tok=nll, dev_status=status,
+                                        no_workspace=args.no_workspace)
+            binding.npd_kd_loss_fwd_bwd(t, mask, labels=labels, nll_tok=tnll, dev_status=status,
+                                        no_workspace=args.no_workspace)
         elif dense:
             binding.npd_kd_loss_fwd_bwd(s, mask, teacher_dense=t, labels=labels, tau=w.tau, grad_scale=1.0,
                                         divergence=div_code, skew_alpha=args.skew_alpha, no_workspace=args.no_workspace,
