@@ -170,39 +170,21 @@ __global__ __launch_bounds__(256) void gang_prepare_kernel(uint32_t* ws, size_t 
 // gradient = grad_scale / tau * p_S (u - ubar) with ubar = sum p_S u (+ ce_grad_scale p_S from the CE term at tau = 1).
 // Entries of probability 0 (logits of -inf, underflow) contribute nothing: m has a floor, log ratios are kept finite.
 struct SkewCoef {
-  float c, Ls, Lt;     // log2 p = x c - L
-  float alpha, beta;   // beta = 1 - alpha
-  float A, B, Cl;      // gradient coefficients, see skew_grad
-  float Av;            // coefficient of the cached v, see skew_cache
+  float c, Rs, Rt, izs, izt;  // p = 2^(x c - R) / z with the row's merged reference and sum (the reference is not
+                              // folded into one logarithm: at logits in the thousands that would cost 2e-4 of p)
+  float alpha, beta;          // beta = 1 - alpha
+  float Av, B;                // gradient = Av v + B p_S, see skew_terms
 };
 constexpr float kSkewTiny = 1.0e-37f;
-constexpr float kSkewLogFloor = -1.0e30f;
 
-// skew KL:          p_S (A p_T / m + B),                         A = (alpha - 1) g,  B = ce - g ubar
-// skew reverse KL:  p_S (Cl log2(p_S / m) + A p_S / m + B),      Cl = g ln 2,  A = -alpha g,  B = g (1 - ubar) + ce
-// with g = grad_scale / tau, ce = ce_grad_scale
-template <int DIVK>
-__device__ __forceinline__ float skew_grad(float xs, float xt, const SkewCoef& k) {
-  const float lps = __builtin_fmaf(xs, k.c, -k.Ls), lpt = __builtin_fmaf(xt, k.c, -k.Lt);
-  const float ps = exp2_fast(lps), pt = exp2_fast(lpt);
-  if constexpr (DIVK == kSkewKl) {
-    const float m = __builtin_fmaxf(__builtin_fmaf(k.alpha, pt, k.beta * ps), kSkewTiny);
-    return ps * __builtin_fmaf(pt * __builtin_amdgcn_rcpf(m), k.A, k.B);
-  } else {
-    const float m = __builtin_fmaxf(__builtin_fmaf(k.beta, pt, k.alpha * ps), kSkewTiny);
-    const float l = __builtin_fmaxf(lps - __log2f(m), kSkewLogFloor);
-    return ps * __builtin_fmaf(l, k.Cl, __builtin_fmaf(ps * __builtin_amdgcn_rcpf(m), k.A, k.B));
-  }
-}
-// Sweep 2 of an element whose gradient is finished from two cached fp32 values, p = p_S and v:
-//   skew KL          v = p_S p_T / m,                                 gradient = A v + B p  (A, B as in skew_grad)
-//   skew reverse KL  v = p_S (ln(p_S / m) - alpha p_S / m) = p_S (u - 1),   gradient = g v + B p
+// Sweep 2 of an element, whose gradient is then finished from two fp32 values, p = p_S and v (g = grad_scale / tau,
+// ce = ce_grad_scale):
+//   skew KL          v = p_S p_T / m,                                       gradient = (alpha - 1) g v + (ce - g ubar) p
+//   skew reverse KL  v = p_S (ln(p_S / m) - alpha p_S / m) = p_S (u - 1),   gradient = g v + (g (1 - ubar) + ce) p
 // dsum: D in log2 units; usum = sum v.
 template <int DIVK>
-__device__ __forceinline__ void skew_cache(float xs, float xt, const SkewCoef& k, float& dsum, float& usum, float& p,
+__device__ __forceinline__ void skew_terms(float ps, float pt, const SkewCoef& k, float& dsum, float& usum, float& p,
                                            float& v) {
-  const float lps = __builtin_fmaf(xs, k.c, -k.Ls), lpt = __builtin_fmaf(xt, k.c, -k.Lt);
-  const float ps = exp2_fast(lps), pt = exp2_fast(lpt);
   p = ps;
   // The floors are additive here (one fused operation each instead of a maximum): kSkewTiny changes nothing above
   // 2e-30, and below that the element's terms are far under one rounding step of the sums.  The log ratio is taken of
@@ -220,6 +202,19 @@ __device__ __forceinline__ void skew_cache(float xs, float xt, const SkewCoef& k
     v = ps * __builtin_fmaf(l, kLn2, t * -k.alpha);
   }
   usum += v;
+}
+// the same from logits (elements outside the cached slice: the sub-group tail of a row)
+template <int DIVK>
+__device__ __forceinline__ void skew_cache(float xs, float xt, const SkewCoef& k, float& dsum, float& usum, float& p,
+                                           float& v) {
+  skew_terms<DIVK>(exp2_fast(__builtin_fmaf(xs, k.c, -k.Rs)) * k.izs, exp2_fast(__builtin_fmaf(xt, k.c, -k.Rt)) * k.izt, k, dsum,
+                   usum, p, v);
+}
+template <int DIVK>
+__device__ __forceinline__ float skew_grad(float xs, float xt, const SkewCoef& k) {
+  float d = 0.0f, u = 0.0f, p, v;
+  skew_cache<DIVK>(xs, xt, k, d, u, p, v);
+  return __builtin_fmaf(v, k.Av, k.B * p);
 }
 
 // K: groups per thread and tensor a slice may have (the slice of a launch has a.gang_groups <= K * 256 groups).
@@ -313,7 +308,13 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
   // -- a wider excursion, a logit of -inf (a masked vocabulary entry: 0 * -inf in the cross term) -- shows in the sums;
   // a wave that sees such a sum takes the careful form below (references that follow the data, guarded differences)
   // over the same registers.
-  constexpr float kRefBias = 100.0f;
+  // The skew forms keep the exponentials of sweep 1 (two fp32 values per element pair, in place of the packed logits,
+  // which are dead from here on -- hence the smaller K of these instances): sweep 2 scales them to probabilities with
+  // one multiplication each instead of unpacking and exponentiating again, and leaves p_S and p_S (u - const) in the
+  // same registers, so that the gradient sweep is one multiply-add per element.  Their references get 64 bits of head
+  // room: an element's exponential is kept down to 2^-62 of the thread's first group's largest.
+  constexpr float kRefBias = SKEW ? 64.0f : 100.0f;
+  float cp[SKEW ? K : 1][8], cv[SKEW ? K : 1][8];
   if (ng > tid) {  // (threads without a group keep their empty partials)
     const float fs = pk_max_value(pk_max_group(sreg[0])), ft = pk_max_value(pk_max_group(treg[0]));
     acc[0].r = __builtin_fmaxf(__builtin_fmaf(fs, c, kRefBias), -1.0e30f);
@@ -339,6 +340,10 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
           acc[0].a = __builtin_fmaf(es, xs[j] - xt[j], acc[0].a);
         else if constexpr (!SKEW)
           acc[1].a = __builtin_fmaf(et, xt[j] - xs[j], acc[1].a);
+        if constexpr (SKEW) {
+          cp[k][j] = es;
+          cv[k][j] = et;
+        }
         if constexpr (LSE1) {
           acc[2].z += exp2_fast(__builtin_fmaf(xs[j], kLog2e, -acc[2].r));
           if (lse1_t) acc[3].z += exp2_fast(__builtin_fmaf(xt[j], kLog2e, -acc[3].r));
@@ -355,13 +360,35 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
     if (__builtin_amdgcn_ballot_w64(odd) != 0) {  // wave-uniform
 #pragma unroll
       for (int i = 0; i < NS; ++i) acc[i].init();
+      if constexpr (SKEW) {  // the packed logits are gone: fetched again (rare; they are still in a cache)
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+          sreg[k] = ld_group<GB>(rs, voff, k, true, true);
+          treg[k] = ld_group<GB>(rt, voff, k, true, true);
+        }
+      }
 #pragma unroll
       for (int k = 0; k < K; ++k) {
         if (k < q || (k == q && tid < part)) accum8<kDense, LSE1, REV>(sreg[k], treg[k], c, lse1_t, acc);
         __builtin_amdgcn_sched_barrier(0);
       }
+      if constexpr (SKEW) {  // the exponentials again, against the references the careful form ended with
+#pragma unroll
+        for (int k = 0; k < K; ++k) {  // (every group, also those past the slice's end: all of the cache is rewritten)
+          float xs[8], xt[8];
+          unpack8(sreg[k], xs);
+          unpack8(treg[k], xt);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            cp[k][j] = exp2_fast(__builtin_fmaf(xs[j], c, -acc[0].r));
+            cv[k][j] = exp2_fast(__builtin_fmaf(xt[j], c, -acc[1].r));
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
     }
   }
+  const float r_s_thread = acc[0].r, r_t_thread = acc[1].r;  // what this thread's cached exponentials refer to
   if (last) {
     for (int e = nvec * 8 + tid; e < V; e += TH) {
       const float xs = bf16_one(srow[e]);
@@ -459,27 +486,23 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
   const bool ce = a.cscale != 0.0f;  // uniform (tau = 1 here whenever it is set)
   Sweep2Coef kf = sweep2_coef(acc[0], acc[1], c, a.gscale, a.cscale, true, true);
   SkewCoef ks;
-  // the skew forms keep p_S and p_S u of the slice as fp32 from sweep 2 on (twice the registers of the packed logits,
-  // which are dead by then -- hence the smaller K of these instances): the gradient sweep is one multiply-add each
-  float cp[SKEW ? K : 1][8], cv[SKEW ? K : 1][8];
   if constexpr (SKEW) {
     // ---- sweep 2 of the skew forms over the registers: D and ubar need the row's normalisers in every term
     ks.c = c;
-    ks.Ls = Ls;
-    ks.Lt = Lt;
+    ks.Rs = acc[0].r;
+    ks.Rt = acc[1].r;
+    ks.izs = 1.0f / acc[0].z;
+    ks.izt = 1.0f / acc[1].z;
     ks.alpha = a.alpha;
     ks.beta = 1.0f - a.alpha;
     float dsum = 0.0f, usum = 0.0f;
+    // cached exponential -> probability
+    const float fs = exp2_fast(r_s_thread - ks.Rs) * ks.izs, ft = exp2_fast(r_t_thread - ks.Rt) * ks.izt;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
       if (k < q || (k == q && tid < part)) {
-        opaque(sreg[k]);  // unpacked again, not kept from sweep 1
-        opaque(treg[k]);
-        float xs[8], xt[8];
-        unpack8(sreg[k], xs);
-        unpack8(treg[k], xt);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) skew_cache<DIVK>(xs[j], xt[j], ks, dsum, usum, cp[k][j], cv[k][j]);
+        for (int j = 0; j < 8; ++j) skew_terms<DIVK>(cp[k][j] * fs, cv[k][j] * ft, ks, dsum, usum, cp[k][j], cv[k][j]);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -515,15 +538,11 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
     const float g = a.gscale;  // (grad_scale / tau)
     if constexpr (DIVK == kSkewKl) {
       const float ubar = (a.alpha - 1.0f) * usum;
-      ks.A = (a.alpha - 1.0f) * g;
+      ks.Av = (a.alpha - 1.0f) * g;
       ks.B = a.cscale - g * ubar;
-      ks.Cl = 0.0f;
-      ks.Av = ks.A;
     } else {
       const float ubar = usum + 1.0f;
-      ks.A = -a.alpha * g;
       ks.B = __builtin_fmaf(g, 1.0f - ubar, a.cscale);
-      ks.Cl = g * kLn2;
       ks.Av = g;
     }
   }
