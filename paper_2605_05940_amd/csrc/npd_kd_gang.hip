@@ -46,11 +46,9 @@ size_t gang_workspace_bytes(int64_t T, int32_t V, int teacher_kind, int divergen
 template <class Kernel>
 static hipError_t launch_gang_kernel(const KdArgs& a, int words_per_slice, Kernel kernel, hipStream_t stream) {
   const size_t words = (size_t)a.T * a.gang * words_per_slice + kGangTailWords;
-  const int pieces = (a.nvec_s + kPieceGroups - 1) / kPieceGroups;
-  const int64_t want = a.T * pieces;
-  const int64_t fill_grid = want < 8 * (int64_t)compute_units() ? want : 8 * (int64_t)compute_units();
-  const hipError_t e = launch_kernel(gang_prepare_kernel, dim3((unsigned)fill_grid), dim3(256), 0, stream, a.ws, words, a.g,
-                                     a.mask, a.T, a.s_stride, a.nvec_s, pieces);
+  const int64_t want = (int64_t)((words + 1023) / 1024);  // four words per thread
+  const int64_t clear_grid = want < 8 * (int64_t)compute_units() ? want : 8 * (int64_t)compute_units();
+  const hipError_t e = launch_kernel(gang_clear_kernel, dim3((unsigned)clear_grid), dim3(256), 0, stream, a.ws, words);
   if (e != hipSuccess) return e;
   return launch_kernel(kernel, dim3((unsigned)(a.T * a.gang)), dim3(kGangThreads), 0, stream, a);
 }

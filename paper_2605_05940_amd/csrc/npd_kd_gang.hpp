@@ -7,11 +7,12 @@
 //   wait until all G slices of the row have posted -> merge them in one fixed tree (every workgroup of the row
 //   computes bit-identical row totals) -> gradient of the slice from the registers -> written once
 //
-// Why: the memory system of this GPU gives a mix of two reads and one write 6.3 TB/s when the chip sweeps memory
-// front to back and every row is read completely before it is written, against 5.7 TB/s when each compute unit
-// works on a row of its own.  Consecutive workgroups are consecutive slices, four workgroups run per compute unit
-// (one row's wait and arithmetic overlap three other slices' memory traffic), and masked rows are zero-filled in the
-// same address order.
+// Why: the memory system of this GPU gives a mix of two reads and one write 6.7 TB/s when the chip sweeps memory
+// front to back, every row is read completely before it is written and no cache line is shared by two workgroups,
+// against 5.7 TB/s when each compute unit works on a row of its own.  Consecutive workgroups are consecutive slices
+// (which begin on 128-byte boundaries of the row), four workgroups run per compute unit (one row's wait and arithmetic
+// overlap three other slices' memory traffic), and the workgroups of rows that are not scored zero-fill their slices
+// in the same address order.
 //
 // The exchange needs no fence: every posted word is a 32-bit atomic store that carries its own validity (the
 // scratch record is cleared to a pattern no posted word takes, by a fill kernel enqueued in front of each launch),
@@ -127,41 +128,22 @@ __device__ __forceinline__ uint32_t gang_wait(const uint32_t* p, uint32_t* aband
 // words of scratch per slice: 3 per partial log-sum-exp, rounded up to a power of two
 __host__ __device__ constexpr int gang_words(int ns) { return ns == 2 ? 8 : 16; }
 
-// Runs in front of every launch of the row-gang kernel: clears the scratch record, and zero-fills the gradient rows of
-// the positions that are not scored.  The loss kernel has 127 registers per thread, four workgroups per CU: as a
-// zero-filler it reaches 4.6 TB/s; this one -- a few registers, workgroups that walk the gradient front to back in
-// pieces of 16 KB -- writes at the rate of a plain fill (6.5 .. 6.9 TB/s), and the loss kernel's workgroups of such rows
-// end at once (1,500 workgroups per microsecond).
-constexpr int kPieceGroups = 1024;  // 128-bit groups per piece: four stores per thread
+// Runs in front of every launch of a row-gang kernel: clears the scratch record (and the words behind it) to the
+// pattern no posted word takes.
+__global__ __launch_bounds__(256) void gang_clear_kernel(uint32_t* ws, size_t words) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words; i += (size_t)gridDim.x * 256) ws[i] = kGangEmpty;
+}
 
-__global__ __launch_bounds__(256) void gang_prepare_kernel(uint32_t* ws, size_t words, uint16_t* g,
-                                                           const uint8_t* __restrict__ mask, int64_t T,
-                                                           int64_t stride, int nvec, int pieces) {
-  const int tid = threadIdx.x;
-  for (size_t i = (size_t)blockIdx.x * 256 + tid; i < words; i += (size_t)gridDim.x * 256) ws[i] = kGangEmpty;
-  // piece c = blockIdx.x + i * gridDim.x, i = 0, 1, ...: the chip walks the gradient front to back.  The mask bytes of 64
-  // pieces ahead are fetched by the 64 lanes at once, so that a workgroup does not wait for memory once per piece.
-  const uint64_t n = (uint64_t)T * (uint64_t)pieces;
+// Zero-fills the groups [g0, g0 + ng) of a gradient row, ng <= K * 256: what the workgroup of a slice does when its
+// row is not scored.  With slices that begin on 128-byte boundaries these short-lived workgroups, started in address
+// order among those of the scored rows, fill as fast as a separate fill pass (and save that pass).
+template <int K>
+__device__ __forceinline__ void gang_zero_slice(uint16_t* grow, int g0, int ng, int tid) {
   const u32x4 z = {0, 0, 0, 0};
-  const int lane = tid & 63;
-  for (uint64_t c0 = blockIdx.x; c0 < n; c0 += 64ull * gridDim.x) {
-    const uint64_t c = c0 + (uint64_t)lane * gridDim.x;
-    const uint64_t row = c / (uint64_t)pieces;
-    const bool fill = c < n && mask[row] == 0;
-    uint64_t todo = __builtin_amdgcn_ballot_w64(fill);  // the same in every wave of the workgroup
-    while (todo) {
-      const int i = __builtin_ctzll(todo);
-      todo &= todo - 1;
-      const uint64_t ci = c0 + (uint64_t)i * gridDim.x;
-      const uint64_t ri = ci / (uint64_t)pieces;
-      const int piece = (int)(ci - ri * (uint64_t)pieces);
-      u32x4* p = reinterpret_cast<u32x4*>(g + ri * stride) + (size_t)piece * kPieceGroups;
-      const int left = nvec - piece * kPieceGroups;
+  u32x4* p = reinterpret_cast<u32x4*>(grow) + g0;
 #pragma unroll
-      for (int j = 0; j < kPieceGroups / 256; ++j)
-        if (j * 256 + tid < left) p[j * 256 + tid] = z;
-    }
-  }
+  for (int k = 0; k < K; ++k)
+    if (k * kGangThreads + tid < ng) __builtin_nontemporal_store(z, p + k * kGangThreads + tid);
 }
 
 // ---- the skew divergences (three sweeps): sums and gradient on normalised log2-probabilities.
@@ -246,13 +228,14 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
   const int ng = g1 > g0 ? g1 - g0 : 0;
   uint16_t* grow = a.g + row * a.s_stride;
 
-  if (!a.mask[row]) {  // not scored: scalars 0, logits never read; gang_prepare_kernel has zero-filled the row's
-    if (slice == 0 && tid == 0) {  // 128-bit groups, the sub-group tail is left to the last slice
+  if (!a.mask[row]) {  // not scored: scalars 0, the slice of the gradient row zero-filled, logits never read
+    if (slice == 0 && tid == 0) {
       if (a.kd) a.kd[row] = 0.0f;
       if (a.nll) a.nll[row] = 0.0f;
       if (a.tnll) a.tnll[row] = 0.0f;
       if (a.lse) a.lse[row] = 0.0f;
     }
+    gang_zero_slice<K>(grow, g0, ng, tid);
     if (last)
       for (int e = nvec * 8 + tid; e < V; e += TH) grow[e] = 0;
     return;

@@ -38,12 +38,13 @@ __global__ __launch_bounds__(kGangThreads, 6) void kd_gang_topk_kernel(const KdA
   const int ng = g1 > g0 ? g1 - g0 : 0;
   uint16_t* grow = a.g + row * a.s_stride;
 
-  if (!a.mask[row]) {  // not scored: gang_prepare_kernel has zero-filled the row's 128-bit groups
+  if (!a.mask[row]) {  // not scored: scalars 0, the slice of the gradient row zero-filled, logits never read
     if (slice == 0 && tid == 0) {
       if (a.kd) a.kd[row] = 0.0f;
       if (a.nll) a.nll[row] = 0.0f;
       if (a.lse) a.lse[row] = 0.0f;
     }
+    gang_zero_slice<K>(grow, g0, ng, tid);
     if (last)
       for (int e = nvec * 8 + tid; e < V; e += TH) grow[e] = 0;
     return;
