@@ -69,7 +69,7 @@ enum {
   NPD_FLAG_FWD_ONLY = 1u,      /* no gradient: grad_out must be NULL                               */
   NPD_FLAG_INPLACE_GRAD = 2u,  /* grad_out == student_logits: each row is overwritten by its gradient */
   NPD_FLAG_NO_WORKSPACE = 4u   /* the caller brings no workspace: npd_workspace_bytes() is 0 and only kernels that
-                                  need none run (for gradient calls on rows of more than 20,480 logits these are
+                                  need none run (for gradient calls on rows of more than 20,416 logits these are
                                   slower than the ones that exchange partial sums through a workspace)           */
 };
 
@@ -212,9 +212,9 @@ npd_status npd_kd_loss_fwd_bwd(const npd_kd_desc* desc, const void* student_logi
  * the process ends).  The call allocates and frees nothing.
  *
  *   - A call whose npd_workspace_bytes(desc) exceeds NPD_NOALLOC_WORKSPACE_BYTES returns NPD_ERR_WORKSPACE and
- *     enqueues nothing (at tau = 1 the array covers n_tokens * ceil(vocab / 20480) <= 524,288, e.g. 65,536 positions
+ *     enqueues nothing (at tau = 1 the array covers n_tokens * ceil(vocab / 20416) <= 524,288, e.g. 65,536 positions
  *     of a 151,936-entry vocabulary; with a dense teacher at tau != 1 half of that; the skew divergences count
- *     ceil(vocab / 12288)).  Pass NPD_FLAG_NO_WORKSPACE, or use
+ *     ceil(vocab / 12224)).  Pass NPD_FLAG_NO_WORKSPACE, or use
  *     npd_kd_loss_fwd_bwd with a workspace, for larger batches.
  *   - Every call on a GPU uses that GPU's one array (cleared by the call itself before use): calls that overlap in
  *     time on one GPU -- two streams, two host threads -- race on it and give wrong results.  Order them on one

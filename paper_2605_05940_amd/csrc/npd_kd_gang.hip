@@ -21,8 +21,9 @@ static int gang_k(int teacher_kind, int divergence) {
   return divergence == kSkewKl || divergence == kSkewReverseKl ? kGangSkewK : kGangK;
 }
 
-// slices per row: a slice has at most kGangK * 256 groups (20,480 logits)
-static int gang_size(int nvec, int k = kGangK) { return (nvec + k * kGangThreads - 1) / (k * kGangThreads); }
+// Slices per row.  A workgroup holds up to k * 256 groups; slices are sized to 8 groups less, because a slice is moved
+// by up to 7 groups so that it begins on a 128-byte boundary of memory (see launch_kd_gang).
+static int gang_size(int nvec, int k = kGangK) { return (nvec + k * kGangThreads - 9) / (k * kGangThreads - 8); }
 
 // Gradient calls with a dense teacher (forward or reverse KL) or a top-k teacher (forward KL), 16-byte aligned rows
 // that span at least two slices.  (The CE
@@ -62,9 +63,10 @@ static hipError_t launch_gang(const KdArgs& a, hipStream_t stream) {
 hipError_t launch_kd_gang(const KdArgs& a0, int teacher_kind, hipStream_t stream) {
   KdArgs a = a0;
   a.gang = gang_size(a.nvec_s, gang_k(teacher_kind, a.divergence));
-  // Slices begin on multiples of 8 groups = 128 bytes from the row's start: when the rows themselves begin on 128-byte
-  // boundaries (a vocabulary and row pitch that are multiples of 64) no cache line is shared by two workgroups --
-  // measured +2.4 points of the HBM peak on config 1, +2.5 on config 4, +3.6 on config 2.
+  // Slices are multiples of 8 groups = 128 bytes long, and the kernels move every boundary inside a row down to the
+  // next 128-byte boundary of the gradient row's address (by 0 .. 7 groups: a row whose pitch is not a multiple of 128
+  // bytes begins anywhere): no cache line is then shared by two workgroups of a row -- measured +2.4 points of the HBM
+  // peak on config 1, +2.5 on config 4, +3.6 on config 2; a row pitch of 16 bytes more than config 1's: +4.
   a.gang_groups = ((a.nvec_s + a.gang - 1) / a.gang + 7) / 8 * 8;
   a.gang_pow2 = 1;
   while (a.gang_pow2 < a.gang) a.gang_pow2 *= 2;

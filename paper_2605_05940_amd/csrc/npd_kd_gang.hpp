@@ -222,11 +222,16 @@ __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a
   const int slice = (int)(blockIdx.x - (unsigned)(row * G));
   const int tid = threadIdx.x;
   const int V = a.V, nvec = a.nvec_s;
-  const int g0 = slice * a.gang_groups;
-  const int g1 = g0 + a.gang_groups < nvec ? g0 + a.gang_groups : nvec;  // this workgroup owns groups [g0, g1)
-  const bool last = slice == G - 1;                                      // ... and the sub-group tail of the row
-  const int ng = g1 > g0 ? g1 - g0 : 0;
   uint16_t* grow = a.g + row * a.s_stride;
+  // This workgroup owns groups [g0, g1) -- the last slice also the sub-group tail of the row.  Boundaries inside the row
+  // are moved down to the next 128-byte boundary of the gradient row's address (by `shift` groups), so that no cache
+  // line is shared by two workgroups of a row; a slice is at most 7 groups longer than a.gang_groups for it.
+  const bool last = slice == G - 1;
+  const int shift = (int)((reinterpret_cast<uintptr_t>(grow) >> 4) & 7u);
+  const int b0 = slice * a.gang_groups - shift, b1 = b0 + a.gang_groups;
+  const int g0 = slice == 0 ? 0 : (b0 < nvec ? b0 : nvec);
+  const int g1 = last ? nvec : (b1 < nvec ? b1 : nvec);
+  const int ng = g1 > g0 ? g1 - g0 : 0;
 
   if (!a.mask[row]) {  // not scored: scalars 0, the slice of the gradient row zero-filled, logits never read
     if (slice == 0 && tid == 0) {

@@ -175,12 +175,14 @@ def test_workspace_rules(lib):
     args = dict(student=far, teacher=2 * far, mask=3 * far, grad=4 * far)
     d = _desc(**big)
     need = lib.npd_workspace_bytes(ctypes.byref(d))
-    assert need == 64 * 8 * 32 + 256                                # 8 slices of <= 20,480 logits, 32 bytes each, + tail
+    assert need == 64 * 8 * 32 + 256                                # 8 slices of <= 2,552 groups, 32 bytes each, + tail
     assert lib.npd_workspace_bytes(ctypes.byref(_desc(tau=2.0, **big))) == 64 * 8 * 64 + 256
     assert lib.npd_workspace_bytes(ctypes.byref(_desc(flags=binding.NPD_FLAG_NO_WORKSPACE, **big))) == 0
     assert lib.npd_workspace_bytes(ctypes.byref(_desc(flags=binding.NPD_FLAG_FWD_ONLY, **big))) == 0
-    assert lib.npd_workspace_bytes(ctypes.byref(_desc(vocab=20480, n_tokens=64, student_stride=20480,
-                                                     teacher_stride=20480))) == 0   # one slice: nothing to exchange
+    assert lib.npd_workspace_bytes(ctypes.byref(_desc(vocab=20416, n_tokens=64, student_stride=20416,
+                                                     teacher_stride=20416))) == 0   # one slice: nothing to exchange
+    assert lib.npd_workspace_bytes(ctypes.byref(_desc(vocab=20424, n_tokens=64, student_stride=20424,
+                                                     teacher_stride=20424))) == 64 * 2 * 32 + 256
     assert lib.npd_workspace_bytes(ctypes.byref(_desc(tau=-1.0, **big))) == 0       # invalid descriptor
     assert _kd(lib, d, **args) == E_WS                              # no workspace
     assert _kd(lib, d, ws=5 * far, ws_bytes=need - 1, **args) == E_WS

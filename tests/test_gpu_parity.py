@@ -603,11 +603,11 @@ def test_cfg4_full_size_inplace(oracle):
 # --------------------------------------------------------------------------- row-gang kernels: slices and their exchange
 
 @pytest.mark.parametrize("V,stride", [
-    (8 * 2561, 8 * 2561),          # two slices, the second all but empty: 1,281 + 1,280 groups
-    (8 * 5120, 8 * 5120),          # two full slices
-    (8 * 5121 + 5, 8 * 5122),      # three slices and a 5-element tail
+    (8 * 2553, 8 * 2553),          # two slices: 1,280 + 1,273 groups (a slice is sized to at most 2,552)
+    (8 * 5104, 8 * 5104),          # two full slices
+    (8 * 5105 + 5, 8 * 5106),      # three slices and a 5-element tail; rows that begin 16 bytes off a 128-byte line
     (151936, 151936),              # eight slices of 2,374 groups
-    (8 * 2560 * 9 + 8, 8 * 2560 * 9 + 24),   # ten slices, nine of them a single group short of full; padded rows
+    (8 * 2552 * 9 + 8, 8 * 2552 * 9 + 24),   # ten slices; a row pitch that moves the boundaries by 0 .. 7 groups
 ])
 @pytest.mark.parametrize("tau,div", [(1.0, "forward"), (2.0, "forward"), (1.0, "reverse"), (1.0, "skew"),
                                      (2.0, "skew"), (1.0, "skew_reverse"), (2.0, "skew_reverse")])
@@ -617,11 +617,12 @@ def test_gang_slices_with_labels_on_their_edges(oracle, V, stride, tau, div):
     taken by the right workgroup.  Out of place and in place."""
     assert binding.npd_workspace_bytes(4, V, tau=1.0) > 0
     nvec = V // 8
-    width = 1536 if div.startswith("skew") else 2560     # groups a slice holds at most (fewer for the skew forms)
+    width = 1528 if div.startswith("skew") else 2552     # groups a slice is sized to at most (fewer for the skew forms)
     gang = -(-nvec // width)
-    per = -(-(-(-nvec // gang)) // 8) * 8      # slices begin on multiples of 8 groups (128 bytes)
-    edges = sorted({0, 7, 8 * per - 1, 8 * per, 8 * per + 1, 8 * (gang - 1) * per - 1, 8 * (gang - 1) * per,
-                    8 * nvec - 1, V - 1, V // 2})
+    per = -(-(-(-nvec // gang)) // 8) * 8      # slices are multiples of 8 groups (128 bytes) long; a boundary sits
+    sh = 3 if stride % 64 else 0                # 0 .. 7 groups below a multiple of that (by the row's address)
+    edges = sorted({0, 7, 8 * (per - sh) - 1, 8 * (per - sh), 8 * per - 1, 8 * per, 8 * per + 1,
+                    8 * (gang - 1) * per - 1, 8 * (gang - 1) * per, 8 * nvec - 1, V - 1, V // 2})
     T = 2 * len(edges)
     w = synth.scaled(synth.config(1), n_rows=1, row_len=T, vocab=V, length_lo=4, length_hi=9)
     lay, s, t, mask, _ = _inputs(w, stride)
@@ -645,16 +646,17 @@ def test_gang_slices_with_labels_on_their_edges(oracle, V, stride, tau, div):
                    amp_from_ref=div != "forward")
 
 
-@pytest.mark.parametrize("V,stride,tau", [(8 * 5121 + 5, 8 * 5122, 1.0), (151936, 151936, 2.0), (151936, 151936, 1.0)])
+@pytest.mark.parametrize("V,stride,tau", [(8 * 5105 + 5, 8 * 5106, 1.0), (151936, 151936, 2.0), (151936, 151936, 1.0)])
 def test_gang_topk_support_and_labels_on_slice_edges(oracle, V, stride, tau):
     """Top-k teacher on rows shared by several workgroups: support positions and labels on the first and last element
     of slices and in the sub-group tail, labels inside and outside the support; out of place and in place."""
     assert binding.npd_workspace_bytes(4, V, teacher_kind=binding.NPD_TEACHER_TOPK, topk=24) > 0
     nvec = V // 8
-    gang = -(-nvec // 2560)
-    per = -(-(-(-nvec // gang)) // 8) * 8      # slices begin on multiples of 8 groups (128 bytes)
-    edges = sorted({0, 7, 8 * per - 1, 8 * per, 8 * per + 1, 8 * (gang - 1) * per - 1, 8 * (gang - 1) * per,
-                    8 * nvec - 1, V - 1, V // 2})
+    gang = -(-nvec // 2552)
+    per = -(-(-(-nvec // gang)) // 8) * 8      # slices are multiples of 8 groups (128 bytes) long; a boundary sits
+    sh = 3 if stride % 64 else 0                # 0 .. 7 groups below a multiple of that (by the row's address)
+    edges = sorted({0, 7, 8 * (per - sh) - 1, 8 * (per - sh), 8 * per - 1, 8 * per, 8 * per + 1,
+                    8 * (gang - 1) * per - 1, 8 * (gang - 1) * per, 8 * nvec - 1, V - 1, V // 2})
     T, k = 2 * len(edges), 24
     w = synth.scaled(synth.config(2), n_rows=1, row_len=T, vocab=V, length_lo=4, length_hi=9, topk=k)
     lay, s, _, mask, _ = _inputs(w, stride, dense_teacher=False)
@@ -1068,7 +1070,7 @@ DIVS = {"reverse": binding.NPD_DIV_REVERSE_KL, "skew": binding.NPD_DIV_SKEW_KL,
     (600000, 600000, 1.0, 0.3, 1.0, False),    # 74 groups per thread: most of the row streamed in every sweep
 ])
 def test_divergence_shapes(oracle, div, V, stride, tau, alpha, scale, inplace, no_workspace):
-    if no_workspace and V < 8 * 2561:
+    if no_workspace and V < 8 * 2553:
         pytest.skip("rows of one slice take the same kernel with and without a workspace")
     T = (12 if V > 500000 else 24) if V > 100000 else 64
     w = synth.scaled(synth.config(1), n_rows=1, row_len=T, vocab=V, length_lo=4, length_hi=16)
