@@ -199,7 +199,7 @@ __device__ __forceinline__ float skew_grad(float xs, float xt, const SkewCoef& k
   return __builtin_fmaf(v, k.Av, k.B * p);
 }
 
-// K: groups per thread and tensor a slice may have (the slice of a launch has a.gang_groups <= K * 256 groups).
+// K: groups per thread and tensor a workgroup holds (a slice has at most a.gang_groups + 7 <= K * 256 - 1 groups).
 template <int K, int TEACHER, bool LSE1, int DIVK = kForwardKl>
 __global__ __launch_bounds__(kGangThreads, 4) void kd_gang_kernel(const KdArgs a) {
   static_assert(TEACHER == kDense, "dense teacher");
