@@ -69,7 +69,7 @@ enum {
   NPD_FLAG_FWD_ONLY = 1u,      /* no gradient: grad_out must be NULL                               */
   NPD_FLAG_INPLACE_GRAD = 2u,  /* grad_out == student_logits: each row is overwritten by its gradient */
   NPD_FLAG_NO_WORKSPACE = 4u   /* the caller brings no workspace: npd_workspace_bytes() is 0 and only kernels that
-                                  need none run (for gradient calls on rows of more than 20,416 logits these are
+                                  need none run (for gradient calls on rows of 30,624 logits and more these are
                                   slower than the ones that exchange partial sums through a workspace)           */
 };
 

@@ -23,7 +23,13 @@ static int gang_k(int teacher_kind, int divergence) {
 
 // Slices per row.  A workgroup holds up to k * 256 groups; slices are sized to 8 groups less, because a slice is moved
 // by up to 7 groups so that it begins on a 128-byte boundary of memory (see launch_kd_gang).
-static int gang_size(int nvec, int k = kGangK) { return (nvec + k * kGangThreads - 9) / (k * kGangThreads - 8); }
+// Rows of less than one and a half slices stay with one workgroup per row (1 is returned): two half-filled slices
+// cost more in exchanges than the access order gains (dense teacher, % of the HBM peak, row gangs / one workgroup per
+// row: V = 20,480 50 / 72, 24,576 67 / 74, 32,000 73 / 69, 50,304 77 / 69, 100,352 81 / 67).
+static int gang_size(int nvec, int k = kGangK) {
+  const int cap = k * kGangThreads - 8;
+  return 2 * nvec < 3 * cap ? 1 : (nvec + cap - 1) / cap;
+}
 
 // Gradient calls with a dense teacher (forward or reverse KL) or a top-k teacher (forward KL), 16-byte aligned rows
 // that span at least two slices.  (The CE

@@ -181,8 +181,10 @@ def test_workspace_rules(lib):
     assert lib.npd_workspace_bytes(ctypes.byref(_desc(flags=binding.NPD_FLAG_FWD_ONLY, **big))) == 0
     assert lib.npd_workspace_bytes(ctypes.byref(_desc(vocab=20416, n_tokens=64, student_stride=20416,
                                                      teacher_stride=20416))) == 0   # one slice: nothing to exchange
-    assert lib.npd_workspace_bytes(ctypes.byref(_desc(vocab=20424, n_tokens=64, student_stride=20424,
-                                                     teacher_stride=20424))) == 64 * 2 * 32 + 256
+    assert lib.npd_workspace_bytes(ctypes.byref(_desc(vocab=30616, n_tokens=64, student_stride=30616,
+                                                     teacher_stride=30616))) == 0   # less than one and a half slices
+    assert lib.npd_workspace_bytes(ctypes.byref(_desc(vocab=30624, n_tokens=64, student_stride=30624,
+                                                     teacher_stride=30624))) == 64 * 2 * 32 + 256
     assert lib.npd_workspace_bytes(ctypes.byref(_desc(tau=-1.0, **big))) == 0       # invalid descriptor
     assert _kd(lib, d, **args) == E_WS                              # no workspace
     assert _kd(lib, d, ws=5 * far, ws_bytes=need - 1, **args) == E_WS

@@ -603,7 +603,7 @@ def test_cfg4_full_size_inplace(oracle):
 # --------------------------------------------------------------------------- row-gang kernels: slices and their exchange
 
 @pytest.mark.parametrize("V,stride", [
-    (8 * 2553, 8 * 2553),          # two slices: 1,280 + 1,273 groups (a slice is sized to at most 2,552)
+    (8 * 3828, 8 * 3828),          # the shortest rows that are shared: two slices of 1,920 + 1,908 groups
     (8 * 5104, 8 * 5104),          # two full slices
     (8 * 5105 + 5, 8 * 5106),      # three slices and a 5-element tail; rows that begin 16 bytes off a 128-byte line
     (151936, 151936),              # eight slices of 2,374 groups
@@ -1070,7 +1070,7 @@ DIVS = {"reverse": binding.NPD_DIV_REVERSE_KL, "skew": binding.NPD_DIV_SKEW_KL,
     (600000, 600000, 1.0, 0.3, 1.0, False),    # 74 groups per thread: most of the row streamed in every sweep
 ])
 def test_divergence_shapes(oracle, div, V, stride, tau, alpha, scale, inplace, no_workspace):
-    if no_workspace and V < 8 * 2553:
+    if no_workspace and V < 8 * 2292:
         pytest.skip("rows of one slice take the same kernel with and without a workspace")
     T = (12 if V > 500000 else 24) if V > 100000 else 64
     w = synth.scaled(synth.config(1), n_rows=1, row_len=T, vocab=V, length_lo=4, length_hi=16)
