@@ -241,7 +241,7 @@ npd_status check_kd_call(const npd_kd_desc* desc, const void* student_logits, co
 
 extern "C" {
 
-int npd_version(void) { return 115; }
+int npd_version(void) { return 116; }
 
 const char* npd_status_string(npd_status st) {
   switch (st) {

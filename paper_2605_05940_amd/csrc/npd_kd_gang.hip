@@ -26,9 +26,15 @@ static int gang_k(int teacher_kind, int divergence) {
 // Rows of less than one and a half slices stay with one workgroup per row (1 is returned): two half-filled slices
 // cost more in exchanges than the access order gains (dense teacher, % of the HBM peak, row gangs / one workgroup per
 // row: V = 20,480 50 / 72, 24,576 67 / 74, 32,000 73 / 69, 50,304 77 / 69, 100,352 81 / 67).
-static int gang_size(int nvec, int k = kGangK) {
+// `on_lines`: every row of the launch begins on a 128-byte boundary, no boundary is ever moved and a slice may be as
+// long as a workgroup holds (V = 102,400: 5 full slices instead of 6).
+static int gang_size(int nvec, int k, bool on_lines) {
   const int cap = k * kGangThreads - 8;
-  return 2 * nvec < 3 * cap ? 1 : (nvec + cap - 1) / cap;
+  if (2 * nvec < 3 * cap) return 1;
+  return on_lines ? (nvec + cap + 7) / (cap + 8) : (nvec + cap - 1) / cap;
+}
+static bool rows_on_lines(const KdArgs& a) {
+  return a.g != nullptr && (reinterpret_cast<uintptr_t>(a.g) & 127u) == 0 && a.s_stride % 64 == 0;
 }
 
 // Gradient calls with a dense teacher (forward or reverse KL) or a top-k teacher (forward KL), 16-byte aligned rows
@@ -39,14 +45,15 @@ bool gang_path_applies(const KdArgs& a, int teacher_kind, bool want_grad) {
   if ((teacher_kind != kDense && teacher_kind != kTopk) || !want_grad) return false;
   if (a.divergence != kForwardKl && teacher_kind != kDense) return false;
   if (a.cscale != 0.0f && a.need_lse1) return false;
-  const int g = gang_size(a.nvec_s, gang_k(teacher_kind, a.divergence));
+  const int g = gang_size(a.nvec_s, gang_k(teacher_kind, a.divergence), rows_on_lines(a));
   if (g < 2 || g > kGangMax) return false;
   return a.T * (int64_t)g <= 0x7fffffffLL;  // one workgroup per slice, 1-D grid
 }
 
 size_t gang_workspace_bytes(int64_t T, int32_t V, int teacher_kind, int divergence, bool lse1) {
-  const int g = gang_size(V / 8, gang_k(teacher_kind, divergence));
-  if (g < 2 || g > kGangMax || T * (int64_t)g > 0x7fffffffLL) return 0;
+  const int g = gang_size(V / 8, gang_k(teacher_kind, divergence), false);  // (the larger of the two counts)
+  if (g < 2 || T * (int64_t)g > 0x7fffffffLL) return 0;
+  if (g > kGangMax && gang_size(V / 8, gang_k(teacher_kind, divergence), true) > kGangMax) return 0;
   return ((size_t)T * g * gang_words(lse1 ? 4 : 2) + kGangTailWords) * sizeof(uint32_t);
 }
 
@@ -68,7 +75,7 @@ static hipError_t launch_gang(const KdArgs& a, hipStream_t stream) {
 
 hipError_t launch_kd_gang(const KdArgs& a0, int teacher_kind, hipStream_t stream) {
   KdArgs a = a0;
-  a.gang = gang_size(a.nvec_s, gang_k(teacher_kind, a.divergence));
+  a.gang = gang_size(a.nvec_s, gang_k(teacher_kind, a.divergence), rows_on_lines(a));
   // Slices are multiples of 8 groups = 128 bytes long, and the kernels move every boundary inside a row down to the
   // next 128-byte boundary of the gradient row's address (by 0 .. 7 groups: a row whose pitch is not a multiple of 128
   // bytes begins anywhere): no cache line is then shared by two workgroups of a row -- measured +2.4 points of the HBM
